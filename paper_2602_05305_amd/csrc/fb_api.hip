@@ -1,0 +1,321 @@
+// C-ABI layer of libflashblock.so: argument validation (host only, no GPU touched), split
+// heuristics, workspace carving and kernel dispatch.  Contract: include/flashblock.h.
+#include <math.h>
+#include <string.h>
+
+#include <string>
+
+#include "../../include/flashblock.h"
+#include "fb_kernels.h"
+
+namespace {
+
+thread_local std::string g_last_hip_error;
+
+constexpr int kMaxKeyBlocks = 16384;   // LDS-resident per-KV-group block tables in the sparse helpers
+constexpr float kLog2e = 1.4426950408889634f;
+
+fb_status hip_fail(hipError_t e) {
+  g_last_hip_error = hipGetErrorString(e);
+  return FB_ERR_HIP;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+fb_status check_shape(const fb_shape* s) {
+  if (s == nullptr) return FB_ERR_NULL;
+  if (s->struct_size != sizeof(fb_shape)) return FB_ERR_SHAPE;
+  if (s->dtype != FB_F32 && s->dtype != FB_BF16) return FB_ERR_DTYPE;
+  if (s->batch < 1 || s->n_q_heads < 1 || s->n_kv_heads < 1 || s->block_len < 1 || s->prefix_len < 0)
+    return FB_ERR_SHAPE;
+  if (s->n_q_heads % s->n_kv_heads != 0) return FB_ERR_SHAPE;
+  if (s->n_q_heads / s->n_kv_heads > 32) return FB_ERR_SHAPE;
+  if (!(s->scale >= 0.f) || isinf(s->scale)) return FB_ERR_SHAPE;   // rejects NaN and negatives
+  if (s->head_dim < 1) return FB_ERR_SHAPE;
+  if (s->head_dim != 64 && s->head_dim != 128) return FB_ERR_UNSUPPORTED;
+  if ((long long)s->batch * s->n_q_heads > 65535) return FB_ERR_UNSUPPORTED;   // grid.y of the fp32 pass
+  const long long rows = (long long)s->batch * s->n_q_heads * s->block_len;
+  if (rows > (1ll << 28)) return FB_ERR_UNSUPPORTED;
+  return FB_OK;
+}
+
+float eff_scale(const fb_shape* s) { return s->scale > 0.f ? s->scale : 1.0f / sqrtf((float)s->head_dim); }
+
+long long rows_of(const fb_shape* s) { return (long long)s->batch * s->n_q_heads * s->block_len; }
+
+int auto_splits(const fb_shape* s) {
+  const int tiles = (s->prefix_len + fb::kKeyTile - 1) / fb::kKeyTile;
+  long long groups, target;
+  int min_tiles;
+  if (s->dtype == FB_BF16) {
+    const int G = s->n_q_heads / s->n_kv_heads;
+    groups = (long long)s->batch * s->n_kv_heads * ((G * s->block_len + fb::kRowsPerWgBf16 - 1) / fb::kRowsPerWgBf16);
+    target = 512;    // two 4-wave workgroups per CU on 256 CUs
+    min_tiles = 4;
+  } else {
+    groups = (long long)s->batch * s->n_q_heads * ((s->block_len + fb::kRowsPerWgF32 - 1) / fb::kRowsPerWgF32);
+    target = 1024;
+    min_tiles = 1;
+  }
+  long long ns = (target + groups - 1) / groups;
+  const long long cap = tiles / min_tiles;
+  if (ns > cap) ns = cap;
+  if (ns > FB_MAX_SPLITS) ns = FB_MAX_SPLITS;
+  if (ns < 1) ns = 1;
+  return (int)ns;
+}
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct WsLayout {
+  size_t o[2], m[2], l[2], mask, ulist, ucnt, total;
+};
+
+WsLayout ws_layout(const fb_shape* s, int nsplit, int nsets, int nblk) {
+  WsLayout w;
+  const size_t rows = (size_t)rows_of(s);
+  size_t off = 0;
+  for (int i = 0; i < 2; ++i) {
+    const size_t n = (i < nsets) ? (size_t)nsplit * rows : 0;
+    w.o[i] = off; off = align256(off + n * s->head_dim * sizeof(float));
+    w.m[i] = off; off = align256(off + n * sizeof(float));
+    w.l[i] = off; off = align256(off + n * sizeof(float));
+  }
+  const size_t nb = (size_t)s->batch * s->n_kv_heads * nblk;
+  w.mask = off;  off = align256(off + nb * sizeof(uint32_t));
+  w.ulist = off; off = align256(off + nb * sizeof(int32_t));
+  w.ucnt = off;  off = align256(off + (nblk > 0 ? (size_t)s->batch * s->n_kv_heads * sizeof(int32_t) : 0));
+  w.total = off;
+  return w;
+}
+
+fb_status check_key_block(const fb_shape* s, int32_t key_block, int32_t topk, int* nblk) {
+  if (key_block <= 0 || topk < 0) return FB_ERR_SHAPE;
+  if (key_block % fb::kKeyTile != 0) return FB_ERR_UNSUPPORTED;
+  const long long nb = ((long long)s->prefix_len + key_block - 1) / key_block;
+  if (nb > kMaxKeyBlocks) return FB_ERR_UNSUPPORTED;
+  *nblk = (int)nb;
+  return FB_OK;
+}
+
+fb::PassParams base_pass(const fb_shape* s, const void* q, const void* k, const void* v, int nkeys, int nsplit) {
+  fb::PassParams p;
+  memset(&p, 0, sizeof(p));
+  p.q = q; p.k = k; p.v = v;
+  p.B = s->batch; p.Hq = s->n_q_heads; p.Hkv = s->n_kv_heads; p.G = s->n_q_heads / s->n_kv_heads;
+  p.Bq = s->block_len; p.nkeys = nkeys; p.nsplit = nsplit;
+  p.scale_log2 = eff_scale(s) * kLog2e;
+  p.key_block = fb::kKeyTile;
+  return p;
+}
+
+hipError_t launch_attn(const fb_shape* s, const fb::PassParams& p, fb::PassMode mode, hipStream_t st) {
+  return s->dtype == FB_BF16 ? fb::launch_attn_bf16(p, s->head_dim, mode, st)
+                             : fb::launch_attn_f32(p, s->head_dim, mode, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+int fb_version(void) { return FB_VERSION; }
+
+const char* fb_status_string(int status) {
+  switch (status) {
+    case FB_OK: return "FB_OK";
+    case FB_ERR_NULL: return "FB_ERR_NULL: required pointer is NULL";
+    case FB_ERR_SHAPE: return "FB_ERR_SHAPE: dimension, head grouping, scale or mode out of range";
+    case FB_ERR_DTYPE: return "FB_ERR_DTYPE: dtype is not FB_F32 / FB_BF16";
+    case FB_ERR_ALIGN: return "FB_ERR_ALIGN: tensor pointer not 16-byte aligned";
+    case FB_ERR_WORKSPACE: return "FB_ERR_WORKSPACE: workspace NULL or too small";
+    case FB_ERR_UNSUPPORTED: return "FB_ERR_UNSUPPORTED: request outside what the kernels cover";
+    case FB_ERR_HIP: return "FB_ERR_HIP: HIP launch failed";
+    default: return "unknown fb_status";
+  }
+}
+
+const char* fb_last_hip_error(void) { return g_last_hip_error.c_str(); }
+
+fb_status fb_check_shape(const fb_shape* shape) { return check_shape(shape); }
+
+int32_t fb_external_splits(const fb_shape* shape) {
+  if (check_shape(shape) != FB_OK) return 0;
+  return auto_splits(shape);
+}
+
+size_t fb_workspace_bytes(const fb_shape* shape, int32_t key_block, int32_t topk, int32_t n_splits) {
+  if (check_shape(shape) != FB_OK) return 0;
+  if (n_splits < 0 || n_splits > FB_MAX_SPLITS) return 0;
+  const int ns = n_splits > 0 ? n_splits : auto_splits(shape);
+  int nblk = 0, nsets = 1;
+  if (key_block != 0) {
+    if (check_key_block(shape, key_block, topk, &nblk) != FB_OK) return 0;
+    nsets = 2;
+  }
+  const size_t t = ws_layout(shape, ns, nsets, nblk).total;
+  return t > 0 ? t : 256;
+}
+
+fb_status fb_external_partial_ex(const fb_shape* shape, const void* q, const void* k_prefix,
+                                 const void* v_prefix, float* o_part, float* m_part, float* lse_part,
+                                 int32_t n_splits, void* workspace, size_t workspace_bytes,
+                                 void* hip_stream) {
+  fb_status st = check_shape(shape);
+  if (st != FB_OK) return st;
+  if (!q || !o_part || !m_part || !lse_part) return FB_ERR_NULL;
+  if (shape->prefix_len > 0 && (!k_prefix || !v_prefix)) return FB_ERR_NULL;
+  if (n_splits < 0 || n_splits > FB_MAX_SPLITS) return FB_ERR_SHAPE;
+  if (!aligned16(q) || !aligned16(k_prefix) || !aligned16(v_prefix) || !aligned16(o_part) ||
+      !aligned16(m_part) || !aligned16(lse_part) || !aligned16(workspace))
+    return FB_ERR_ALIGN;
+  const int ns = n_splits > 0 ? n_splits : auto_splits(shape);
+  const WsLayout w = ws_layout(shape, ns, 1, 0);
+  if (!workspace || workspace_bytes < w.total) return FB_ERR_WORKSPACE;
+
+  hipStream_t stream = (hipStream_t)hip_stream;
+  char* ws = (char*)workspace;
+  fb::PassParams p = base_pass(shape, q, k_prefix, v_prefix, shape->prefix_len, ns);
+  p.ws_o = (float*)(ws + w.o[0]); p.ws_m = (float*)(ws + w.m[0]); p.ws_l = (float*)(ws + w.l[0]);
+  hipError_t e = launch_attn(shape, p, fb::kPassDense, stream);
+  if (e != hipSuccess) return hip_fail(e);
+
+  fb::CombineParams c;
+  memset(&c, 0, sizeof(c));
+  c.rows = (int)rows_of(shape); c.D = shape->head_dim; c.nsplit = ns;
+  c.ws_o = p.ws_o; c.ws_m = p.ws_m; c.ws_l = p.ws_l;
+  c.o = o_part; c.m = m_part; c.lse = lse_part;
+  e = fb::launch_combine(c, stream);
+  if (e != hipSuccess) return hip_fail(e);
+  return FB_OK;
+}
+
+fb_status fb_external_partial(const fb_shape* shape, const void* q, const void* k_prefix,
+                              const void* v_prefix, float* o_part, float* m_part, float* lse_part,
+                              void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return fb_external_partial_ex(shape, q, k_prefix, v_prefix, o_part, m_part, lse_part, 0, workspace,
+                                workspace_bytes, hip_stream);
+}
+
+fb_status fb_internal_merge(const fb_shape* shape, const void* q, const void* k_block,
+                            const void* v_block, const float* o_part, const float* m_part,
+                            const float* lse_part, void* out, float* lse_out, void* hip_stream) {
+  fb_status st = check_shape(shape);
+  if (st != FB_OK) return st;
+  if (!q || !k_block || !v_block || !out) return FB_ERR_NULL;
+  const int n_ext = (o_part != nullptr) + (m_part != nullptr) + (lse_part != nullptr);
+  if (n_ext != 0 && n_ext != 3) return FB_ERR_NULL;   // all three or none
+  if (!aligned16(q) || !aligned16(k_block) || !aligned16(v_block) || !aligned16(o_part) ||
+      !aligned16(m_part) || !aligned16(lse_part) || !aligned16(out) || !aligned16(lse_out))
+    return FB_ERR_ALIGN;
+  fb::PassParams p = base_pass(shape, q, k_block, v_block, shape->block_len, 1);
+  p.ext_o = o_part; p.ext_m = m_part; p.ext_lse = lse_part;
+  p.out = out; p.lse_out = lse_out;
+  hipError_t e = launch_attn(shape, p, fb::kPassInternal, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return hip_fail(e);
+  return FB_OK;
+}
+
+fb_status fb_pool_keys(const fb_shape* shape, const void* k_prefix, int32_t key_block, float* k_pooled,
+                       void* hip_stream) {
+  fb_status st = check_shape(shape);
+  if (st != FB_OK) return st;
+  int nblk = 0;
+  st = check_key_block(shape, key_block, 0, &nblk);
+  if (st != FB_OK) return st;
+  if (shape->prefix_len > 0 && (!k_prefix || !k_pooled)) return FB_ERR_NULL;
+  if (!aligned16(k_prefix) || !aligned16(k_pooled)) return FB_ERR_ALIGN;
+  fb::PoolParams p;
+  p.k = k_prefix; p.k_pooled = k_pooled;
+  p.BH = shape->batch * shape->n_kv_heads; p.nkeys = shape->prefix_len; p.D = shape->head_dim;
+  p.key_block = key_block; p.nblk = nblk; p.is_bf16 = shape->dtype == FB_BF16;
+  hipError_t e = fb::launch_pool_keys(p, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return hip_fail(e);
+  return FB_OK;
+}
+
+fb_status fb_select_topk(const fb_shape* shape, const void* q, const float* k_pooled, int32_t key_block,
+                         int32_t topk, int32_t* sel_idx, void* hip_stream) {
+  fb_status st = check_shape(shape);
+  if (st != FB_OK) return st;
+  int nblk = 0;
+  st = check_key_block(shape, key_block, topk, &nblk);
+  if (st != FB_OK) return st;
+  if (topk == 0) return FB_OK;
+  if (!q || !sel_idx || (nblk > 0 && !k_pooled)) return FB_ERR_NULL;
+  if (!aligned16(q) || !aligned16(k_pooled) || !aligned16(sel_idx)) return FB_ERR_ALIGN;
+  fb::SelectParams p;
+  p.q = q; p.k_pooled = k_pooled; p.sel_idx = sel_idx;
+  p.B = shape->batch; p.Hq = shape->n_q_heads; p.Hkv = shape->n_kv_heads;
+  p.G = shape->n_q_heads / shape->n_kv_heads; p.Bq = shape->block_len; p.D = shape->head_dim;
+  p.nblk = nblk; p.topk = topk; p.is_bf16 = shape->dtype == FB_BF16;
+  hipError_t e = fb::launch_select_topk(p, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return hip_fail(e);
+  return FB_OK;
+}
+
+fb_status fb_sparse_external_residual(const fb_shape* shape, int32_t mode, const void* q,
+                                      const void* k_prefix, const void* v_prefix, int32_t key_block,
+                                      int32_t topk, const int32_t* sel_idx, float* res_o, float* res_m,
+                                      float* res_lse, float* o_part, float* m_part, float* lse_part,
+                                      void* workspace, size_t workspace_bytes, void* hip_stream) {
+  fb_status st = check_shape(shape);
+  if (st != FB_OK) return st;
+  if (mode != FB_SPARSE_REFRESH && mode != FB_SPARSE_REUSE) return FB_ERR_SHAPE;
+  int nblk = 0;
+  st = check_key_block(shape, key_block, topk, &nblk);
+  if (st != FB_OK) return st;
+  if (!q || !res_o || !res_m || !res_lse || !o_part || !m_part || !lse_part) return FB_ERR_NULL;
+  if (shape->prefix_len > 0 && (!k_prefix || !v_prefix)) return FB_ERR_NULL;
+  if (topk > 0 && !sel_idx) return FB_ERR_NULL;
+  if (!aligned16(q) || !aligned16(k_prefix) || !aligned16(v_prefix) || !aligned16(sel_idx) ||
+      !aligned16(res_o) || !aligned16(res_m) || !aligned16(res_lse) || !aligned16(o_part) ||
+      !aligned16(m_part) || !aligned16(lse_part) || !aligned16(workspace))
+    return FB_ERR_ALIGN;
+  const int ns = auto_splits(shape);
+  const WsLayout w = ws_layout(shape, ns, 2, nblk);
+  if (!workspace || workspace_bytes < w.total) return FB_ERR_WORKSPACE;
+
+  hipStream_t stream = (hipStream_t)hip_stream;
+  char* ws = (char*)workspace;
+
+  fb::MaskParams mp;
+  mp.sel_idx = topk > 0 ? sel_idx : nullptr;
+  mp.blk_mask = (uint32_t*)(ws + w.mask); mp.union_list = (int32_t*)(ws + w.ulist);
+  mp.union_cnt = (int32_t*)(ws + w.ucnt);
+  mp.B = shape->batch; mp.Hq = shape->n_q_heads; mp.Hkv = shape->n_kv_heads;
+  mp.G = shape->n_q_heads / shape->n_kv_heads; mp.topk = topk; mp.nblk = nblk;
+  hipError_t e = hipSuccess;
+  if (nblk > 0) {
+    e = fb::launch_build_masks(mp, stream);
+    if (e != hipSuccess) return hip_fail(e);
+  }
+
+  fb::PassParams p = base_pass(shape, q, k_prefix, v_prefix, shape->prefix_len, ns);
+  p.ws_o = (float*)(ws + w.o[0]); p.ws_m = (float*)(ws + w.m[0]); p.ws_l = (float*)(ws + w.l[0]);
+  p.ws_o2 = (float*)(ws + w.o[1]); p.ws_m2 = (float*)(ws + w.m[1]); p.ws_l2 = (float*)(ws + w.l[1]);
+  p.blk_mask = mp.blk_mask; p.union_list = mp.union_list; p.union_cnt = mp.union_cnt;
+  p.key_block = key_block; p.nblk = nblk;
+
+  fb::CombineParams c;
+  memset(&c, 0, sizeof(c));
+  c.rows = (int)rows_of(shape); c.D = shape->head_dim; c.nsplit = ns;
+  c.o = o_part; c.m = m_part; c.lse = lse_part;
+  if (nblk > 0) {
+    c.ws_o = p.ws_o; c.ws_m = p.ws_m; c.ws_l = p.ws_l;
+    e = launch_attn(shape, p, mode == FB_SPARSE_REFRESH ? fb::kPassSparseRefresh : fb::kPassSparseReuse, stream);
+    if (e != hipSuccess) return hip_fail(e);
+  } else {
+    c.nsplit = 0;   // empty prefix: nothing selected, nothing residual
+  }
+  if (mode == FB_SPARSE_REFRESH) {
+    if (nblk > 0) { c.ws_o2 = p.ws_o2; c.ws_m2 = p.ws_m2; c.ws_l2 = p.ws_l2; }
+    c.res_out_o = res_o; c.res_out_m = res_m; c.res_out_lse = res_lse;
+  } else {
+    c.res_in_o = res_o; c.res_in_m = res_m; c.res_in_lse = res_lse;
+  }
+  e = fb::launch_combine(c, stream);
+  if (e != hipSuccess) return hip_fail(e);
+  return FB_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,429 @@
+// bf16 attention pass for gfx950 (MI355X): MFMA 32x32x16 tiles, fp32 statistics.
+//
+// Computes the per-row statistics of Eq. 3-4/6 (arxiv 2602.05305, Section 4.2) of a block of
+// query rows against a stream of keys, and either stores split partials (external passes) or
+// finishes with the log-space composition of Eq. 8-9 against a cached partial (internal pass).
+//
+// Work decomposition
+//   workgroup = 4 wavefronts = 128 group-flattened query rows of one KV head (with 4 query
+//   heads per KV head and a 32-row block that is exactly the whole KV group, so every K/V
+//   byte is fetched once per pass); wavefront w owns rows [32w, 32w+32).
+//   grid = batch * Hkv * row_tiles * nsplit workgroups, remapped so that workgroups that share
+//   K/V (row tiles of one KV head) land on the same XCD / L2.
+// Per 64-key tile
+//   K tile  -> LDS row-major [key][D] (row stride D*2+16 bytes: conflict-free ds_read_b128)
+//   V tile  -> LDS transposed [d][key slot] (stride 64*2+16 bytes); the transpose happens in
+//              registers on the way from global memory, keys are stored in the slot order in
+//              which the score MFMA leaves them in registers.
+//   S^T = K Q^T  : A = K rows from LDS, B = Q^T held in registers for the whole pass.
+//                  Each lane ends up with 32 scores of ONE query row (row = lane%32), so the
+//                  row max / row sum are in-lane reductions plus one exchange with lane^32.
+//   O^T += V^T P^T: A = V^T from LDS, B = P^T = the lane's own exp2'd scores packed to bf16.
+//   Tiles are double-buffered: global loads of tile t+1 are in flight (in registers) while
+//   tile t is computed from LDS; one barrier per tile.
+// Precision: bf16 operands, fp32 MFMA accumulation, fp32 max / sum / rescale, probabilities
+// rounded to bf16 for the PV product; scores live in the log2 domain (scale*log2(e) folded).
+#include "fb_kernels.h"
+
+namespace fb {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+template <int D>
+struct Cfg {
+  static constexpr int KT = kKeyTile;               // keys per tile
+  static constexpr int KSTR = D * 2 + 16;           // bytes per K row in LDS
+  static constexpr int VSTR = KT * 2 + 16;          // bytes per V^T row in LDS
+  static constexpr int KBYTES = KT * KSTR;
+  static constexpr int VBYTES = D * VSTR;
+  static constexpr int STAGE = KBYTES + VBYTES;
+  static constexpr int LDS = 2 * STAGE;
+  static constexpr int NK = (KT * (D / 8)) / 256;   // 16-byte K chunks per thread per tile
+  static constexpr int VUNITS = (KT / 4) * (D / 8); // (4 keys x 8 d) transpose units per tile
+  static constexpr int NKS = D / 16;                // MFMA k-steps of the score product
+  static constexpr int NDB = D / 32;                // 32-wide output column blocks
+};
+
+struct TileRegs {
+  uint4 k[4];
+  uint4 v[4];
+};
+
+// Running softmax state of the 32 rows a wavefront owns (one row per lane pair l, l^32).
+template <int NDB>
+struct WaveState {
+  float m, l;          // log2-domain running reference; per-lane partial row sum
+  f32x16 o[NDB];       // O^T: lane (row = lane%32, h = lane/32) holds d = 32db + 8(r/4) + 4h + r%4
+  __device__ __forceinline__ void init() {
+    m = -INFINITY;
+    l = 0.f;
+#pragma unroll
+    for (int i = 0; i < NDB; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[i][r] = 0.f;
+  }
+};
+
+template <int D>
+__device__ __forceinline__ void tile_load(TileRegs& t, const __bf16* __restrict__ K,
+                                          const __bf16* __restrict__ V, int k0, int nkeys, int tid) {
+  using C = Cfg<D>;
+  const uint4 z = make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+  for (int i = 0; i < C::NK; ++i) {
+    const int c = tid + 256 * i;
+    const int row = c / (D / 8), col = c % (D / 8);
+    const int key = k0 + row;
+    t.k[i] = (key < nkeys) ? *(const uint4*)(K + (size_t)key * D + col * 8) : z;
+  }
+  if (tid < C::VUNITS) {
+    const int doct = tid % (D / 8), kq = tid / (D / 8);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int key = k0 + 4 * kq + j;
+      t.v[j] = (key < nkeys) ? *(const uint4*)(V + (size_t)key * D + doct * 8) : z;
+    }
+  }
+}
+
+template <int D>
+__device__ __forceinline__ void tile_store(const TileRegs& t, unsigned char* __restrict__ stage, int tid) {
+  using C = Cfg<D>;
+  unsigned char* Ks = stage;
+  unsigned char* Vt = stage + C::KBYTES;
+#pragma unroll
+  for (int i = 0; i < C::NK; ++i) {
+    const int c = tid + 256 * i;
+    const int row = c / (D / 8), col = c % (D / 8);
+    *(uint4*)(Ks + row * C::KSTR + col * 16) = t.k[i];
+  }
+  if (tid < C::VUNITS) {
+    const int doct = tid % (D / 8), kq = tid / (D / 8);
+    // key quad kq of a 16-key group goes to slot quad {0,2,1,3}[kq%4]: the order in which the
+    // 32x32 score accumulators hand keys to the two lane halves.
+    const int g4 = kq & 3;
+    const int sq = ((g4 & 1) << 1) | (g4 >> 1);
+    const int slot = 16 * (kq >> 2) + 4 * sq;
+    const uint32_t a[4] = {t.v[0].x, t.v[0].y, t.v[0].z, t.v[0].w};
+    const uint32_t b[4] = {t.v[1].x, t.v[1].y, t.v[1].z, t.v[1].w};
+    const uint32_t c[4] = {t.v[2].x, t.v[2].y, t.v[2].z, t.v[2].w};
+    const uint32_t d[4] = {t.v[3].x, t.v[3].y, t.v[3].z, t.v[3].w};
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      uint2 lo, hi;   // column 2w (low halves) and 2w+1 (high halves) of the 4 keys
+      lo.x = (a[w] & 0xffffu) | (b[w] << 16);
+      lo.y = (c[w] & 0xffffu) | (d[w] << 16);
+      hi.x = (a[w] >> 16) | (b[w] & 0xffff0000u);
+      hi.y = (c[w] >> 16) | (d[w] & 0xffff0000u);
+      const int dcol = doct * 8 + 2 * w;
+      *(uint2*)(Vt + dcol * C::VSTR + slot * 2) = lo;
+      *(uint2*)(Vt + (dcol + 1) * C::VSTR + slot * 2) = hi;
+    }
+  }
+}
+
+// One 64-key tile for one wavefront: scores, online softmax update, value accumulation.
+//   lane_on : this lane's query row takes part in this tile for this accumulator set
+//   nvalid  : keys of the tile that exist (ragged tail); 64 for full tiles
+template <int D>
+__device__ __forceinline__ void tile_compute(WaveState<Cfg<D>::NDB>& st, const bf16x8 (&qreg)[Cfg<D>::NKS],
+                                             const unsigned char* __restrict__ stage, float scale_log2,
+                                             bool lane_on, int nvalid, int l32, int h) {
+  using C = Cfg<D>;
+  const unsigned char* Ks = stage;
+  const unsigned char* Vt = stage + C::KBYTES;
+
+  f32x16 s[2];
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < C::NKS; ++ks) {
+      const bf16x8 a = *(const bf16x8*)(Ks + (kb * 32 + l32) * C::KSTR + (ks * 16 + 8 * h) * 2);
+      s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], s[kb], 0, 0, 0);
+    }
+  }
+  // s[kb][r] is the raw dot product of query row l32 with key kb*32 + 8*(r/4) + 4*h + r%4
+  if (nvalid < C::KT) {
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int key = kb * 32 + 8 * (r / 4) + 4 * h + (r % 4);
+        if (key >= nvalid) s[kb][r] = -INFINITY;
+      }
+  }
+  float tmax = -INFINITY;
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[kb][r]);
+  tmax = lane_on ? tmax * scale_log2 : -INFINITY;
+  tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+  const float m_new = fmaxf(st.m, tmax);
+  const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+  const float alpha = __builtin_amdgcn_exp2f(st.m - m_use);
+  float lsum = 0.f;
+  bf16x8 pb[4];
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      // raw v_exp_f32: exp2(-inf) = 0, results below 2^-126 flush to 0 (irrelevant for weights)
+      float pf = __builtin_amdgcn_exp2f(fmaf(s[kb][r], scale_log2, -m_use));
+      if (!lane_on) pf = 0.f;                        // rows that sit this tile out
+      lsum += pf;
+      pb[2 * kb + r / 8][r % 8] = (__bf16)pf;
+    }
+  st.l = st.l * alpha + lsum;
+  st.m = m_new;
+  if (__any(alpha != 1.f)) {
+#pragma unroll
+    for (int db = 0; db < C::NDB; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) st.o[db][r] *= alpha;
+  }
+#pragma unroll
+  for (int db = 0; db < C::NDB; ++db)
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const bf16x8 a = *(const bf16x8*)(Vt + (db * 32 + l32) * C::VSTR + (t * 16 + 8 * h) * 2);
+      st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[t], st.o[db], 0, 0, 0);
+    }
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  bf16x2 v;
+  v[0] = (__bf16)a;
+  v[1] = (__bf16)b;
+  return __builtin_bit_cast(uint32_t, v);
+}
+
+template <int D, int MODE>
+__global__ __launch_bounds__(256, (MODE == kPassSparseRefresh) ? 1 : 2) void attn_bf16_kernel(const PassParams p) {
+  using C = Cfg<D>;
+  extern __shared__ __align__(16) unsigned char smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, h = lane >> 5;
+
+  // XCD-aware remap: hardware deals consecutive workgroup ids round-robin to the 8 XCDs; make
+  // each XCD own a contiguous range of work items (row tiles of one KV head are adjacent).
+  const int nwg = gridDim.x;
+  int w;
+  {
+    const int bid = blockIdx.x, q8 = nwg / 8, r8 = nwg % 8;
+    const int xcd = bid % 8, j = bid / 8;
+    w = (xcd < r8 ? xcd * (q8 + 1) : r8 * (q8 + 1) + (xcd - r8) * q8) + j;
+  }
+  const int nrows = p.G * p.Bq;
+  const int ntile_rows = (nrows + kRowsPerWgBf16 - 1) / kRowsPerWgBf16;
+  const int rt = w % ntile_rows;
+  w /= ntile_rows;
+  const int split = w % p.nsplit;
+  w /= p.nsplit;
+  const int kvh = w % p.Hkv;
+  const int b = w / p.Hkv;
+  const int bk = b * p.Hkv + kvh;
+  const int nkeys = p.nkeys;
+
+  const int row = rt * kRowsPerWgBf16 + wave * 32 + l32;      // group-flattened row of this lane
+  const bool row_ok = row < nrows;
+  const size_t grow = (size_t)(b * p.Hq + kvh * p.G) * p.Bq + row;   // global row index
+
+  const __bf16* __restrict__ Q = (const __bf16*)p.q;
+  const __bf16* __restrict__ K = (const __bf16*)p.k + (size_t)bk * nkeys * D;
+  const __bf16* __restrict__ V = (const __bf16*)p.v + (size_t)bk * nkeys * D;
+
+  bf16x8 qreg[C::NKS];
+#pragma unroll
+  for (int ks = 0; ks < C::NKS; ++ks) {
+    uint4 u = make_uint4(0u, 0u, 0u, 0u);
+    if (row_ok) u = *(const uint4*)(Q + grow * D + ks * 16 + 8 * h);
+    qreg[ks] = __builtin_bit_cast(bf16x8, u);
+  }
+
+  // tile list of this workgroup
+  int tpb = 1, total;
+  if constexpr (MODE == kPassSparseReuse) {
+    tpb = p.key_block / kKeyTile;
+    total = p.union_cnt[bk] * tpb;
+  } else {
+    total = (nkeys + kKeyTile - 1) / kKeyTile;
+  }
+  const TileRange tr = split_range(total, p.nsplit, split);
+  const uint32_t* __restrict__ bmask = p.blk_mask ? p.blk_mask + (size_t)bk * p.nblk : nullptr;
+  const int32_t* __restrict__ ulist = p.union_list ? p.union_list + (size_t)bk * p.nblk : nullptr;
+  const uint32_t my_bit = 1u << ((row_ok ? row : 0) / p.Bq);
+
+  auto entry_k0 = [&](int e, uint32_t& mask) -> int {
+    if constexpr (MODE == kPassSparseReuse) {
+      const int blk = ulist[e / tpb];
+      mask = bmask[blk];
+      return blk * p.key_block + kKeyTile * (e % tpb);
+    } else if constexpr (MODE == kPassSparseRefresh) {
+      mask = bmask[(e * kKeyTile) / p.key_block];
+      return e * kKeyTile;
+    } else {
+      mask = 0xffffffffu;
+      return e * kKeyTile;
+    }
+  };
+
+  WaveState<C::NDB> sel;
+  sel.init();
+  WaveState<(MODE == kPassSparseRefresh) ? C::NDB : 1> res;
+  res.init();
+
+  TileRegs regs;
+  uint32_t mask_cur = 0, mask_next = 0;
+  int k0_cur = 0, k0_next = 0;
+  if (tr.begin < tr.end) {
+    k0_cur = entry_k0(tr.begin, mask_cur);
+    tile_load<D>(regs, K, V, k0_cur, nkeys, tid);
+    tile_store<D>(regs, smem, tid);
+  }
+  __syncthreads();
+  for (int e = tr.begin; e < tr.end; ++e) {
+    const int cur = (e - tr.begin) & 1;
+    const bool more = (e + 1 < tr.end);
+    if (more) {
+      k0_next = entry_k0(e + 1, mask_next);
+      tile_load<D>(regs, K, V, k0_next, nkeys, tid);
+    }
+    const unsigned char* stage = smem + cur * C::STAGE;
+    const int nvalid = min(C::KT, nkeys - k0_cur);      // <= 0 only for a reuse-list tile past the end
+    if (nvalid > 0) {
+      if constexpr (MODE == kPassSparseRefresh) {
+        const bool on = row_ok && (mask_cur & my_bit);
+        if (__any(on)) tile_compute<D>(sel, qreg, stage, p.scale_log2, on, nvalid, l32, h);
+        const bool off = row_ok && !(mask_cur & my_bit);
+        if (__any(off)) tile_compute<D>(res, qreg, stage, p.scale_log2, off, nvalid, l32, h);
+      } else if constexpr (MODE == kPassSparseReuse) {
+        const bool on = row_ok && (mask_cur & my_bit);
+        if (__any(on)) tile_compute<D>(sel, qreg, stage, p.scale_log2, on, nvalid, l32, h);
+      } else {
+        tile_compute<D>(sel, qreg, stage, p.scale_log2, true, nvalid, l32, h);
+      }
+    }
+    if (more) tile_store<D>(regs, smem + (cur ^ 1) * C::STAGE, tid);
+    __syncthreads();
+    k0_cur = k0_next;
+    mask_cur = mask_next;
+  }
+
+  // ---------------------------------------------------------------- epilogue
+  const float l_sel = sel.l + __shfl_xor(sel.l, 32, 64);
+  if constexpr (MODE == kPassInternal) {
+    if (!row_ok) return;
+    float me2 = -INFINITY, le = 0.f;
+    if (p.ext_o != nullptr) {
+      const float me = p.ext_m[grow], lse = p.ext_lse[grow];
+      if (lse != -INFINITY) {
+        me2 = me * kLog2e;
+        le = exp2f((lse - me) * kLog2e);
+      }
+    }
+    // Eq. 8-9 with the cached pair expressed through (o, m, lse): A_out e^{L_out-M} = o e^{m-M}
+    const float M2 = fmaxf(me2, sel.m);
+    const float Mu = (M2 == -INFINITY) ? 0.f : M2;
+    const float we = exp2f(me2 - Mu), wi = exp2f(sel.m - Mu);
+    const float den = le * we + l_sel * wi;
+    const float inv = den > 0.f ? 1.f / den : 0.f;
+    __bf16* out = (__bf16*)p.out + grow * D;
+#pragma unroll
+    for (int db = 0; db < C::NDB; ++db)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const int d0 = 32 * db + 8 * q4 + 4 * h;
+        f32x4 e = {0.f, 0.f, 0.f, 0.f};
+        if (le > 0.f) e = *(const f32x4*)(p.ext_o + grow * D + d0);
+        float r[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r[i] = (sel.o[db][4 * q4 + i] * wi + e[i] * we) * inv;
+        uint2 pk;
+        pk.x = pack_bf16x2(r[0], r[1]);
+        pk.y = pack_bf16x2(r[2], r[3]);
+        *(uint2*)(out + d0) = pk;
+      }
+    if (p.lse_out != nullptr && h == 0) p.lse_out[grow] = den > 0.f ? (M2 + log2f(den)) * kLn2 : -INFINITY;
+  } else {
+    const size_t rows_total = (size_t)p.B * p.Hq * p.Bq;
+    const size_t wrow = (size_t)split * rows_total + grow;
+    if (row_ok) {
+#pragma unroll
+      for (int db = 0; db < C::NDB; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const int d0 = 32 * db + 8 * q4 + 4 * h;
+          f32x4 o4 = {sel.o[db][4 * q4], sel.o[db][4 * q4 + 1], sel.o[db][4 * q4 + 2], sel.o[db][4 * q4 + 3]};
+          *(f32x4*)(p.ws_o + wrow * D + d0) = o4;
+        }
+      if (h == 0) {
+        p.ws_m[wrow] = sel.m;
+        p.ws_l[wrow] = l_sel;
+      }
+    }
+    if constexpr (MODE == kPassSparseRefresh) {
+      const float l_res = res.l + __shfl_xor(res.l, 32, 64);
+      if (row_ok) {
+#pragma unroll
+        for (int db = 0; db < C::NDB; ++db)
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4) {
+            const int d0 = 32 * db + 8 * q4 + 4 * h;
+            f32x4 o4 = {res.o[db][4 * q4], res.o[db][4 * q4 + 1], res.o[db][4 * q4 + 2], res.o[db][4 * q4 + 3]};
+            *(f32x4*)(p.ws_o2 + wrow * D + d0) = o4;
+          }
+        if (h == 0) {
+          p.ws_m2[wrow] = res.m;
+          p.ws_l2[wrow] = l_res;
+        }
+      }
+    }
+  }
+}
+
+template <int D, int MODE>
+hipError_t launch_one(const PassParams& p, hipStream_t s) {
+  static bool attr_set = false;   // raising the dynamic-LDS limit is idempotent; the flag only saves calls
+  auto kern = attn_bf16_kernel<D, MODE>;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, Cfg<D>::LDS);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int nrows = p.G * p.Bq;
+  const int ntile_rows = (nrows + kRowsPerWgBf16 - 1) / kRowsPerWgBf16;
+  const long long nwg = (long long)p.B * p.Hkv * ntile_rows * p.nsplit;
+  hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(256), Cfg<D>::LDS, s, p);
+  return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_d(const PassParams& p, PassMode mode, hipStream_t s) {
+  switch (mode) {
+    case kPassDense: return launch_one<D, kPassDense>(p, s);
+    case kPassInternal: return launch_one<D, kPassInternal>(p, s);
+    case kPassSparseRefresh: return launch_one<D, kPassSparseRefresh>(p, s);
+    case kPassSparseReuse: return launch_one<D, kPassSparseReuse>(p, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+hipError_t launch_attn_bf16(const PassParams& p, int D, PassMode mode, hipStream_t s) {
+  if (D == 64) return launch_d<64>(p, mode, s);
+  return launch_d<128>(p, mode, s);
+}
+
+}  // namespace fb

@@ -1,0 +1,216 @@
+// fp32 attention pass for gfx950: plain-FMA scores, wavefront-shuffle softmax statistics.
+//
+// Computes the per-row statistics of Eq. 3-4/6 (arxiv 2602.05305, Section 4.2) over a key
+// range, for storage type float.  This is the exactness path (max-abs 1e-5 against a float64
+// reference): scores are fp32 FMA chains, the running maximum is exact, and every reduction
+// has a fixed order, so results are bit-reproducible.
+//
+// Work decomposition: one workgroup = 4 wavefronts = 4 consecutive query rows of one query
+// head; grid = (row chunks, batch*Hq, splits).  Per 64-key tile the workgroup stages K in LDS
+// (row stride D+4 floats: conflict-free 128-bit reads), lane j of each wavefront scores key j
+// against its wavefront's query row, max/sum go through 6-step xor shuffles, and the value
+// accumulation has lanes own output columns (lane, lane+64) with p_j broadcast by readlane
+// while V rows are read coalesced from global memory (L1/L2 serve the 4 rows' re-reads).
+#include "fb_kernels.h"
+
+namespace fb {
+namespace {
+
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, 64));
+  return x;
+}
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+  return x;
+}
+
+template <int NACC>
+struct RowState {
+  float m, l;
+  float acc[NACC];
+  __device__ __forceinline__ void init() {
+    m = -INFINITY;
+    l = 0.f;
+#pragma unroll
+    for (int i = 0; i < NACC; ++i) acc[i] = 0.f;
+  }
+};
+
+// One online-softmax update of a row's state with the 64 scores held one per lane
+// (log2 domain; -inf marks keys outside the set).
+template <int D, int NACC>
+__device__ __forceinline__ void row_update(RowState<NACC>& st, float s, const float* __restrict__ V,
+                                           int k0, int nvalid, int lane) {
+  const float tmax = wave_max(s);
+  const float m_new = fmaxf(st.m, tmax);
+  const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+  const float p = exp2f(s - m_use);
+  const float alpha = exp2f(st.m - m_use);
+  st.l = st.l * alpha + wave_sum(p);
+#pragma unroll
+  for (int i = 0; i < NACC; ++i) st.acc[i] *= alpha;
+  const float* vrow = V + (size_t)k0 * D + lane;
+  for (int j = 0; j < nvalid; ++j) {
+    const float pj = __shfl(p, j, 64);
+#pragma unroll
+    for (int i = 0; i < NACC; ++i) st.acc[i] = fmaf(pj, vrow[(size_t)j * D + 64 * i], st.acc[i]);
+  }
+  st.m = m_new;
+}
+
+template <int D, int MODE>
+__global__ __launch_bounds__(256) void attn_f32_kernel(const PassParams p) {
+  constexpr int KSTR = D + 4;
+  constexpr int NACC = D / 64;
+  __shared__ __align__(16) float Ks[kKeyTile * KSTR];
+  __shared__ __align__(16) float Qs[4 * D];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int chunk = blockIdx.x;
+  const int bh = blockIdx.y;
+  const int b = bh / p.Hq, h = bh % p.Hq;
+  const int kvh = h / p.G, g = h % p.G;
+  const int split = blockIdx.z;
+  const int row = chunk * 4 + wave;
+  const bool valid = row < p.Bq;
+  const int nkeys = p.nkeys;
+  const int bk = b * p.Hkv + kvh;
+
+  const float* __restrict__ Q = (const float*)p.q + (size_t)(b * p.Hq + h) * p.Bq * D;
+  const float* __restrict__ K = (const float*)p.k + (size_t)bk * nkeys * D;
+  const float* __restrict__ V = (const float*)p.v + (size_t)bk * nkeys * D;
+
+  for (int i = tid; i < 4 * D; i += 256) {
+    const int r = chunk * 4 + i / D;
+    Qs[i] = (r < p.Bq) ? Q[(size_t)r * D + (i % D)] : 0.f;
+  }
+
+  // tile list of this workgroup
+  int tpb = 1, total;
+  if constexpr (MODE == kPassSparseReuse) {
+    tpb = p.key_block / kKeyTile;
+    total = p.union_cnt[bk] * tpb;
+  } else {
+    total = (nkeys + kKeyTile - 1) / kKeyTile;
+  }
+  const TileRange tr = split_range(total, p.nsplit, split);
+
+  RowState<NACC> sel, res;   // res only used by the sparse refresh pass
+  sel.init();
+  res.init();
+
+  for (int e = tr.begin; e < tr.end; ++e) {
+    int k0;
+    bool is_sel = true;
+    if constexpr (MODE == kPassSparseReuse) {
+      const int blk = p.union_list[(size_t)bk * p.nblk + e / tpb];
+      k0 = blk * p.key_block + kKeyTile * (e % tpb);
+      is_sel = (p.blk_mask[(size_t)bk * p.nblk + blk] >> g) & 1u;
+      if (!is_sel || k0 >= nkeys) continue;   // uniform over the workgroup
+    } else {
+      k0 = e * kKeyTile;
+      if constexpr (MODE == kPassSparseRefresh)
+        is_sel = (p.blk_mask[(size_t)bk * p.nblk + k0 / p.key_block] >> g) & 1u;
+    }
+    __syncthreads();   // all wavefronts are done with the previous K tile (and Qs is written)
+    for (int c = tid; c < kKeyTile * (D / 4); c += 256) {
+      const int r = c / (D / 4), c4 = c % (D / 4);
+      const int key = k0 + r;
+      float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (key < nkeys) val = *(const float4*)(K + (size_t)key * D + c4 * 4);
+      *(float4*)(Ks + r * KSTR + c4 * 4) = val;
+    }
+    __syncthreads();
+    if (valid) {
+      const float4* kr = (const float4*)(Ks + lane * KSTR);
+      const float4* qr = (const float4*)(Qs + wave * D);
+      float s = 0.f;
+#pragma unroll 8
+      for (int i = 0; i < D / 4; ++i) {
+        const float4 a = kr[i], c = qr[i];
+        s = fmaf(a.x, c.x, s);
+        s = fmaf(a.y, c.y, s);
+        s = fmaf(a.z, c.z, s);
+        s = fmaf(a.w, c.w, s);
+      }
+      s *= p.scale_log2;
+      if (k0 + lane >= nkeys) s = -INFINITY;
+      const int nvalid = min(kKeyTile, nkeys - k0);
+      if (MODE == kPassSparseRefresh && !is_sel)
+        row_update<D, NACC>(res, s, V, k0, nvalid, lane);
+      else
+        row_update<D, NACC>(sel, s, V, k0, nvalid, lane);
+    }
+  }
+
+  if (!valid) return;
+  const size_t grow = (size_t)(b * p.Hq + h) * p.Bq + row;
+  if constexpr (MODE == kPassInternal) {
+    // Eq. 8-9 with the cached pair expressed through (o, m, lse): A_out e^{L_out-M} = o e^{m-M}.
+    constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
+    float me2 = -INFINITY, le = 0.f;
+    if (p.ext_o != nullptr) {
+      const float me = p.ext_m[grow], lse = p.ext_lse[grow];
+      if (lse != -INFINITY) {
+        me2 = me * kLog2e;
+        le = exp2f((lse - me) * kLog2e);
+      }
+    }
+    const float M2 = fmaxf(me2, sel.m);
+    const float Mu = (M2 == -INFINITY) ? 0.f : M2;
+    const float we = exp2f(me2 - Mu), wi = exp2f(sel.m - Mu);
+    const float den = le * we + sel.l * wi;
+    const float inv = den > 0.f ? 1.f / den : 0.f;
+    float* out = (float*)p.out + grow * D;
+#pragma unroll
+    for (int i = 0; i < NACC; ++i) {
+      float num = sel.acc[i] * wi;
+      if (le > 0.f) num = fmaf(p.ext_o[grow * D + lane + 64 * i], we, num);
+      out[lane + 64 * i] = num * inv;
+    }
+    if (p.lse_out != nullptr && lane == 0)
+      p.lse_out[grow] = den > 0.f ? (M2 + log2f(den)) * kLn2 : -INFINITY;
+  } else {
+    const size_t rows_total = (size_t)p.B * p.Hq * p.Bq;
+    const size_t wrow = (size_t)split * rows_total + grow;
+#pragma unroll
+    for (int i = 0; i < NACC; ++i) p.ws_o[wrow * D + lane + 64 * i] = sel.acc[i];
+    if (lane == 0) {
+      p.ws_m[wrow] = sel.m;
+      p.ws_l[wrow] = sel.l;
+    }
+    if constexpr (MODE == kPassSparseRefresh) {
+#pragma unroll
+      for (int i = 0; i < NACC; ++i) p.ws_o2[wrow * D + lane + 64 * i] = res.acc[i];
+      if (lane == 0) {
+        p.ws_m2[wrow] = res.m;
+        p.ws_l2[wrow] = res.l;
+      }
+    }
+  }
+}
+
+template <int D>
+hipError_t launch_d(const PassParams& p, PassMode mode, hipStream_t s) {
+  const dim3 grid((p.Bq + kRowsPerWgF32 - 1) / kRowsPerWgF32, p.B * p.Hq, p.nsplit);
+  const dim3 block(256);
+  switch (mode) {
+    case kPassDense: hipLaunchKernelGGL((attn_f32_kernel<D, kPassDense>), grid, block, 0, s, p); break;
+    case kPassInternal: hipLaunchKernelGGL((attn_f32_kernel<D, kPassInternal>), grid, block, 0, s, p); break;
+    case kPassSparseRefresh: hipLaunchKernelGGL((attn_f32_kernel<D, kPassSparseRefresh>), grid, block, 0, s, p); break;
+    case kPassSparseReuse: hipLaunchKernelGGL((attn_f32_kernel<D, kPassSparseReuse>), grid, block, 0, s, p); break;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_attn_f32(const PassParams& p, int D, PassMode mode, hipStream_t s) {
+  if (D == 64) return launch_d<64>(p, mode, s);
+  return launch_d<128>(p, mode, s);
+}
+
+}  // namespace fb

@@ -1,0 +1,280 @@
+// Small kernels around the attention passes: the split-KV combine (Eq. 5 applied to the
+// per-split partials, fixed order), key-block pooling / top-k selection for the sparse
+// variant, and the per-KV-group selection masks + union list the sparse passes iterate over.
+#include "fb_kernels.h"
+
+namespace fb {
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// ------------------------------------------------------------------------------ combine
+// A folded partial in the log2 domain: o4 (4 columns of this thread), reference m2, sum l.
+struct Folded {
+  float4 o;
+  float m2, l;
+};
+
+__device__ __forceinline__ Folded fold_splits(const float* __restrict__ ws_o, const float* __restrict__ ws_m,
+                                              const float* __restrict__ ws_l, int nsplit, size_t rows,
+                                              size_t row, int D, int c4) {
+  Folded f;
+  f.o = make_float4(0.f, 0.f, 0.f, 0.f);
+  f.l = 0.f;
+  float M = -INFINITY;
+  for (int s = 0; s < nsplit; ++s) M = fmaxf(M, ws_m[(size_t)s * rows + row]);
+  f.m2 = M;
+  if (M == -INFINITY) return f;
+  for (int s = 0; s < nsplit; ++s) {
+    const size_t r = (size_t)s * rows + row;
+    const float w = exp2f(ws_m[r] - M);
+    const float4 o = *(const float4*)(ws_o + r * D + c4 * 4);
+    f.o.x = fmaf(o.x, w, f.o.x);
+    f.o.y = fmaf(o.y, w, f.o.y);
+    f.o.z = fmaf(o.z, w, f.o.z);
+    f.o.w = fmaf(o.w, w, f.o.w);
+    f.l = fmaf(ws_l[r], w, f.l);
+  }
+  return f;
+}
+
+__device__ __forceinline__ Folded fold_two(const Folded& a, const Folded& b) {
+  Folded f;
+  f.m2 = fmaxf(a.m2, b.m2);
+  const float mu = (f.m2 == -INFINITY) ? 0.f : f.m2;
+  const float wa = exp2f(a.m2 - mu), wb = exp2f(b.m2 - mu);
+  f.o.x = a.o.x * wa + b.o.x * wb;
+  f.o.y = a.o.y * wa + b.o.y * wb;
+  f.o.z = a.o.z * wa + b.o.z * wb;
+  f.o.w = a.o.w * wa + b.o.w * wb;
+  f.l = a.l * wa + b.l * wb;
+  return f;
+}
+
+// Emit (o, m, lse) in natural-log units.  m is rounded when converted, so o and l are
+// rescaled to the reference that consumers recover as m * log2(e): the pair stays exact.
+__device__ __forceinline__ void emit(const Folded& f, float* __restrict__ o, float* __restrict__ m,
+                                     float* __restrict__ lse, size_t row, int D, int c4) {
+  float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+  float m_nat = -INFINITY, L = -INFINITY;
+  if (f.l > 0.f) {
+    m_nat = f.m2 * kLn2;
+    const float back = m_nat * kLog2e;
+    const float adj = exp2f(f.m2 - back);
+    v = make_float4(f.o.x * adj, f.o.y * adj, f.o.z * adj, f.o.w * adj);
+    L = (f.m2 + log2f(f.l)) * kLn2;
+  }
+  *(float4*)(o + row * D + c4 * 4) = v;
+  if (c4 == 0) {
+    m[row] = m_nat;
+    lse[row] = L;
+  }
+}
+
+__global__ __launch_bounds__(256) void combine_kernel(const CombineParams p) {
+  const int per_row = p.D / 4;
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (size_t)p.rows * per_row) return;
+  const size_t row = idx / per_row;
+  const int c4 = (int)(idx % per_row);
+
+  Folded sel;
+  if (p.ws_o != nullptr && p.nsplit > 0) {
+    sel = fold_splits(p.ws_o, p.ws_m, p.ws_l, p.nsplit, p.rows, row, p.D, c4);
+  } else {
+    sel.o = make_float4(0.f, 0.f, 0.f, 0.f);
+    sel.m2 = -INFINITY;
+    sel.l = 0.f;
+  }
+  Folded res;
+  res.o = make_float4(0.f, 0.f, 0.f, 0.f);
+  res.m2 = -INFINITY;
+  res.l = 0.f;
+  if (p.ws_o2 != nullptr) {           // refresh: residual set from this pass
+    res = fold_splits(p.ws_o2, p.ws_m2, p.ws_l2, p.nsplit, p.rows, row, p.D, c4);
+  } else if (p.res_in_o != nullptr) { // reuse: cached residual, natural-log units
+    const float lse = p.res_in_lse[row];
+    if (lse != -INFINITY) {
+      const float m = p.res_in_m[row];
+      res.m2 = m * kLog2e;
+      res.l = exp2f((lse - m) * kLog2e);
+      res.o = *(const float4*)(p.res_in_o + row * p.D + c4 * 4);
+    }
+  }
+  if (p.res_out_o != nullptr) emit(res, p.res_out_o, p.res_out_m, p.res_out_lse, row, p.D, c4);
+  const Folded total = fold_two(sel, res);
+  emit(total, p.o, p.m, p.lse, row, p.D, c4);
+}
+
+// ------------------------------------------------------------------------------ pooling
+__device__ __forceinline__ float load_elem(const void* base, size_t i, int is_bf16) {
+  if (is_bf16) {
+    const uint32_t u = ((uint32_t)((const uint16_t*)base)[i]) << 16;
+    return __uint_as_float(u);
+  }
+  return ((const float*)base)[i];
+}
+
+// grid (nblk, B*Hkv), 256 threads: column d = tid % D, token lane = tid / D.
+__global__ __launch_bounds__(256) void pool_keys_kernel(const PoolParams p) {
+  __shared__ float red[256];
+  const int c = blockIdx.x, bh = blockIdx.y;
+  const int D = p.D, tid = threadIdx.x;
+  const int d = tid % D, tl = tid / D, ntl = 256 / D;
+  const int k0 = c * p.key_block, k1 = min(p.nkeys, k0 + p.key_block);
+  float s = 0.f;
+  for (int k = k0 + tl; k < k1; k += ntl) s += load_elem(p.k, ((size_t)bh * p.nkeys + k) * D + d, p.is_bf16);
+  red[tid] = s;
+  __syncthreads();
+  if (tl == 0) {
+    for (int j = 1; j < ntl; ++j) s += red[j * D + d];
+    p.k_pooled[((size_t)bh * p.nblk + c) * D + d] = s / (float)(k1 - k0);
+  }
+}
+
+// ------------------------------------------------------------------------------ top-k
+// grid (B*Hq), 256 threads, dynamic LDS: qbar[D] | red[256] | score[nblk] | flag[nblk]
+__global__ __launch_bounds__(256) void select_topk_kernel(const SelectParams p) {
+  extern __shared__ __align__(16) float lds[];
+  float* qbar = lds;
+  float* red = qbar + p.D;
+  float* score = red + 256;
+  int* flag = (int*)(score + p.nblk);
+  __shared__ int chunk_cnt[256];
+
+  const int bh = blockIdx.x, b = bh / p.Hq, h = bh % p.Hq, kvh = h / p.G;
+  const int D = p.D, tid = threadIdx.x, nblk = p.nblk;
+  const int k = min(p.topk, nblk);
+
+  {  // mean over the block's query rows
+    const int d = tid % D, tl = tid / D, ntl = 256 / D;
+    float s = 0.f;
+    for (int r = tl; r < p.Bq; r += ntl) s += load_elem(p.q, ((size_t)bh * p.Bq + r) * D + d, p.is_bf16);
+    red[tid] = s;
+    __syncthreads();
+    if (tl == 0) {
+      for (int j = 1; j < ntl; ++j) s += red[j * D + d];
+      qbar[d] = s / (float)p.Bq;
+    }
+    __syncthreads();
+  }
+  const float* kp = p.k_pooled + (size_t)(b * p.Hkv + kvh) * nblk * D;
+  for (int c = tid; c < nblk; c += 256) {
+    const float4* kr = (const float4*)(kp + (size_t)c * D);
+    float s = 0.f;
+    for (int i = 0; i < D / 4; ++i) {
+      const float4 a = kr[i];
+      s = fmaf(a.x, qbar[4 * i], s);
+      s = fmaf(a.y, qbar[4 * i + 1], s);
+      s = fmaf(a.z, qbar[4 * i + 2], s);
+      s = fmaf(a.w, qbar[4 * i + 3], s);
+    }
+    score[c] = s;
+  }
+  __syncthreads();
+  // rank by counting: block c is kept iff fewer than k blocks beat it (ties: lower index wins)
+  for (int c = tid; c < nblk; c += 256) {
+    const float sc = score[c];
+    int beat = 0;
+    for (int j = 0; j < nblk; ++j) {
+      const float sj = score[j];
+      beat += (sj > sc) || (sj == sc && j < c);
+    }
+    flag[c] = beat < k;
+  }
+  __syncthreads();
+  // ascending compaction: thread t owns blocks [t*per, (t+1)*per)
+  const int per = (nblk + 255) / 256;
+  const int c0 = min(nblk, tid * per), c1 = min(nblk, c0 + per);
+  int mine = 0;
+  for (int c = c0; c < c1; ++c) mine += flag[c];
+  chunk_cnt[tid] = mine;
+  __syncthreads();
+  int pos = 0;
+  for (int t = 0; t < tid; ++t) pos += chunk_cnt[t];
+  int32_t* out = p.sel_idx + (size_t)bh * p.topk;
+  for (int c = c0; c < c1; ++c)
+    if (flag[c]) out[pos++] = c;
+  for (int j = k + tid; j < p.topk; j += 256) out[j] = -1;
+}
+
+// ------------------------------------------------------------------------------ masks + union
+// grid (B*Hkv), 256 threads, dynamic LDS: mask[nblk]
+__global__ __launch_bounds__(256) void build_masks_kernel(const MaskParams p) {
+  extern __shared__ __align__(16) uint32_t lmask[];
+  __shared__ int chunk_cnt[256];
+  const int bk = blockIdx.x, b = bk / p.Hkv, kvh = bk % p.Hkv;
+  const int tid = threadIdx.x, nblk = p.nblk;
+  for (int c = tid; c < nblk; c += 256) lmask[c] = 0u;
+  __syncthreads();
+  if (p.sel_idx != nullptr) {
+    const int n = p.G * p.topk;
+    const int32_t* base = p.sel_idx + (size_t)(b * p.Hq + kvh * p.G) * p.topk;
+    for (int i = tid; i < n; i += 256) {
+      const int c = base[i];
+      if (c >= 0 && c < nblk) atomicOr(&lmask[c], 1u << (i / p.topk));
+    }
+  }
+  __syncthreads();
+  const int per = (nblk + 255) / 256;
+  const int c0 = min(nblk, tid * per), c1 = min(nblk, c0 + per);
+  int mine = 0;
+  for (int c = c0; c < c1; ++c) {
+    const uint32_t m = lmask[c];
+    p.blk_mask[(size_t)bk * nblk + c] = m;
+    mine += (m != 0u);
+  }
+  chunk_cnt[tid] = mine;
+  __syncthreads();
+  int pos = 0;
+  for (int t = 0; t < tid; ++t) pos += chunk_cnt[t];
+  int32_t* list = p.union_list + (size_t)bk * nblk;
+  for (int c = c0; c < c1; ++c)
+    if (lmask[c] != 0u) list[pos++] = c;
+  if (tid == 255) p.union_cnt[bk] = pos;
+}
+
+}  // namespace
+
+hipError_t launch_combine(const CombineParams& p, hipStream_t s) {
+  const size_t n = (size_t)p.rows * (p.D / 4);
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(combine_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_pool_keys(const PoolParams& p, hipStream_t s) {
+  if (p.nblk == 0 || p.BH == 0) return hipSuccess;
+  hipLaunchKernelGGL(pool_keys_kernel, dim3(p.nblk, p.BH), dim3(256), 0, s, p);
+  return hipGetLastError();
+}
+
+// Dynamic LDS above the 64 KiB default needs the per-kernel limit raised once.
+template <typename K>
+hipError_t ensure_lds(K kern, size_t bytes, bool& done) {
+  if (bytes <= 48 * 1024 || done) return hipSuccess;
+  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 2048);
+  if (e == hipSuccess) done = true;
+  return e;
+}
+
+hipError_t launch_select_topk(const SelectParams& p, hipStream_t s) {
+  static bool raised = false;
+  const size_t lds = (size_t)(p.D + 256 + 2 * p.nblk) * 4;
+  hipError_t e = ensure_lds(select_topk_kernel, lds, raised);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(select_topk_kernel, dim3(p.B * p.Hq), dim3(256), lds, s, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_build_masks(const MaskParams& p, hipStream_t s) {
+  static bool raised = false;
+  const size_t lds = (size_t)p.nblk * 4;
+  hipError_t e = ensure_lds(build_masks_kernel, lds, raised);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(build_masks_kernel, dim3(p.B * p.Hkv), dim3(256), lds, s, p);
+  return hipGetLastError();
+}
+
+}  // namespace fb

@@ -1,0 +1,95 @@
+// Internal interface between the C-ABI layer (fb_api.hip) and the gfx950 kernels.
+// Not installed; the public contract is include/flashblock.h.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fb {
+
+constexpr int kKeyTile = 64;  // keys per main-loop iteration in every attention kernel
+
+// What a pass iterates over and what it emits.
+enum PassMode : int {
+  kPassDense = 0,          // keys [0, nkeys) cut into nsplit tile ranges -> split partials
+  kPassInternal = 1,       // keys [0, nkeys), no split; epilogue = Eq. 8-9 merge with cached partial
+  kPassSparseRefresh = 2,  // like dense, but every key block is routed to the selected or the residual set
+  kPassSparseReuse = 3     // only key blocks of the per-KV-group union list; selected set only
+};
+
+// One attention pass.  Rows of one KV group are addressed "group-flattened": query head
+// kvh*G+g, block row i  <->  flat row g*Bq+i, which is contiguous in Q / partial / out memory.
+struct PassParams {
+  const void* q;        // [B,Hq,Bq,D]
+  const void* k;        // [B,Hkv,nkeys,D]
+  const void* v;        // [B,Hkv,nkeys,D]
+  int B, Hq, Hkv, G, Bq, nkeys;
+  int nsplit;
+  float scale_log2;     // scale * log2(e): scores are kept in the log2 domain inside the kernels
+  // split partial sets in the workspace, layout [set][split][B*Hq*Bq] rows:
+  //   o [.., D] sum exp2(s2 - m2) v ; m2 (log2 domain reference) ; l = sum exp2(s2 - m2)
+  float* ws_o;  float* ws_m;  float* ws_l;      // set 0: dense / selected
+  float* ws_o2; float* ws_m2; float* ws_l2;     // set 1: residual (sparse refresh only)
+  // internal pass epilogue
+  const float* ext_o; const float* ext_m; const float* ext_lse;   // cached partial (natural log), may be null
+  void* out; float* lse_out;
+  // sparse passes
+  const uint32_t* blk_mask;   // [B,Hkv,nblk] bit g set: head g of the group selected the block
+  const int32_t* union_list;  // [B,Hkv,nblk] ascending blocks with mask != 0
+  const int32_t* union_cnt;   // [B,Hkv]
+  int key_block, nblk;
+};
+
+// Fold split partials (and optionally a cached residual) into final (o, m, lse) partials.
+struct CombineParams {
+  int rows, D, nsplit;
+  const float* ws_o;  const float* ws_m;  const float* ws_l;    // selected / dense set, may be null when nsplit==0
+  const float* ws_o2; const float* ws_m2; const float* ws_l2;   // residual set (refresh) or null
+  const float* res_in_o; const float* res_in_m; const float* res_in_lse;   // cached residual (reuse) or null
+  float* res_out_o; float* res_out_m; float* res_out_lse;                  // residual out (refresh) or null
+  float* o; float* m; float* lse;                                          // total out
+};
+
+struct SelectParams {
+  const void* q; const float* k_pooled; int32_t* sel_idx;
+  int B, Hq, Hkv, G, Bq, D, nblk, topk, is_bf16;
+};
+
+struct PoolParams {
+  const void* k; float* k_pooled;
+  int BH, nkeys, D, key_block, nblk, is_bf16;
+};
+
+struct MaskParams {
+  const int32_t* sel_idx; uint32_t* blk_mask; int32_t* union_list; int32_t* union_cnt;
+  int B, Hq, Hkv, G, topk, nblk;
+};
+
+// Host-side launchers; each returns the hipError_t of its launch(es).
+hipError_t launch_attn_f32(const PassParams& p, int D, PassMode mode, hipStream_t s);
+hipError_t launch_attn_bf16(const PassParams& p, int D, PassMode mode, hipStream_t s);
+hipError_t launch_combine(const CombineParams& p, hipStream_t s);
+hipError_t launch_pool_keys(const PoolParams& p, hipStream_t s);
+hipError_t launch_select_topk(const SelectParams& p, hipStream_t s);
+hipError_t launch_build_masks(const MaskParams& p, hipStream_t s);
+
+// Row tiles (workgroups along the group-flattened row axis) per KV group, per kernel family.
+constexpr int kRowsPerWgBf16 = 128;  // 4 waves x 32 rows
+constexpr int kRowsPerWgF32 = 4;     // 4 waves x 1 row
+
+// ---- device helpers shared by the attention kernels -------------------------------------
+// Tile schedule of one workgroup: which 64-key tiles it visits.
+struct TileRange {
+  int begin, end;   // entries [begin, end) of the pass's tile list
+};
+
+__device__ __forceinline__ TileRange split_range(int total, int nsplit, int split) {
+  // balanced contiguous cut of `total` entries into nsplit pieces
+  const long long t = total;
+  TileRange r;
+  r.begin = (int)((t * split) / nsplit);
+  r.end = (int)((t * (split + 1)) / nsplit);
+  return r;
+}
+
+}  // namespace fb

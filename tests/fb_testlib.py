@@ -1,0 +1,140 @@
+"""Helpers shared by the GPU parity tests: upload seeded workloads, drive the HIP path through
+the C ABI binding, and compare with the numpy float64 oracle."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import flashblock_oracle as orc
+from paper_2602_05305_amd import flashblock as fb
+from paper_2602_05305_amd import workloads as wl
+
+DEV = "cuda:0"
+
+
+def tdtype(dtype):
+    return torch.bfloat16 if dtype == "bf16" else torch.float32
+
+
+def to_dev(x: np.ndarray, dtype: str) -> torch.Tensor:
+    """float32 numpy array of storage-exact values -> device tensor of the storage type."""
+    return torch.from_numpy(np.ascontiguousarray(x)).to(DEV).to(tdtype(dtype)).contiguous()
+
+
+def shape_of(w: wl.Workload, prefix_len=None, scale=0.0):
+    return fb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.block_len,
+                         w.prefix_len if prefix_len is None else prefix_len, w.dtype, scale)
+
+
+class Partial:
+    """Device buffers of one (o, m, lse) partial."""
+
+    def __init__(self, w: wl.Workload):
+        rows = (w.batch, w.n_q_heads, w.block_len)
+        self.o = torch.empty(rows + (w.head_dim,), device=DEV, dtype=torch.float32)
+        self.m = torch.empty(rows, device=DEV, dtype=torch.float32)
+        self.lse = torch.empty(rows, device=DEV, dtype=torch.float32)
+
+    def numpy(self):
+        return {"o": self.o.double().cpu().numpy(), "m": self.m.double().cpu().numpy(),
+                "lse": self.lse.double().cpu().numpy()}
+
+
+def workspace(shape, key_block=0, topk=0, n_splits=0):
+    n = fb.fb_workspace_bytes(shape, key_block, topk, n_splits)
+    assert n > 0
+    return torch.empty(n, device=DEV, dtype=torch.uint8)
+
+
+def tolerances(dtype):
+    """(abs, rel) of |gpu - oracle| <= abs + rel*|oracle|: 1e-5 max-abs for fp32 storage,
+    1e-2 / 1e-2 for bf16 storage with fp32 accumulation."""
+    return (1e-5, 0.0) if dtype == "f32" else (1e-2, 1e-2)
+
+
+def assert_close(got, want, dtype, what, lse=False):
+    got, want = np.asarray(got, dtype=np.float64), np.asarray(want, dtype=np.float64)
+    assert got.shape == want.shape, (what, got.shape, want.shape)
+    a, r = tolerances(dtype)
+    inf = np.isneginf(want)
+    assert np.array_equal(np.isneginf(got), inf), f"{what}: -inf pattern differs"
+    assert not np.isnan(got).any(), f"{what}: NaN"
+    g, wv = got[~inf], want[~inf]
+    if dtype == "f32" and lse:
+        bound = 1e-5 * np.maximum(1.0, np.abs(wv))     # log-normaliser: relative to its magnitude
+    else:
+        bound = a + r * np.abs(wv)
+    err = np.abs(g - wv)
+    if err.size and (err > bound).any():
+        i = int(np.argmax(err - bound))
+        raise AssertionError(f"{what}: |gpu-oracle| = {err.flat[i]:.3e} > {bound.flat[i]:.3e} "
+                             f"(max err {err.max():.3e}, {int((err > bound).sum())} of {err.size} elements)")
+    return float(err.max()) if err.size else 0.0
+
+
+def check_partial(gpu_part, ora_part, dtype, what):
+    """Raw (o, m) is not unique; compare the derived Eq. 6 pair (A, L)."""
+    e1 = assert_close(orc.normalized(gpu_part), orc.normalized(ora_part), dtype, what + " A")
+    e2 = assert_close(gpu_part["lse"], ora_part["lse"], dtype, what + " L", lse=True)
+    # pairing sanity: m must not be below lse - log(nkeys) by construction and not NaN
+    assert not np.isnan(gpu_part["m"]).any()
+    return e1, e2
+
+
+def run_dense_block_gpu(w: wl.Workload, Kp, Vp, steps, R=None, n_splits=0, scale=0.0):
+    """Drive one block through the HIP path.  Returns per step dict(out, lse, ext(numpy partial))."""
+    R = w.refresh if R is None else R
+    shape = shape_of(w, scale=scale)
+    kp = to_dev(Kp, w.dtype) if w.prefix_len > 0 else None
+    vp = to_dev(Vp, w.dtype) if w.prefix_len > 0 else None
+    ws = workspace(shape, n_splits=n_splits)
+    ext = Partial(w)
+    res = []
+    for t, (Q, Kb, Vb) in enumerate(steps):
+        q, kb, vb = to_dev(Q, w.dtype), to_dev(Kb, w.dtype), to_dev(Vb, w.dtype)
+        if t % R == 0:
+            if n_splits:
+                fb.fb_external_partial_ex(shape, q, kp, vp, ext.o, ext.m, ext.lse, n_splits, ws)
+            else:
+                fb.fb_external_partial(shape, q, kp, vp, ext.o, ext.m, ext.lse, ws)
+        out = torch.empty_like(q)
+        lse = torch.empty(q.shape[:3], device=DEV, dtype=torch.float32)
+        fb.fb_internal_merge(shape, q, kb, vb, ext.o, ext.m, ext.lse, out, lse)
+        torch.cuda.synchronize()
+        res.append({"out": out.double().cpu().numpy(), "lse": lse.double().cpu().numpy(), "ext": ext.numpy()})
+    return res
+
+
+def run_sparse_block_gpu(w: wl.Workload, Kp, Vp, steps, idx_per_refresh=None, R=None, scale=0.0):
+    """Sparse path.  idx_per_refresh: dict refresh-step -> int32 [B,Hq,k] (the oracle's selection);
+    None = select on the GPU with fb_pool_keys + fb_select_topk."""
+    R = w.refresh if R is None else R
+    shape = shape_of(w, scale=scale)
+    kp, vp = to_dev(Kp, w.dtype), to_dev(Vp, w.dtype)
+    ws = workspace(shape, w.key_block, w.topk)
+    nblk = -(-w.prefix_len // w.key_block)
+    pooled = torch.empty((w.batch, w.n_kv_heads, nblk, w.head_dim), device=DEV, dtype=torch.float32)
+    fb.fb_pool_keys(shape, kp, w.key_block, pooled)
+    resid, ext = Partial(w), Partial(w)
+    idx = None
+    res = []
+    for t, (Q, Kb, Vb) in enumerate(steps):
+        q, kb, vb = to_dev(Q, w.dtype), to_dev(Kb, w.dtype), to_dev(Vb, w.dtype)
+        refresh = (t % R == 0)
+        if refresh:
+            if idx_per_refresh is not None:
+                idx = torch.from_numpy(np.ascontiguousarray(idx_per_refresh[t], dtype=np.int32)).to(DEV)
+            else:
+                idx = torch.empty((w.batch, w.n_q_heads, max(w.topk, 1)), device=DEV, dtype=torch.int32)
+                fb.fb_select_topk(shape, q, pooled, w.key_block, w.topk, idx)
+        k_arg = idx.shape[2] if (idx_per_refresh is not None) else w.topk
+        fb.fb_sparse_external_residual(shape, fb.FB_SPARSE_REFRESH if refresh else fb.FB_SPARSE_REUSE, q, kp, vp,
+                                       w.key_block, k_arg, idx if k_arg > 0 else None, resid.o, resid.m, resid.lse,
+                                       ext.o, ext.m, ext.lse, ws)
+        out = torch.empty_like(q)
+        lse = torch.empty(q.shape[:3], device=DEV, dtype=torch.float32)
+        fb.fb_internal_merge(shape, q, kb, vb, ext.o, ext.m, ext.lse, out, lse)
+        torch.cuda.synchronize()
+        res.append({"out": out.double().cpu().numpy(), "lse": lse.double().cpu().numpy(), "ext": ext.numpy(),
+                    "residual": resid.numpy(), "idx": idx.cpu().numpy().copy()})
+    return res

@@ -1,0 +1,160 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the header declares,
+and every argument error is reported before anything touches a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2602_05305_amd import flashblock as fb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "flashblock.h")
+
+
+def _declared():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fb_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = fb.load_library()
+    names = _declared()
+    assert {"fb_external_partial", "fb_internal_merge", "fb_sparse_external_residual"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(names) == set(fb.exported_symbols())
+    assert fb.fb_version() == 100
+    for n in names:   # the binding offers the same names
+        assert hasattr(fb, n) or n in ("fb_status_string", "fb_last_hip_error"), n
+
+
+def test_struct_layout_matches_header():
+    assert ctypes.sizeof(fb.fb_shape) == 36
+    assert fb.fb_shape.scale.offset == 32
+
+
+def _ok_shape(**kw):
+    base = dict(batch=1, n_q_heads=4, n_kv_heads=2, head_dim=64, block_len=16, prefix_len=256, dtype="f32")
+    base.update(kw)
+    return fb.make_shape(**base)
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(), fb.FB_OK),
+    (dict(batch=0), fb.FB_ERR_SHAPE),
+    (dict(n_q_heads=5), fb.FB_ERR_SHAPE),
+    (dict(n_q_heads=66, n_kv_heads=2), fb.FB_ERR_SHAPE),
+    (dict(block_len=0), fb.FB_ERR_SHAPE),
+    (dict(prefix_len=-1), fb.FB_ERR_SHAPE),
+    (dict(prefix_len=0), fb.FB_OK),
+    (dict(head_dim=96), fb.FB_ERR_UNSUPPORTED),
+    (dict(head_dim=0), fb.FB_ERR_SHAPE),
+    (dict(dtype=7), fb.FB_ERR_DTYPE),
+    (dict(scale=-1.0), fb.FB_ERR_SHAPE),
+    (dict(scale=float("nan")), fb.FB_ERR_SHAPE),
+    (dict(scale=float("inf")), fb.FB_ERR_SHAPE),
+    (dict(dtype="bf16", head_dim=128), fb.FB_OK),
+])
+def test_check_shape(kw, status):
+    assert fb.fb_check_shape(_ok_shape(**kw)) == status
+
+
+def test_struct_size_is_checked():
+    s = _ok_shape()
+    s.struct_size = 8
+    assert fb.fb_check_shape(s) == fb.FB_ERR_SHAPE
+    assert fb.load_library().fb_check_shape(None) == fb.FB_ERR_NULL
+
+
+def test_workspace_and_split_queries():
+    s = _ok_shape()
+    assert fb.fb_external_splits(s) >= 1
+    assert fb.fb_workspace_bytes(s) >= 256
+    assert fb.fb_workspace_bytes(s, 0, 0, 8) >= 8 * 64 * (64 + 2) * 4
+    assert fb.fb_workspace_bytes(s, 64, 2) > fb.fb_workspace_bytes(s)
+    assert fb.fb_workspace_bytes(s, 48, 2) == 0             # key_block not a multiple of 64
+    assert fb.fb_workspace_bytes(s, 0, 0, 1000) == 0
+    assert fb.fb_workspace_bytes(_ok_shape(batch=0)) == 0
+    big = _ok_shape(dtype="bf16", head_dim=128, n_q_heads=32, n_kv_heads=8, block_len=32, prefix_len=131072)
+    assert fb.fb_external_splits(big) == 64
+
+
+FAKE = ctypes.c_void_p(0x1000)       # aligned, never dereferenced: validation fails first
+ODD = ctypes.c_void_p(0x1004)
+
+
+def test_external_partial_error_paths():
+    lib = fb.load_library()
+    s = _ok_shape()
+    ws_bytes = fb.fb_workspace_bytes(s)
+    call = lib.fb_external_partial
+    assert call(ctypes.byref(s), None, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, ws_bytes, None) == fb.FB_ERR_NULL
+    assert call(ctypes.byref(s), FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, ws_bytes, None) == fb.FB_ERR_NULL
+    assert call(ctypes.byref(s), FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, ws_bytes, None) == fb.FB_ERR_NULL
+    assert call(ctypes.byref(s), ODD, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, ws_bytes, None) == fb.FB_ERR_ALIGN
+    assert call(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, ODD, FAKE, ws_bytes, None) == fb.FB_ERR_ALIGN
+    assert call(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, ws_bytes, None) == fb.FB_ERR_WORKSPACE
+    assert call(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, ws_bytes - 1, None) == fb.FB_ERR_WORKSPACE
+    bad = _ok_shape(head_dim=96)
+    assert call(ctypes.byref(bad), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, ws_bytes, None) == fb.FB_ERR_UNSUPPORTED
+    ex = lib.fb_external_partial_ex
+    assert ex(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 257, FAKE, 1 << 30, None) == fb.FB_ERR_SHAPE
+    assert ex(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, -1, FAKE, 1 << 30, None) == fb.FB_ERR_SHAPE
+    assert ex(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 16, FAKE, ws_bytes - 1, None) in (
+        fb.FB_ERR_WORKSPACE,)
+
+
+def test_internal_merge_error_paths():
+    lib = fb.load_library()
+    s = _ok_shape()
+    call = lib.fb_internal_merge
+    assert call(ctypes.byref(s), None, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, None) == fb.FB_ERR_NULL
+    assert call(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, None) == fb.FB_ERR_NULL
+    assert call(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, None, None) == fb.FB_ERR_NULL  # 2 of 3
+    assert call(ctypes.byref(s), FAKE, FAKE, ODD, FAKE, FAKE, FAKE, FAKE, None, None) == fb.FB_ERR_ALIGN
+    assert call(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, ODD, None) == fb.FB_ERR_ALIGN
+
+
+def test_sparse_error_paths():
+    lib = fb.load_library()
+    s = _ok_shape()
+    ws_bytes = fb.fb_workspace_bytes(s, 64, 2)
+    call = lib.fb_sparse_external_residual
+    args = [FAKE] * 3 + [64, 2, FAKE] + [FAKE] * 6 + [FAKE, ws_bytes, None]
+    assert call(ctypes.byref(s), 2, *args) == fb.FB_ERR_SHAPE                       # bad mode
+    a = list(args); a[3] = 48
+    assert call(ctypes.byref(s), 0, *a) == fb.FB_ERR_UNSUPPORTED                    # key_block % 64
+    a = list(args); a[3] = 0
+    assert call(ctypes.byref(s), 0, *a) == fb.FB_ERR_SHAPE
+    a = list(args); a[4] = -1
+    assert call(ctypes.byref(s), 0, *a) == fb.FB_ERR_SHAPE
+    a = list(args); a[5] = None
+    assert call(ctypes.byref(s), 0, *a) == fb.FB_ERR_NULL                           # topk > 0 needs idx
+    a = list(args); a[6] = None
+    assert call(ctypes.byref(s), 1, *a) == fb.FB_ERR_NULL
+    a = list(args); a[13] = ws_bytes - 1
+    assert call(ctypes.byref(s), 0, *a) == fb.FB_ERR_WORKSPACE
+    a = list(args); a[0] = ODD
+    assert call(ctypes.byref(s), 0, *a) == fb.FB_ERR_ALIGN
+    assert lib.fb_pool_keys(ctypes.byref(s), FAKE, 32, FAKE, None) == fb.FB_ERR_UNSUPPORTED
+    assert lib.fb_pool_keys(ctypes.byref(s), None, 64, FAKE, None) == fb.FB_ERR_NULL
+    assert lib.fb_select_topk(ctypes.byref(s), None, FAKE, 64, 2, FAKE, None) == fb.FB_ERR_NULL
+    assert lib.fb_select_topk(ctypes.byref(s), FAKE, FAKE, 64, 2, ODD, None) == fb.FB_ERR_ALIGN
+    huge = _ok_shape(prefix_len=64 * 16385)
+    assert lib.fb_pool_keys(ctypes.byref(huge), FAKE, 64, FAKE, None) == fb.FB_ERR_UNSUPPORTED
+
+
+def test_status_strings():
+    lib = fb.load_library()
+    seen = {lib.fb_status_string(i).decode() for i in range(8)}
+    assert len(seen) == 8 and all(s.startswith("FB_") for s in seen)
+    assert lib.fb_status_string(99).decode().startswith("unknown")
+
+
+def test_binding_has_no_cpu_fallback(monkeypatch, tmp_path):
+    monkeypatch.setattr(fb, "_lib", None)
+    monkeypatch.setattr(fb, "LIB_PATH", str(tmp_path / "missing.so"))
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        fb.load_library()

@@ -1,0 +1,131 @@
+"""GPU parity of the dense cached-external path against the numpy float64 oracle: every call
+goes through the C ABI (ctypes binding) and is compared element by element on the same seeded
+inputs.  Tolerances: fp32 storage 1e-5 max-abs; bf16 storage 1e-2 abs + 1e-2 rel."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import flashblock_oracle as orc
+from paper_2602_05305_amd import flashblock as fb
+from paper_2602_05305_amd import workloads as wl
+
+import fb_testlib as T
+
+pytestmark = pytest.mark.gpu
+
+
+def _wl(dtype, B, Hq, Hkv, d, P, Bq, S=3, R=2, scale_in=None):
+    if scale_in is None:
+        scale_in = 1.0 if dtype == "f32" else 1.0
+    return wl.Workload(f"case_{dtype}_{B}_{Hq}_{Hkv}_{d}_{P}_{Bq}", B, Hq, Hkv, d, P, Bq, S, R, dtype, scale_in)
+
+
+def _compare_block(w, seed, R=None, n_splits=0, scale=0.0):
+    print(f"[case] {w.name} seed={seed} R={R} n_splits={n_splits}", flush=True)
+    Kp, Vp = wl.make_prefix(w, seed)
+    steps = wl.make_block_steps(w, seed)
+    R = w.refresh if R is None else R
+    ora = orc.run_block_dense(Kp, Vp, steps, R, scale=(scale if scale else None))
+    gpu = T.run_dense_block_gpu(w, Kp, Vp, steps, R=R, n_splits=n_splits, scale=scale)
+    worst = 0.0
+    for t, (g, o) in enumerate(zip(gpu, ora)):
+        worst = max(worst, T.assert_close(g["out"], o["out"], w.dtype, f"{w.name} step {t} out"))
+        T.assert_close(g["lse"], o["lse"], w.dtype, f"{w.name} step {t} lse", lse=True)
+        T.check_partial(g["ext"], o["ext"], w.dtype, f"{w.name} step {t} ext")
+    return worst
+
+
+# ------------------------------------------------------------------ fp32 storage
+def test_tiny_f32_config_all_steps():
+    """BASELINE config 1: B1, 4 heads MHA, d64, prefix 256, block 16, 4 steps, refresh every 4."""
+    w = wl.CONFIGS["tiny_f32"]
+    for seed in (1000, 1001):
+        _compare_block(w, seed)
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,d,P,Bq", [
+    (2, 4, 2, 64, 300, 5),      # GQA, ragged key tail, ragged row chunk
+    (1, 2, 2, 128, 129, 7),     # d = 128, one key past a tile boundary
+    (1, 3, 1, 64, 64, 1),       # single query row, exactly one tile, G = 3
+    (1, 2, 1, 128, 1, 4),       # single prefix key
+    (1, 2, 2, 64, 0, 6),        # empty prefix: out = A_in
+    (1, 8, 2, 64, 1000, 33),    # several tiles and several row chunks
+])
+def test_f32_shapes(B, Hq, Hkv, d, P, Bq):
+    _compare_block(_wl("f32", B, Hq, Hkv, d, P, Bq), seed=7)
+
+
+@pytest.mark.parametrize("n_splits", [1, 2, 3, 7, 16])
+def test_f32_split_counts(n_splits):
+    """Split-KV combine (Eq. 5 folded over splits) including more splits than tiles."""
+    _compare_block(_wl("f32", 1, 4, 2, 64, 450, 9), seed=11, n_splits=n_splits)
+
+
+def test_f32_refresh_every_step_is_exact_attention():
+    """R = 1: every step equals plain attention over [prefix | block]."""
+    w = _wl("f32", 1, 4, 4, 64, 200, 8, S=3, R=1)
+    Kp, Vp = wl.make_prefix(w, 3)
+    steps = wl.make_block_steps(w, 3)
+    gpu = T.run_dense_block_gpu(w, Kp, Vp, steps, R=1)
+    for t, (Q, Kb, Vb) in enumerate(steps):
+        a, lz = orc.full_attention(Q, np.concatenate([Kp, Kb], 2), np.concatenate([Vp, Vb], 2))
+        T.assert_close(gpu[t]["out"], a, "f32", f"R=1 step {t}")
+        T.assert_close(gpu[t]["lse"], lz, "f32", f"R=1 step {t} lse", lse=True)
+
+
+def test_f32_explicit_scale_and_large_scores():
+    w = _wl("f32", 1, 2, 2, 64, 150, 4)     # score std = 8 * 0.5 = 4, extremes beyond +-15
+    _compare_block(w, seed=5, scale=0.5)
+
+
+def test_f32_no_external_partial_means_internal_only():
+    w = _wl("f32", 1, 2, 1, 64, 0, 10)
+    steps = wl.make_block_steps(w, 2)
+    Q, Kb, Vb = steps[0]
+    shape = T.shape_of(w)
+    q, kb, vb = (T.to_dev(x, "f32") for x in (Q, Kb, Vb))
+    out = torch.empty_like(q)
+    lse = torch.empty(q.shape[:3], device=T.DEV)
+    fb.fb_internal_merge(shape, q, kb, vb, None, None, None, out, lse)
+    inn = orc.partial(Q, Kb, Vb)
+    T.assert_close(out.double().cpu().numpy(), orc.normalized(inn), "f32", "internal only")
+    T.assert_close(lse.double().cpu().numpy(), inn["lse"], "f32", "internal only lse", lse=True)
+    out2 = torch.empty_like(q)
+    fb.fb_internal_merge(shape, q, kb, vb, None, None, None, out2, None)     # lse_out is optional
+    assert torch.equal(out, out2)
+
+
+# ------------------------------------------------------------------ bf16 storage
+@pytest.mark.parametrize("B,Hq,Hkv,d,P,Bq", [
+    (1, 8, 2, 128, 1000, 32),    # the LLM GQA group shape: 4 heads x 32 rows = one 128-row tile
+    (2, 4, 4, 64, 333, 48),      # d = 64, MHA, 48 rows: ragged row tile
+    (1, 8, 2, 128, 200, 40),     # 160 rows per group: two row tiles, wavefronts straddle heads
+    (1, 4, 1, 128, 64, 16),      # exactly one key tile
+    (1, 2, 2, 128, 65, 3),       # one key past the tile, tiny block
+    (1, 4, 2, 128, 0, 32),       # empty prefix
+    (1, 2, 2, 64, 2500, 130),    # 130 rows: second row tile has 2 rows
+])
+def test_bf16_shapes(B, Hq, Hkv, d, P, Bq):
+    _compare_block(_wl("bf16", B, Hq, Hkv, d, P, Bq), seed=21)
+
+
+@pytest.mark.parametrize("n_splits", [1, 2, 5, 8, 40])
+def test_bf16_split_counts(n_splits):
+    _compare_block(_wl("bf16", 1, 8, 2, 128, 2000, 32), seed=23, n_splits=n_splits)
+
+
+def test_bf16_llm_scaling_inputs():
+    """Inputs drawn as in the LLM-shaped configs (N(0,1)/sqrt(128)), prefix a few thousand."""
+    w = wl.CONFIGS["llm_32k"].with_(prefix_len=4096 + 37, steps=4, refresh=4)
+    _compare_block(w, seed=2000)
+
+
+def test_bf16_bitwise_reproducible():
+    w = _wl("bf16", 1, 8, 2, 128, 3000, 32)
+    Kp, Vp = wl.make_prefix(w, 31)
+    steps = wl.make_block_steps(w, 31)
+    a = T.run_dense_block_gpu(w, Kp, Vp, steps, n_splits=6)
+    b = T.run_dense_block_gpu(w, Kp, Vp, steps, n_splits=6)
+    for x, y in zip(a, b):
+        assert np.array_equal(x["out"], y["out"]) and np.array_equal(x["ext"]["o"], y["ext"]["o"])
+        assert np.array_equal(x["lse"], y["lse"])
