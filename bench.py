@@ -1,0 +1,313 @@
+#!/usr/bin/env python3
+"""Benchmark of the FlashBlock attention hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llm_32k] [--no-long] [--no-cpu]
+
+A "step" is one diffusion step of one block: fb_internal_merge on every step plus
+fb_external_partial on refresh steps (t mod R == 0).  The headline value is the mean attention
+time per diffusion step on the LLM-shaped 32K-context workload with the prefix K/V resident in
+HBM; consecutive blocks rotate through distinct K/V buffer sets so that the 128 MiB of one set
+cannot be served from the last-level cache.  One JSON line is printed, with
+  roofline      the external-pass kernel against the HBM roofline (HIP events around that
+                kernel, recorded on the stream it runs on, in a second pass over the same loop),
+  cpu_baseline  the numpy float64 oracle timed on the host cores on whole blocks of the same shape,
+and extra objects for the full-recomputation comparison (R = 1 with the same kernels) and
+the 128K-context external pass.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+
+
+class HipEvents:
+    """Raw HIP events through libamdhip64 (already loaded by torch)."""
+
+    def __init__(self):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+
+    def create(self):
+        ev = ctypes.c_void_p()
+        rc = self.hip.hipEventCreate(ctypes.byref(ev))
+        if rc != 0:
+            raise RuntimeError(f"hipEventCreate failed: {rc}")
+        return ev
+
+    def elapsed_ms(self, a, b):
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b)
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed: {rc}")
+        return ms.value
+
+    def destroy(self, ev):
+        self.hip.hipEventDestroy(ev)
+
+
+def external_algorithmic_bytes(w):
+    """Bytes the external pass must move per launch: prefix K and V once, Q once, and the
+    (o, m, lse) partial written once.  Split-KV scratch traffic is overhead, not counted."""
+    esz = 4 if w.dtype == "f32" else 2
+    rows = w.batch * w.n_q_heads * w.block_len
+    return w.kv_bytes + rows * w.head_dim * esz + rows * (w.head_dim + 2) * 4
+
+
+class DeviceBlock:
+    """Device-resident synthetic data of one workload: NSETS prefix K/V sets, one block's per-step
+    (Q, K_block, V_block), the cached partial, outputs and workspace."""
+
+    def __init__(self, w, nsets, seed=1234):
+        import torch
+        from paper_2602_05305_amd import flashblock as fb
+        self.w, self.fb, self.torch = w, fb, torch
+        dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+        g = torch.Generator(device="cuda").manual_seed(seed)
+        kshape = (w.batch, w.n_kv_heads, w.prefix_len, w.head_dim)
+        self.K = [(torch.randn(kshape, device="cuda", generator=g) * w.input_scale).to(dt) for _ in range(nsets)]
+        self.V = [(torch.randn(kshape, device="cuda", generator=g) * w.input_scale).to(dt) for _ in range(nsets)]
+        qs = (w.batch, w.n_q_heads, w.block_len, w.head_dim)
+        ks = (w.batch, w.n_kv_heads, w.block_len, w.head_dim)
+        q = torch.randn(qs, device="cuda", generator=g) * w.input_scale
+        k = torch.randn(ks, device="cuda", generator=g) * w.input_scale
+        v = torch.randn(ks, device="cuda", generator=g) * w.input_scale
+        self.steps = []
+        for _ in range(w.steps):     # cumulative random walk between diffusion steps
+            self.steps.append((q.to(dt).contiguous(), k.to(dt).contiguous(), v.to(dt).contiguous()))
+            q = self.steps[-1][0].float() + w.step_sigma * torch.randn(qs, device="cuda", generator=g)
+            k = self.steps[-1][1].float() + w.step_sigma * torch.randn(ks, device="cuda", generator=g)
+            v = self.steps[-1][2].float() + w.step_sigma * torch.randn(ks, device="cuda", generator=g)
+        self.shape = fb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.block_len, w.prefix_len, w.dtype)
+        rows = (w.batch, w.n_q_heads, w.block_len)
+        self.o = torch.empty(rows + (w.head_dim,), device="cuda", dtype=torch.float32)
+        self.m = torch.empty(rows, device="cuda", dtype=torch.float32)
+        self.lse = torch.empty(rows, device="cuda", dtype=torch.float32)
+        self.out = torch.empty(qs, device="cuda", dtype=dt)
+        self.ws = torch.empty(fb.fb_workspace_bytes(self.shape), device="cuda", dtype=torch.uint8)
+        self.nsets = nsets
+
+    def step(self, t, kv_set, R, prof=None):
+        """One diffusion step t of a block whose prefix is K/V set kv_set."""
+        fb = self.fb
+        q, kb, vb = self.steps[t]
+        if t % R == 0:
+            if prof is None:
+                fb.fb_external_partial(self.shape, q, self.K[kv_set], self.V[kv_set], self.o, self.m, self.lse, self.ws)
+            else:
+                fb.fb_external_partial_prof(self.shape, q, self.K[kv_set], self.V[kv_set], self.o, self.m, self.lse,
+                                            0, self.ws, prof[0], prof[1], prof[2])
+        fb.fb_internal_merge(self.shape, q, kb, vb, self.o, self.m, self.lse, self.out, None)
+
+    def run_eager(self, n_steps, R, first_step=0):
+        S = self.w.steps
+        for i in range(first_step, first_step + n_steps):
+            self.step(i % S, (i // S) % self.nsets, R)
+
+    def make_graphs(self, R):
+        """One HIP graph per K/V set holding a whole block (S steps)."""
+        torch = self.torch
+        graphs = []
+        side = torch.cuda.Stream()
+        for s in range(self.nsets):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                for t in range(self.w.steps):
+                    self.step(t, s, R)
+            graphs.append(g)
+        return graphs
+
+
+def time_steps(dev, n_steps, warmup, R, use_graph):
+    """Wall-clock of exactly n_steps diffusion steps (whole blocks replayed as graphs, any
+    remainder eagerly), after `warmup` untimed steps.  Returns seconds."""
+    torch = dev.torch
+    S = dev.w.steps
+    dev.run_eager(S, R)            # first launches (one-time kernel attribute calls) stay outside any capture
+    torch.cuda.synchronize()
+    graphs = dev.make_graphs(R) if use_graph else None
+
+    def run(n, start):
+        if graphs is None:
+            dev.run_eager(n, R, start)
+            return
+        blocks, rem = divmod(n, S)
+        b0 = start // S
+        for b in range(blocks):
+            graphs[(b0 + b) % dev.nsets].replay()
+        if rem:
+            dev.run_eager(rem, R, (b0 + blocks) * S)
+
+    run(warmup, 0)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(n_steps, 0)
+    torch.cuda.synchronize()
+    return time.perf_counter() - t0
+
+
+def profile_external(dev, n_blocks, R):
+    """Second pass over the same loop with HIP events around the external pass's kernels.
+    Returns mean ms of (attention kernel, combine kernel, whole external call) and of a whole
+    refresh step and reuse step."""
+    torch = dev.torch
+    hev = HipEvents()
+    S = dev.w.steps
+    recs = []
+    for b in range(n_blocks):
+        evs = [hev.create() for _ in range(3)]
+        step_ev = [torch.cuda.Event(enable_timing=True) for _ in range(S + 1)]
+        step_ev[0].record()
+        for t in range(S):
+            dev.step(t, b % dev.nsets, R, prof=evs if t == 0 else None)
+            step_ev[t + 1].record()
+        recs.append((evs, step_ev))
+    torch.cuda.synchronize()
+    attn, comb, refresh, reuse = [], [], [], []
+    for evs, step_ev in recs[1:] if len(recs) > 1 else recs:     # first block is warm-up
+        attn.append(hev.elapsed_ms(evs[0], evs[1]))
+        comb.append(hev.elapsed_ms(evs[1], evs[2]))
+        for t in range(S):
+            (refresh if t % R == 0 else reuse).append(step_ev[t].elapsed_time(step_ev[t + 1]))
+    for evs, _ in recs:
+        for e in evs:
+            hev.destroy(e)
+    mean = lambda x: sum(x) / max(1, len(x))
+    med = lambda x: sorted(x)[len(x) // 2] if x else 0.0
+    return {"attn_ms": mean(attn), "attn_ms_min": min(attn), "combine_ms": mean(comb),
+            "refresh_step_ms": med(refresh), "reuse_step_ms": med(reuse), "launches": len(attn)}
+
+
+def roofline_obj(w, attn_ms, traffic=None):
+    alg = external_algorithmic_bytes(w)
+    ach = alg / (attn_ms * 1e-3) / 1e9
+    return {"bound": "hbm", "kernel": "fb::attn_bf16_kernel<128, dense> (external pass)",
+            "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": traffic,
+            "algorithmic_bytes_per_launch": alg, "avg_launch_us": round(attn_ms * 1e3, 2)}
+
+
+def cpu_baseline(w, budget_s=12.0):
+    """The numpy float64 oracle, as it stands, on whole blocks of the workload's full shape."""
+    import numpy as np  # noqa: F401
+    from oracle import flashblock_oracle as orc
+    from paper_2602_05305_amd import workloads as wl
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    Kp, Vp = wl.make_prefix(w, 1)
+    steps = wl.make_block_steps(w, 1)
+    n_blocks, t0 = 0, time.perf_counter()
+    while True:
+        orc.run_block_dense(Kp, Vp, steps, w.refresh)
+        n_blocks += 1
+        el = time.perf_counter() - t0
+        if el >= budget_s or n_blocks >= 50:
+            break
+    us = el / (n_blocks * w.steps) * 1e6
+    return {"value": round(us, 1), "unit": "us/step", "cores": int(threads), "kind": "oracle",
+            "sample": f"{n_blocks} whole block(s) of {w.steps} diffusion steps (1 refresh + {w.steps - 1} reuse, R={w.refresh}) "
+                      f"at the full {w.name} shape, numpy float64, {el:.1f} s",
+            "host_cores_visible": len(os.sched_getaffinity(0))}
+
+
+def describe(w):
+    return (f"{w.name}: batch {w.batch}, {w.n_q_heads} q heads / {w.n_kv_heads} kv heads, head_dim {w.head_dim}, "
+            f"prefix {w.prefix_len}, block {w.block_len}, {w.steps} steps/block, refresh every {w.refresh}, {w.dtype}")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=4000)
+    ap.add_argument("--warmup", type=int, default=400)
+    ap.add_argument("--workload", default="llm_32k")
+    ap.add_argument("--no-graph", action="store_true", help="launch every step eagerly instead of per-block HIP graphs")
+    ap.add_argument("--no-long", action="store_true", help="skip the 128K-context external-pass measurement")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on exactly one GPU (the path has no multi-GPU part); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2602_05305_amd import flashblock as fb
+    from paper_2602_05305_amd import workloads as wl
+    fb.load_library()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    w = wl.CONFIGS[args.workload]
+    K, W = args.steps, args.warmup
+    nsets = max(2, min(4, int(-(-600e6 // w.kv_bytes))))     # working set well beyond the last-level cache
+    dev = DeviceBlock(w, nsets)
+
+    use_graph = not args.no_graph
+    sec = time_steps(dev, K, W, w.refresh, use_graph)
+    us_step = sec / K * 1e6
+    sec_full = time_steps(dev, K, W, 1, use_graph)           # full recomputation: refresh on every step
+    us_full = sec_full / K * 1e6
+    sec_eager = time_steps(dev, min(K, 800), min(W, 80), w.refresh, False)
+    prof = profile_external(dev, 41, w.refresh)
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{w.name}.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+    line = {
+        "metric": "attention us per diffusion step (cached block-external attention, 32K context); "
+                  "external-pass HBM GB/s in roofline / external_128k",
+        "value": round(us_step, 3), "unit": "us/step", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(us_step / 1e3, 6), "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": describe(w), "kv_buffer_sets_rotated": nsets,
+                   "launch": "one HIP graph per block" if use_graph else "eager",
+                   "external_splits": fb.fb_external_splits(dev.shape)},
+        "roofline": roofline_obj(w, prof["attn_ms"], traffic),
+        "steps_detail": {"refresh_step_us": round(prof["refresh_step_ms"] * 1e3, 2),
+                         "reuse_step_us": round(prof["reuse_step_ms"] * 1e3, 2),
+                         "external_attn_kernel_us": round(prof["attn_ms"] * 1e3, 2),
+                         "external_combine_kernel_us": round(prof["combine_ms"] * 1e3, 2),
+                         "eager_us_per_step": round(sec_eager / min(K, 800) * 1e6, 3)},
+        "full_recompute": {"us_per_step": round(us_full, 3), "speedup_cached_vs_full": round(us_full / us_step, 3),
+                           "note": "same kernels with refresh interval 1"},
+    }
+    del dev
+    torch.cuda.empty_cache()
+
+    if not args.no_long:
+        wl128 = wl.CONFIGS["long_128k"]
+        d2 = DeviceBlock(wl128, 2)
+        for _ in range(3):
+            d2.step(0, 0, wl128.refresh)
+        p2 = profile_external(d2, 21, wl128.refresh)
+        r2 = roofline_obj(wl128, p2["attn_ms"])
+        r2["workload"] = describe(wl128)
+        r2["external_call_us"] = round((p2["attn_ms"] + p2["combine_ms"]) * 1e3, 2)
+        r2["refresh_step_us"] = round(p2["refresh_step_ms"] * 1e3, 2)
+        r2["reuse_step_us"] = round(p2["reuse_step_ms"] * 1e3, 2)
+        line["external_128k"] = r2
+        del d2
+        torch.cuda.empty_cache()
+
+    if not args.no_cpu:
+        line["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -127,6 +127,16 @@ fb_status fb_external_partial_ex(const fb_shape* shape, const void* q, const voi
                                  float* lse_part, int32_t n_splits, void* workspace,
                                  size_t workspace_bytes, void* hip_stream);
 
+/* Profiling aid: fb_external_partial_ex that also records three caller-created HIP events
+ * (hipEvent_t cast to void*, created with timing enabled) on hip_stream: ev_begin before the
+ * streaming attention kernel, ev_attn_end between it and the split combine, ev_end after the
+ * combine.  Any of the three may be NULL.  Results are identical to fb_external_partial_ex. */
+fb_status fb_external_partial_prof(const fb_shape* shape, const void* q, const void* k_prefix,
+                                   const void* v_prefix, float* o_part, float* m_part,
+                                   float* lse_part, int32_t n_splits, void* workspace,
+                                   size_t workspace_bytes, void* ev_begin, void* ev_attn_end,
+                                   void* ev_end, void* hip_stream);
+
 /*
  * One diffusion step with a cached external partial (Algorithm 1): block-internal attention
  * of q against the block's own current k_block/v_block, bidirectional (Eq. 7), composed in

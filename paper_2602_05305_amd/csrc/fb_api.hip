@@ -156,10 +156,10 @@ size_t fb_workspace_bytes(const fb_shape* shape, int32_t key_block, int32_t topk
   return t > 0 ? t : 256;
 }
 
-fb_status fb_external_partial_ex(const fb_shape* shape, const void* q, const void* k_prefix,
-                                 const void* v_prefix, float* o_part, float* m_part, float* lse_part,
-                                 int32_t n_splits, void* workspace, size_t workspace_bytes,
-                                 void* hip_stream) {
+fb_status fb_external_partial_prof(const fb_shape* shape, const void* q, const void* k_prefix,
+                                   const void* v_prefix, float* o_part, float* m_part, float* lse_part,
+                                   int32_t n_splits, void* workspace, size_t workspace_bytes,
+                                   void* ev_begin, void* ev_attn_end, void* ev_end, void* hip_stream) {
   fb_status st = check_shape(shape);
   if (st != FB_OK) return st;
   if (!q || !o_part || !m_part || !lse_part) return FB_ERR_NULL;
@@ -176,8 +176,11 @@ fb_status fb_external_partial_ex(const fb_shape* shape, const void* q, const voi
   char* ws = (char*)workspace;
   fb::PassParams p = base_pass(shape, q, k_prefix, v_prefix, shape->prefix_len, ns);
   p.ws_o = (float*)(ws + w.o[0]); p.ws_m = (float*)(ws + w.m[0]); p.ws_l = (float*)(ws + w.l[0]);
-  hipError_t e = launch_attn(shape, p, fb::kPassDense, stream);
+  hipError_t e = hipSuccess;
+  if (ev_begin && (e = hipEventRecord((hipEvent_t)ev_begin, stream)) != hipSuccess) return hip_fail(e);
+  e = launch_attn(shape, p, fb::kPassDense, stream);
   if (e != hipSuccess) return hip_fail(e);
+  if (ev_attn_end && (e = hipEventRecord((hipEvent_t)ev_attn_end, stream)) != hipSuccess) return hip_fail(e);
 
   fb::CombineParams c;
   memset(&c, 0, sizeof(c));
@@ -186,7 +189,16 @@ fb_status fb_external_partial_ex(const fb_shape* shape, const void* q, const voi
   c.o = o_part; c.m = m_part; c.lse = lse_part;
   e = fb::launch_combine(c, stream);
   if (e != hipSuccess) return hip_fail(e);
+  if (ev_end && (e = hipEventRecord((hipEvent_t)ev_end, stream)) != hipSuccess) return hip_fail(e);
   return FB_OK;
+}
+
+fb_status fb_external_partial_ex(const fb_shape* shape, const void* q, const void* k_prefix,
+                                 const void* v_prefix, float* o_part, float* m_part, float* lse_part,
+                                 int32_t n_splits, void* workspace, size_t workspace_bytes,
+                                 void* hip_stream) {
+  return fb_external_partial_prof(shape, q, k_prefix, v_prefix, o_part, m_part, lse_part, n_splits,
+                                  workspace, workspace_bytes, nullptr, nullptr, nullptr, hip_stream);
 }
 
 fb_status fb_external_partial(const fb_shape* shape, const void* q, const void* k_prefix,

@@ -50,10 +50,74 @@ struct Cfg {
   static constexpr int NDB = D / 32;                // 32-wide output column blocks
 };
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef const __attribute__((address_space(1))) u32x4* gptr128;   // global address space: global_load_dwordx4
+
 struct TileRegs {
-  uint4 k[4];
-  uint4 v[4];
+  u32x4 k[4];
+  u32x4 v[4];
 };
+
+__device__ __forceinline__ u32x4 gload128(const __bf16* p) { return *(gptr128)(p); }
+
+// Global -> registers for one 64-key tile.  Keys past the end of the key range are clamped to
+// the last key: the loads stay in bounds and branch-free, the duplicated rows are finite, and
+// their scores are masked to -inf before the softmax so they never contribute.
+template <int D>
+__device__ __forceinline__ void tile_load(TileRegs& t, const __bf16* __restrict__ K,
+                                          const __bf16* __restrict__ V, int k0, int nkeys, int tid) {
+  using C = Cfg<D>;
+  const int last = nkeys - 1;
+#pragma unroll
+  for (int i = 0; i < C::NK; ++i) {
+    const int c = tid + 256 * i;
+    const int row = c / (D / 8), col = c % (D / 8);
+    const int key = min(k0 + row, last);
+    t.k[i] = gload128(K + (size_t)key * D + col * 8);
+  }
+  if (C::VUNITS >= 256 || tid < C::VUNITS) {
+    const int doct = tid % (D / 8), kq = tid / (D / 8);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int key = min(k0 + 4 * kq + j, last);
+      t.v[j] = gload128(V + (size_t)key * D + doct * 8);
+    }
+  }
+}
+
+template <int D>
+__device__ __forceinline__ void tile_store(const TileRegs& t, unsigned char* __restrict__ stage, int tid) {
+  using C = Cfg<D>;
+  unsigned char* Ks = stage;
+  unsigned char* Vt = stage + C::KBYTES;
+#pragma unroll
+  for (int i = 0; i < C::NK; ++i) {
+    const int c = tid + 256 * i;
+    const int row = c / (D / 8), col = c % (D / 8);
+    *(u32x4*)(Ks + row * C::KSTR + col * 16) = t.k[i];
+  }
+  if (C::VUNITS >= 256 || tid < C::VUNITS) {
+    const int doct = tid % (D / 8), kq = tid / (D / 8);
+    // key quad kq of a 16-key group goes to slot quad {0,2,1,3}[kq%4]: the order in which the
+    // 32x32 score accumulators hand keys to the two lane halves.
+    const int g4 = kq & 3;
+    const int sq = ((g4 & 1) << 1) | (g4 >> 1);
+    const int slot = 16 * (kq >> 2) + 4 * sq;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const uint32_t a = t.v[0][w], b = t.v[1][w], c = t.v[2][w], d = t.v[3][w];
+      u32x2 lo, hi;   // column 2w (low halves) and 2w+1 (high halves) of the 4 keys
+      lo.x = (a & 0xffffu) | (b << 16);
+      lo.y = (c & 0xffffu) | (d << 16);
+      hi.x = (a >> 16) | (b & 0xffff0000u);
+      hi.y = (c >> 16) | (d & 0xffff0000u);
+      const int dcol = doct * 8 + 2 * w;
+      *(u32x2*)(Vt + dcol * C::VSTR + slot * 2) = lo;
+      *(u32x2*)(Vt + (dcol + 1) * C::VSTR + slot * 2) = hi;
+    }
+  }
+}
 
 // Running softmax state of the 32 rows a wavefront owns (one row per lane pair l, l^32).
 template <int NDB>
@@ -69,64 +133,6 @@ struct WaveState {
       for (int r = 0; r < 16; ++r) o[i][r] = 0.f;
   }
 };
-
-template <int D>
-__device__ __forceinline__ void tile_load(TileRegs& t, const __bf16* __restrict__ K,
-                                          const __bf16* __restrict__ V, int k0, int nkeys, int tid) {
-  using C = Cfg<D>;
-  const uint4 z = make_uint4(0u, 0u, 0u, 0u);
-#pragma unroll
-  for (int i = 0; i < C::NK; ++i) {
-    const int c = tid + 256 * i;
-    const int row = c / (D / 8), col = c % (D / 8);
-    const int key = k0 + row;
-    t.k[i] = (key < nkeys) ? *(const uint4*)(K + (size_t)key * D + col * 8) : z;
-  }
-  if (tid < C::VUNITS) {
-    const int doct = tid % (D / 8), kq = tid / (D / 8);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int key = k0 + 4 * kq + j;
-      t.v[j] = (key < nkeys) ? *(const uint4*)(V + (size_t)key * D + doct * 8) : z;
-    }
-  }
-}
-
-template <int D>
-__device__ __forceinline__ void tile_store(const TileRegs& t, unsigned char* __restrict__ stage, int tid) {
-  using C = Cfg<D>;
-  unsigned char* Ks = stage;
-  unsigned char* Vt = stage + C::KBYTES;
-#pragma unroll
-  for (int i = 0; i < C::NK; ++i) {
-    const int c = tid + 256 * i;
-    const int row = c / (D / 8), col = c % (D / 8);
-    *(uint4*)(Ks + row * C::KSTR + col * 16) = t.k[i];
-  }
-  if (tid < C::VUNITS) {
-    const int doct = tid % (D / 8), kq = tid / (D / 8);
-    // key quad kq of a 16-key group goes to slot quad {0,2,1,3}[kq%4]: the order in which the
-    // 32x32 score accumulators hand keys to the two lane halves.
-    const int g4 = kq & 3;
-    const int sq = ((g4 & 1) << 1) | (g4 >> 1);
-    const int slot = 16 * (kq >> 2) + 4 * sq;
-    const uint32_t a[4] = {t.v[0].x, t.v[0].y, t.v[0].z, t.v[0].w};
-    const uint32_t b[4] = {t.v[1].x, t.v[1].y, t.v[1].z, t.v[1].w};
-    const uint32_t c[4] = {t.v[2].x, t.v[2].y, t.v[2].z, t.v[2].w};
-    const uint32_t d[4] = {t.v[3].x, t.v[3].y, t.v[3].z, t.v[3].w};
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      uint2 lo, hi;   // column 2w (low halves) and 2w+1 (high halves) of the 4 keys
-      lo.x = (a[w] & 0xffffu) | (b[w] << 16);
-      lo.y = (c[w] & 0xffffu) | (d[w] << 16);
-      hi.x = (a[w] >> 16) | (b[w] & 0xffff0000u);
-      hi.y = (c[w] >> 16) | (d[w] & 0xffff0000u);
-      const int dcol = doct * 8 + 2 * w;
-      *(uint2*)(Vt + dcol * C::VSTR + slot * 2) = lo;
-      *(uint2*)(Vt + (dcol + 1) * C::VSTR + slot * 2) = hi;
-    }
-  }
-}
 
 // One 64-key tile for one wavefront: scores, online softmax update, value accumulation.
 //   lane_on : this lane's query row takes part in this tile for this accumulator set
@@ -167,7 +173,12 @@ __device__ __forceinline__ void tile_compute(WaveState<Cfg<D>::NDB>& st, const b
     for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[kb][r]);
   tmax = lane_on ? tmax * scale_log2 : -INFINITY;
   tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-  const float m_new = fmaxf(st.m, tmax);
+  // Lazy reference update: the running reference m only moves when the tile maximum exceeds it
+  // by more than kLazy (log2 units).  Weights then stay below 2^kLazy, which fp32 sums and the
+  // relative precision of bf16 weights absorb, and (o, l, m) remain exactly paired; in return
+  // the 16*NDB accumulator registers are rescaled on a small fraction of the tiles only.
+  constexpr float kLazy = 8.f;
+  const float m_new = (tmax > st.m + kLazy) ? tmax : st.m;
   const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
   const float alpha = __builtin_amdgcn_exp2f(st.m - m_use);
   float lsum = 0.f;
@@ -246,8 +257,8 @@ __global__ __launch_bounds__(256, (MODE == kPassSparseRefresh) ? 1 : 2) void att
   bf16x8 qreg[C::NKS];
 #pragma unroll
   for (int ks = 0; ks < C::NKS; ++ks) {
-    uint4 u = make_uint4(0u, 0u, 0u, 0u);
-    if (row_ok) u = *(const uint4*)(Q + grow * D + ks * 16 + 8 * h);
+    u32x4 u = {0u, 0u, 0u, 0u};
+    if (row_ok) u = gload128(Q + grow * D + ks * 16 + 8 * h);
     qreg[ks] = __builtin_bit_cast(bf16x8, u);
   }
 
@@ -283,41 +294,44 @@ __global__ __launch_bounds__(256, (MODE == kPassSparseRefresh) ? 1 : 2) void att
   WaveState<(MODE == kPassSparseRefresh) ? C::NDB : 1> res;
   res.init();
 
-  TileRegs regs;
-  uint32_t mask_cur = 0, mask_next = 0;
-  int k0_cur = 0, k0_next = 0;
-  if (tr.begin < tr.end) {
-    k0_cur = entry_k0(tr.begin, mask_cur);
+  // Steady state per iteration: issue the global loads of tile i+1 (they stay in flight in
+  // registers), compute tile i from LDS, park tile i+1 in the other LDS stage, one barrier.
+  auto compute = [&](const unsigned char* stage, int k0, uint32_t mask) {
+    const int nvalid = min(C::KT, nkeys - k0);      // <= 0 only for a reuse-list tile past the end
+    if constexpr (MODE == kPassSparseReuse) {
+      if (nvalid <= 0) return;
+    }
+    if constexpr (MODE == kPassSparseRefresh) {
+      const bool on = row_ok && (mask & my_bit);
+      if (__any(on)) tile_compute<D>(sel, qreg, stage, p.scale_log2, on, nvalid, l32, h);
+      const bool off = row_ok && !(mask & my_bit);
+      if (__any(off)) tile_compute<D>(res, qreg, stage, p.scale_log2, off, nvalid, l32, h);
+    } else if constexpr (MODE == kPassSparseReuse) {
+      const bool on = row_ok && (mask & my_bit);
+      if (__any(on)) tile_compute<D>(sel, qreg, stage, p.scale_log2, on, nvalid, l32, h);
+    } else {
+      tile_compute<D>(sel, qreg, stage, p.scale_log2, true, nvalid, l32, h);
+    }
+  };
+
+  const int ntiles = tr.end - tr.begin;
+  if (ntiles > 0) {
+    TileRegs regs;
+    uint32_t mask_cur = 0, mask_next = 0;
+    int k0_cur = entry_k0(tr.begin, mask_cur), k0_next = 0;
     tile_load<D>(regs, K, V, k0_cur, nkeys, tid);
     tile_store<D>(regs, smem, tid);
-  }
-  __syncthreads();
-  for (int e = tr.begin; e < tr.end; ++e) {
-    const int cur = (e - tr.begin) & 1;
-    const bool more = (e + 1 < tr.end);
-    if (more) {
-      k0_next = entry_k0(e + 1, mask_next);
-      tile_load<D>(regs, K, V, k0_next, nkeys, tid);
-    }
-    const unsigned char* stage = smem + cur * C::STAGE;
-    const int nvalid = min(C::KT, nkeys - k0_cur);      // <= 0 only for a reuse-list tile past the end
-    if (nvalid > 0) {
-      if constexpr (MODE == kPassSparseRefresh) {
-        const bool on = row_ok && (mask_cur & my_bit);
-        if (__any(on)) tile_compute<D>(sel, qreg, stage, p.scale_log2, on, nvalid, l32, h);
-        const bool off = row_ok && !(mask_cur & my_bit);
-        if (__any(off)) tile_compute<D>(res, qreg, stage, p.scale_log2, off, nvalid, l32, h);
-      } else if constexpr (MODE == kPassSparseReuse) {
-        const bool on = row_ok && (mask_cur & my_bit);
-        if (__any(on)) tile_compute<D>(sel, qreg, stage, p.scale_log2, on, nvalid, l32, h);
-      } else {
-        tile_compute<D>(sel, qreg, stage, p.scale_log2, true, nvalid, l32, h);
-      }
-    }
-    if (more) tile_store<D>(regs, smem + (cur ^ 1) * C::STAGE, tid);
     __syncthreads();
-    k0_cur = k0_next;
-    mask_cur = mask_next;
+    for (int i = 0; i < ntiles - 1; ++i) {
+      k0_next = entry_k0(tr.begin + i + 1, mask_next);
+      tile_load<D>(regs, K, V, k0_next, nkeys, tid);
+      compute(smem + (i & 1) * C::STAGE, k0_cur, mask_cur);
+      tile_store<D>(regs, smem + ((i + 1) & 1) * C::STAGE, tid);
+      __syncthreads();
+      k0_cur = k0_next;
+      mask_cur = mask_next;
+    }
+    compute(smem + ((ntiles - 1) & 1) * C::STAGE, k0_cur, mask_cur);
   }
 
   // ---------------------------------------------------------------- epilogue
@@ -349,10 +363,10 @@ __global__ __launch_bounds__(256, (MODE == kPassSparseRefresh) ? 1 : 2) void att
         float r[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) r[i] = (sel.o[db][4 * q4 + i] * wi + e[i] * we) * inv;
-        uint2 pk;
+        u32x2 pk;
         pk.x = pack_bf16x2(r[0], r[1]);
         pk.y = pack_bf16x2(r[2], r[3]);
-        *(uint2*)(out + d0) = pk;
+        *(u32x2*)(out + d0) = pk;
       }
     if (p.lse_out != nullptr && h == 0) p.lse_out[grow] = den > 0.f ? (M2 + log2f(den)) * kLn2 : -INFINITY;
   } else {

@@ -72,28 +72,18 @@ __device__ __forceinline__ void emit(const Folded& f, float* __restrict__ o, flo
   }
 }
 
-__global__ __launch_bounds__(256) void combine_kernel(const CombineParams p) {
-  const int per_row = p.D / 4;
-  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= (size_t)p.rows * per_row) return;
-  const size_t row = idx / per_row;
-  const int c4 = (int)(idx % per_row);
+__device__ __forceinline__ Folded empty_folded() {
+  Folded f;
+  f.o = make_float4(0.f, 0.f, 0.f, 0.f);
+  f.m2 = -INFINITY;
+  f.l = 0.f;
+  return f;
+}
 
-  Folded sel;
-  if (p.ws_o != nullptr && p.nsplit > 0) {
-    sel = fold_splits(p.ws_o, p.ws_m, p.ws_l, p.nsplit, p.rows, row, p.D, c4);
-  } else {
-    sel.o = make_float4(0.f, 0.f, 0.f, 0.f);
-    sel.m2 = -INFINITY;
-    sel.l = 0.f;
-  }
-  Folded res;
-  res.o = make_float4(0.f, 0.f, 0.f, 0.f);
-  res.m2 = -INFINITY;
-  res.l = 0.f;
-  if (p.ws_o2 != nullptr) {           // refresh: residual set from this pass
-    res = fold_splits(p.ws_o2, p.ws_m2, p.ws_l2, p.nsplit, p.rows, row, p.D, c4);
-  } else if (p.res_in_o != nullptr) { // reuse: cached residual, natural-log units
+// Everything after the split fold: residual in/out, total, emission (shared by both kernels).
+__device__ __forceinline__ void finish_row(const CombineParams& p, const Folded& sel, Folded res,
+                                           bool have_res_set, size_t row, int c4) {
+  if (!have_res_set && p.res_in_o != nullptr) {   // reuse: cached residual, natural-log units
     const float lse = p.res_in_lse[row];
     if (lse != -INFINITY) {
       const float m = p.res_in_m[row];
@@ -105,6 +95,63 @@ __global__ __launch_bounds__(256) void combine_kernel(const CombineParams p) {
   if (p.res_out_o != nullptr) emit(res, p.res_out_o, p.res_out_m, p.res_out_lse, row, p.D, c4);
   const Folded total = fold_two(sel, res);
   emit(total, p.o, p.m, p.lse, row, p.D, c4);
+}
+
+// Few splits: one thread per (row, 4 columns) walks the splits.
+__global__ __launch_bounds__(256) void combine_kernel(const CombineParams p) {
+  const int per_row = p.D / 4;
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (size_t)p.rows * per_row) return;
+  const size_t row = idx / per_row;
+  const int c4 = (int)(idx % per_row);
+  Folded sel = empty_folded(), res = empty_folded();
+  if (p.ws_o != nullptr && p.nsplit > 0) sel = fold_splits(p.ws_o, p.ws_m, p.ws_l, p.nsplit, p.rows, row, p.D, c4);
+  const bool have_res_set = p.ws_o2 != nullptr;
+  if (have_res_set) res = fold_splits(p.ws_o2, p.ws_m2, p.ws_l2, p.nsplit, p.rows, row, p.D, c4);
+  finish_row(p, sel, res, have_res_set, row, c4);
+}
+
+// Many splits: one workgroup per row; NSL = 256/(D/4) thread groups each fold every NSL-th split
+// (independent 16-byte loads in flight), then one group folds the NSL results in fixed order.
+__device__ __forceinline__ Folded fold_strided(const float* __restrict__ ws_o, const float* __restrict__ ws_m,
+                                               const float* __restrict__ ws_l, int nsplit, size_t rows,
+                                               size_t row, int D, int c4, int first, int stride) {
+  Folded f = empty_folded();
+  float M = -INFINITY;
+  for (int s = first; s < nsplit; s += stride) M = fmaxf(M, ws_m[(size_t)s * rows + row]);
+  f.m2 = M;
+  if (M == -INFINITY) return f;
+#pragma unroll 4
+  for (int s = first; s < nsplit; s += stride) {
+    const size_t r = (size_t)s * rows + row;
+    const float w = exp2f(ws_m[r] - M);
+    const float4 o = *(const float4*)(ws_o + r * D + c4 * 4);
+    f.o.x = fmaf(o.x, w, f.o.x);
+    f.o.y = fmaf(o.y, w, f.o.y);
+    f.o.z = fmaf(o.z, w, f.o.z);
+    f.o.w = fmaf(o.w, w, f.o.w);
+    f.l = fmaf(ws_l[r], w, f.l);
+  }
+  return f;
+}
+
+__global__ __launch_bounds__(256) void combine_wide_kernel(const CombineParams p) {
+  __shared__ Folded sh[2][256];
+  const int per_row = p.D / 4, nsl = 256 / per_row;
+  const int tid = threadIdx.x, sl = tid / per_row, c4 = tid % per_row;
+  const size_t row = blockIdx.x;
+  const bool have_res_set = p.ws_o2 != nullptr;
+  sh[0][tid] = fold_strided(p.ws_o, p.ws_m, p.ws_l, p.nsplit, p.rows, row, p.D, c4, sl, nsl);
+  if (have_res_set) sh[1][tid] = fold_strided(p.ws_o2, p.ws_m2, p.ws_l2, p.nsplit, p.rows, row, p.D, c4, sl, nsl);
+  __syncthreads();
+  if (sl != 0) return;
+  Folded sel = sh[0][c4], res = empty_folded();
+  for (int j = 1; j < nsl; ++j) sel = fold_two(sel, sh[0][j * per_row + c4]);
+  if (have_res_set) {
+    res = sh[1][c4];
+    for (int j = 1; j < nsl; ++j) res = fold_two(res, sh[1][j * per_row + c4]);
+  }
+  finish_row(p, sel, res, have_res_set, row, c4);
 }
 
 // ------------------------------------------------------------------------------ pooling
@@ -240,7 +287,10 @@ __global__ __launch_bounds__(256) void build_masks_kernel(const MaskParams p) {
 hipError_t launch_combine(const CombineParams& p, hipStream_t s) {
   const size_t n = (size_t)p.rows * (p.D / 4);
   if (n == 0) return hipSuccess;
-  hipLaunchKernelGGL(combine_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p);
+  if (p.nsplit >= 8 && p.ws_o != nullptr)
+    hipLaunchKernelGGL(combine_wide_kernel, dim3((unsigned)p.rows), dim3(256), 0, s, p);
+  else
+    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p);
   return hipGetLastError();
 }
 

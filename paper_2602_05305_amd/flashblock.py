@@ -43,6 +43,7 @@ _SIGNATURES = {
     "fb_workspace_bytes": (c_size_t, [POINTER(fb_shape), c_int32, c_int32, c_int32]),
     "fb_external_partial": (c_int, [POINTER(fb_shape)] + [c_void_p] * 7 + [c_size_t, c_void_p]),
     "fb_external_partial_ex": (c_int, [POINTER(fb_shape)] + [c_void_p] * 6 + [c_int32, c_void_p, c_size_t, c_void_p]),
+    "fb_external_partial_prof": (c_int, [POINTER(fb_shape)] + [c_void_p] * 6 + [c_int32, c_void_p, c_size_t] + [c_void_p] * 4),
     "fb_internal_merge": (c_int, [POINTER(fb_shape)] + [c_void_p] * 9),
     "fb_pool_keys": (c_int, [POINTER(fb_shape), c_void_p, c_int32, c_void_p, c_void_p]),
     "fb_select_topk": (c_int, [POINTER(fb_shape), c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p]),
@@ -124,6 +125,16 @@ def fb_external_partial_ex(shape, q, k_prefix, v_prefix, o_part, m_part, lse_par
                                                _ptr(o_part), _ptr(m_part), _ptr(lse_part), n_splits, _ptr(workspace),
                                                workspace.numel() * workspace.element_size(), _stream(stream))
     _check(st, "fb_external_partial_ex")
+
+
+def fb_external_partial_prof(shape, q, k_prefix, v_prefix, o_part, m_part, lse_part, n_splits, workspace,
+                             ev_begin, ev_attn_end, ev_end, stream=None):
+    """ev_*: raw hipEvent_t handles (ints / c_void_p) or None."""
+    st = load_library().fb_external_partial_prof(ctypes.byref(shape), _ptr(q), _ptr(k_prefix), _ptr(v_prefix),
+                                                 _ptr(o_part), _ptr(m_part), _ptr(lse_part), n_splits, _ptr(workspace),
+                                                 workspace.numel() * workspace.element_size(), ev_begin, ev_attn_end,
+                                                 ev_end, _stream(stream))
+    _check(st, "fb_external_partial_prof")
 
 
 def fb_internal_merge(shape, q, k_block, v_block, o_part, m_part, lse_part, out, lse_out=None, stream=None):
