@@ -237,6 +237,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch every step eagerly instead of per-block HIP graphs")
     ap.add_argument("--no-long", action="store_true", help="skip the 128K-context external-pass measurement")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--profile-external", type=int, default=0, metavar="N",
+                    help="only run N external passes of the workload (for rocprofv3), print nothing else")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (the path has no multi-GPU part); use --gpus 1",
@@ -252,6 +254,13 @@ def main():
         sys.exit(3)
     torch.cuda.set_device(0)
     w = wl.CONFIGS[args.workload]
+    if args.profile_external > 0:
+        d = DeviceBlock(w, max(2, min(4, int(-(-600e6 // w.kv_bytes)))))
+        for i in range(args.profile_external):
+            d.step(0, i % d.nsets, w.refresh)
+        torch.cuda.synchronize()
+        print(f"ran {args.profile_external} refresh steps of {w.name}")
+        return
     K, W = args.steps, args.warmup
     nsets = max(2, min(4, int(-(-600e6 // w.kv_bytes))))     # working set well beyond the last-level cache
     dev = DeviceBlock(w, nsets)

@@ -77,7 +77,7 @@ __device__ __forceinline__ void tile_load(TileRegs& t, const __bf16* __restrict_
     t.k[i] = gload128(K + (size_t)key * D + col * 8);
   }
   if (C::VUNITS >= 256 || tid < C::VUNITS) {
-    const int doct = tid % (D / 8), kq = tid / (D / 8);
+    const int kq = tid % (C::KT / 4), doct = tid / (C::KT / 4);   // see tile_store: lanes vary the key quad
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int key = min(k0 + 4 * kq + j, last);
@@ -98,7 +98,11 @@ __device__ __forceinline__ void tile_store(const TileRegs& t, unsigned char* __r
     *(u32x4*)(Ks + row * C::KSTR + col * 16) = t.k[i];
   }
   if (C::VUNITS >= 256 || tid < C::VUNITS) {
-    const int doct = tid % (D / 8), kq = tid / (D / 8);
+    const int kq = tid % (C::KT / 4), doct = tid / (C::KT / 4);   // see tile_store: lanes vary the key quad
+    // Lane -> unit mapping: the 16 key quads vary fastest across lanes.  One ds_write_b64 of a
+    // wavefront then covers 16 x 8 contiguous bytes of two adjacent V^T rows per 32 lanes, which
+    // is bank-conflict-free; with the d-octet varying fastest, lanes would hit rows 8 apart
+    // (8 * VSTR = 32 dwords mod 64 banks: an 8-way conflict, measured 10x slower).
     // key quad kq of a 16-key group goes to slot quad {0,2,1,3}[kq%4]: the order in which the
     // 32x32 score accumulators hand keys to the two lane halves.
     const int g4 = kq & 3;
@@ -219,7 +223,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
 }
 
 template <int D, int MODE>
-__global__ __launch_bounds__(256, (MODE == kPassSparseRefresh) ? 1 : 2) void attn_bf16_kernel(const PassParams p) {
+__global__ __launch_bounds__(256, (MODE == kPassSparseRefresh || MODE == kPassInternal) ? 1 : 2) void attn_bf16_kernel(const PassParams p) {
   using C = Cfg<D>;
   extern __shared__ __align__(16) unsigned char smem[];
 
@@ -262,6 +266,28 @@ __global__ __launch_bounds__(256, (MODE == kPassSparseRefresh) ? 1 : 2) void att
     qreg[ks] = __builtin_bit_cast(bf16x8, u);
   }
 
+  // Internal pass: the cached external partial is independent of everything computed here, so
+  // its loads are issued up front and complete under the attention work (the pass is a chain
+  // of memory latencies, not of arithmetic).
+  constexpr int NEO = (MODE == kPassInternal) ? C::NDB * 4 : 1;
+  f32x4 eo[NEO];
+  float ext_m_v = -INFINITY, ext_lse_v = -INFINITY;
+  if constexpr (MODE == kPassInternal) {
+    typedef const __attribute__((address_space(1))) f32x4* gptr_f4;
+    typedef const __attribute__((address_space(1))) float* gptr_f;
+    const bool have = (p.ext_o != nullptr) && row_ok;
+#pragma unroll
+    for (int i = 0; i < NEO; ++i) eo[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (have) {
+      ext_m_v = *((gptr_f)p.ext_m + grow);
+      ext_lse_v = *((gptr_f)p.ext_lse + grow);
+#pragma unroll
+      for (int db = 0; db < C::NDB; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4)
+          eo[db * 4 + q4] = *(gptr_f4)(p.ext_o + grow * D + 32 * db + 8 * q4 + 4 * h);
+    }
+  }
   // tile list of this workgroup
   int tpb = 1, total;
   if constexpr (MODE == kPassSparseReuse) {
@@ -333,18 +359,14 @@ __global__ __launch_bounds__(256, (MODE == kPassSparseRefresh) ? 1 : 2) void att
     }
     compute(smem + ((ntiles - 1) & 1) * C::STAGE, k0_cur, mask_cur);
   }
-
   // ---------------------------------------------------------------- epilogue
   const float l_sel = sel.l + __shfl_xor(sel.l, 32, 64);
   if constexpr (MODE == kPassInternal) {
     if (!row_ok) return;
     float me2 = -INFINITY, le = 0.f;
-    if (p.ext_o != nullptr) {
-      const float me = p.ext_m[grow], lse = p.ext_lse[grow];
-      if (lse != -INFINITY) {
-        me2 = me * kLog2e;
-        le = exp2f((lse - me) * kLog2e);
-      }
+    if (ext_lse_v != -INFINITY) {
+      me2 = ext_m_v * kLog2e;
+      le = exp2f((ext_lse_v - ext_m_v) * kLog2e);
     }
     // Eq. 8-9 with the cached pair expressed through (o, m, lse): A_out e^{L_out-M} = o e^{m-M}
     const float M2 = fmaxf(me2, sel.m);
@@ -358,8 +380,7 @@ __global__ __launch_bounds__(256, (MODE == kPassSparseRefresh) ? 1 : 2) void att
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
         const int d0 = 32 * db + 8 * q4 + 4 * h;
-        f32x4 e = {0.f, 0.f, 0.f, 0.f};
-        if (le > 0.f) e = *(const f32x4*)(p.ext_o + grow * D + d0);
+        const f32x4 e = eo[(MODE == kPassInternal) ? db * 4 + q4 : 0];   // o of an empty partial is 0 by contract
         float r[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) r[i] = (sel.o[db][4 * q4 + i] * wi + e[i] * we) * inv;
