@@ -214,7 +214,7 @@ def cpu_baseline(w, budget_s=12.0):
         orc.run_block_dense(Kp, Vp, steps, w.refresh)
         n_blocks += 1
         el = time.perf_counter() - t0
-        if el >= budget_s or n_blocks >= 50:
+        if el >= budget_s or n_blocks >= 400:
             break
     us = el / (n_blocks * w.steps) * 1e6
     return {"value": round(us, 1), "unit": "us/step", "cores": int(threads), "kind": "oracle",
@@ -238,7 +238,9 @@ def main():
     ap.add_argument("--no-long", action="store_true", help="skip the 128K-context external-pass measurement")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--profile-external", type=int, default=0, metavar="N",
-                    help="only run N external passes of the workload (for rocprofv3), print nothing else")
+                    help="only run N refresh steps of the workload (for rocprofv3), print nothing else")
+    ap.add_argument("--profile-copy", type=int, default=0, metavar="N",
+                    help="only run N plain device copies of 256 MiB (calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (the path has no multi-GPU part); use --gpus 1",
@@ -254,6 +256,14 @@ def main():
         sys.exit(3)
     torch.cuda.set_device(0)
     w = wl.CONFIGS[args.workload]
+    if args.profile_copy > 0:
+        x = torch.full((256 * 1024 * 1024,), 3, dtype=torch.uint8, device="cuda")
+        y = torch.empty_like(x)
+        for _ in range(args.profile_copy):
+            y.copy_(x)
+        torch.cuda.synchronize()
+        print(f"ran {args.profile_copy} device copies of {x.numel()} bytes (read {x.numel()} + write {x.numel()} per copy)")
+        return
     if args.profile_external > 0:
         d = DeviceBlock(w, max(2, min(4, int(-(-600e6 // w.kv_bytes)))))
         for i in range(args.profile_external):
@@ -274,9 +284,11 @@ def main():
     prof = profile_external(dev, 41, w.refresh)
 
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"traffic_{w.name}.json")
-    if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+    tpath = os.path.join(ROOT, "profiles", f"attn_bf16_external_{w.name}_hbm_traffic.txt")
+    if os.path.exists(tpath):       # measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, see that file
+        for ln in open(tpath):
+            if ln.startswith("hbm_bytes_per_launch"):
+                traffic = int(float(ln.split("=")[1].split()[0]))
     line = {
         "metric": "attention us per diffusion step (cached block-external attention, 32K context); "
                   "external-pass HBM GB/s in roofline / external_128k",

@@ -35,16 +35,17 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
-template <int D>
+template <int D, int KT_>
 struct Cfg {
-  static constexpr int KT = kKeyTile;               // keys per tile
+  static constexpr int KT = KT_;                    // keys per tile: 64, or 32 for the short internal pass
   static constexpr int KSTR = D * 2 + 16;           // bytes per K row in LDS
   static constexpr int VSTR = KT * 2 + 16;          // bytes per V^T row in LDS
   static constexpr int KBYTES = KT * KSTR;
   static constexpr int VBYTES = D * VSTR;
   static constexpr int STAGE = KBYTES + VBYTES;
   static constexpr int LDS = 2 * STAGE;
-  static constexpr int NK = (KT * (D / 8)) / 256;   // 16-byte K chunks per thread per tile
+  static constexpr int NK = (KT * (D / 8) + 255) / 256;   // 16-byte K chunks per thread per tile
+  static constexpr int KCHUNKS = KT * (D / 8);
   static constexpr int VUNITS = (KT / 4) * (D / 8); // (4 keys x 8 d) transpose units per tile
   static constexpr int NKS = D / 16;                // MFMA k-steps of the score product
   static constexpr int NDB = D / 32;                // 32-wide output column blocks
@@ -64,17 +65,17 @@ __device__ __forceinline__ u32x4 gload128(const __bf16* p) { return *(gptr128)(p
 // Global -> registers for one 64-key tile.  Keys past the end of the key range are clamped to
 // the last key: the loads stay in bounds and branch-free, the duplicated rows are finite, and
 // their scores are masked to -inf before the softmax so they never contribute.
-template <int D>
+template <int D, int KT>
 __device__ __forceinline__ void tile_load(TileRegs& t, const __bf16* __restrict__ K,
                                           const __bf16* __restrict__ V, int k0, int nkeys, int tid) {
-  using C = Cfg<D>;
+  using C = Cfg<D, KT>;
   const int last = nkeys - 1;
 #pragma unroll
   for (int i = 0; i < C::NK; ++i) {
     const int c = tid + 256 * i;
     const int row = c / (D / 8), col = c % (D / 8);
     const int key = min(k0 + row, last);
-    t.k[i] = gload128(K + (size_t)key * D + col * 8);
+    if (C::KCHUNKS % 256 == 0 || c < C::KCHUNKS) t.k[i] = gload128(K + (size_t)key * D + col * 8);
   }
   if (C::VUNITS >= 256 || tid < C::VUNITS) {
     const int kq = tid % (C::KT / 4), doct = tid / (C::KT / 4);   // see tile_store: lanes vary the key quad
@@ -86,16 +87,16 @@ __device__ __forceinline__ void tile_load(TileRegs& t, const __bf16* __restrict_
   }
 }
 
-template <int D>
+template <int D, int KT>
 __device__ __forceinline__ void tile_store(const TileRegs& t, unsigned char* __restrict__ stage, int tid) {
-  using C = Cfg<D>;
+  using C = Cfg<D, KT>;
   unsigned char* Ks = stage;
   unsigned char* Vt = stage + C::KBYTES;
 #pragma unroll
   for (int i = 0; i < C::NK; ++i) {
     const int c = tid + 256 * i;
     const int row = c / (D / 8), col = c % (D / 8);
-    *(u32x4*)(Ks + row * C::KSTR + col * 16) = t.k[i];
+    if (C::KCHUNKS % 256 == 0 || c < C::KCHUNKS) *(u32x4*)(Ks + row * C::KSTR + col * 16) = t.k[i];
   }
   if (C::VUNITS >= 256 || tid < C::VUNITS) {
     const int kq = tid % (C::KT / 4), doct = tid / (C::KT / 4);   // see tile_store: lanes vary the key quad
@@ -141,17 +142,19 @@ struct WaveState {
 // One 64-key tile for one wavefront: scores, online softmax update, value accumulation.
 //   lane_on : this lane's query row takes part in this tile for this accumulator set
 //   nvalid  : keys of the tile that exist (ragged tail); 64 for full tiles
-template <int D>
-__device__ __forceinline__ void tile_compute(WaveState<Cfg<D>::NDB>& st, const bf16x8 (&qreg)[Cfg<D>::NKS],
+template <int D, int KT, int WS>
+__device__ __forceinline__ void tile_compute(WaveState<Cfg<D, KT>::NDB / WS>& st, const bf16x8 (&qreg)[Cfg<D, KT>::NKS],
                                              const unsigned char* __restrict__ stage, float scale_log2,
-                                             bool lane_on, int nvalid, int l32, int h) {
-  using C = Cfg<D>;
+                                             bool lane_on, int nvalid, int l32, int h, int db_base) {
+  using C = Cfg<D, KT>;
+  constexpr int NDBL = C::NDB / WS;   // output column blocks this wavefront owns
   const unsigned char* Ks = stage;
   const unsigned char* Vt = stage + C::KBYTES;
 
-  f32x16 s[2];
+  constexpr int NKB = KT / 32;
+  f32x16 s[NKB];
 #pragma unroll
-  for (int kb = 0; kb < 2; ++kb) {
+  for (int kb = 0; kb < NKB; ++kb) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
 #pragma unroll
@@ -163,7 +166,7 @@ __device__ __forceinline__ void tile_compute(WaveState<Cfg<D>::NDB>& st, const b
   // s[kb][r] is the raw dot product of query row l32 with key kb*32 + 8*(r/4) + 4*h + r%4
   if (nvalid < C::KT) {
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int key = kb * 32 + 8 * (r / 4) + 4 * h + (r % 4);
@@ -172,7 +175,7 @@ __device__ __forceinline__ void tile_compute(WaveState<Cfg<D>::NDB>& st, const b
   }
   float tmax = -INFINITY;
 #pragma unroll
-  for (int kb = 0; kb < 2; ++kb)
+  for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
     for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[kb][r]);
   tmax = lane_on ? tmax * scale_log2 : -INFINITY;
@@ -186,9 +189,9 @@ __device__ __forceinline__ void tile_compute(WaveState<Cfg<D>::NDB>& st, const b
   const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
   const float alpha = __builtin_amdgcn_exp2f(st.m - m_use);
   float lsum = 0.f;
-  bf16x8 pb[4];
+  bf16x8 pb[2 * NKB];
 #pragma unroll
-  for (int kb = 0; kb < 2; ++kb)
+  for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       // raw v_exp_f32: exp2(-inf) = 0, results below 2^-126 flush to 0 (irrelevant for weights)
@@ -201,15 +204,15 @@ __device__ __forceinline__ void tile_compute(WaveState<Cfg<D>::NDB>& st, const b
   st.m = m_new;
   if (__any(alpha != 1.f)) {
 #pragma unroll
-    for (int db = 0; db < C::NDB; ++db)
+    for (int db = 0; db < NDBL; ++db)
 #pragma unroll
       for (int r = 0; r < 16; ++r) st.o[db][r] *= alpha;
   }
 #pragma unroll
-  for (int db = 0; db < C::NDB; ++db)
+  for (int db = 0; db < NDBL; ++db)
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const bf16x8 a = *(const bf16x8*)(Vt + (db * 32 + l32) * C::VSTR + (t * 16 + 8 * h) * 2);
+    for (int t = 0; t < 2 * NKB; ++t) {
+      const bf16x8 a = *(const bf16x8*)(Vt + ((db_base + db) * 32 + l32) * C::VSTR + (t * 16 + 8 * h) * 2);
       st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[t], st.o[db], 0, 0, 0);
     }
 }
@@ -222,9 +225,9 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
   return __builtin_bit_cast(uint32_t, v);
 }
 
-template <int D, int MODE>
+template <int D, int MODE, int KT, int WS>
 __global__ __launch_bounds__(256, (MODE == kPassSparseRefresh || MODE == kPassInternal) ? 1 : 2) void attn_bf16_kernel(const PassParams p) {
-  using C = Cfg<D>;
+  using C = Cfg<D, KT>;
   extern __shared__ __align__(16) unsigned char smem[];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -240,23 +243,79 @@ __global__ __launch_bounds__(256, (MODE == kPassSparseRefresh || MODE == kPassIn
     w = (xcd < r8 ? xcd * (q8 + 1) : r8 * (q8 + 1) + (xcd - r8) * q8) + j;
   }
   const int nrows = p.G * p.Bq;
-  const int ntile_rows = (nrows + kRowsPerWgBf16 - 1) / kRowsPerWgBf16;
-  const int rt = w % ntile_rows;
-  w /= ntile_rows;
-  const int split = w % p.nsplit;
-  w /= p.nsplit;
-  const int kvh = w % p.Hkv;
-  const int b = w / p.Hkv;
+  uint32_t rest = fastdiv((uint32_t)w, p.div_rowtiles);
+  const int rt = w - (int)(rest * p.div_rowtiles.d);
+  int split = 0;
+  if constexpr (MODE != kPassInternal) {
+    const uint32_t r2 = fastdiv(rest, p.div_nsplit);
+    split = (int)(rest - r2 * p.div_nsplit.d);
+    rest = r2;
+  }
+  const int b = (int)fastdiv(rest, p.div_hkv);
+  const int kvh = (int)(rest - (uint32_t)b * p.div_hkv.d);
   const int bk = b * p.Hkv + kvh;
   const int nkeys = p.nkeys;
 
-  const int row = rt * kRowsPerWgBf16 + wave * 32 + l32;      // group-flattened row of this lane
+  // WS wavefronts share one 32-row group and split the output columns between them (each repeats
+  // the cheap score / softmax work): used when the pass has too few rows to fill the GPU, where
+  // the time is a single wavefront's instruction stream, not throughput.
+  constexpr int ROWS = kRowsPerWgBf16 / WS;
+  constexpr int NDBL = C::NDB / WS;
+  const int db_base = (wave % WS) * NDBL;
+  const int row = rt * ROWS + (wave / WS) * 32 + l32;      // group-flattened row of this lane
   const bool row_ok = row < nrows;
   const size_t grow = (size_t)(b * p.Hq + kvh * p.G) * p.Bq + row;   // global row index
 
   const __bf16* __restrict__ Q = (const __bf16*)p.q;
   const __bf16* __restrict__ K = (const __bf16*)p.k + (size_t)bk * nkeys * D;
   const __bf16* __restrict__ V = (const __bf16*)p.v + (size_t)bk * nkeys * D;
+
+  // tile list of this workgroup
+  int tpb = 1, total;
+  if constexpr (MODE == kPassSparseReuse) {
+    tpb = p.key_block / KT;
+    total = p.union_cnt[bk] * tpb;
+  } else {
+    total = (nkeys + KT - 1) / KT;
+  }
+  const TileRange tr = split_range(total, p.nsplit, split);
+  const uint32_t* __restrict__ bmask = p.blk_mask ? p.blk_mask + (size_t)bk * p.nblk : nullptr;
+  const int32_t* __restrict__ ulist = p.union_list ? p.union_list + (size_t)bk * p.nblk : nullptr;
+  const uint32_t my_bit = 1u << ((row_ok ? row : 0) / p.Bq);
+
+  auto entry_k0 = [&](int e, uint32_t& mask) -> int {
+    if constexpr (MODE == kPassSparseReuse) {
+      const int blk = ulist[e / tpb];
+      mask = bmask[blk];
+      return blk * p.key_block + KT * (e % tpb);
+    } else if constexpr (MODE == kPassSparseRefresh) {
+      mask = bmask[(e * KT) / p.key_block];
+      return e * KT;
+    } else {
+      mask = 0xffffffffu;
+      return e * KT;
+    }
+  };
+
+  // The first tile's loads go out before anything else touches memory: the start of the kernel
+  // is a chain of cold latencies (instruction fetch, TLB, HBM), so the longest one starts first.
+  // Tiles are visited in a rotated order (start offset differs per workgroup): workgroups that
+  // run in lockstep would otherwise all read the same offset of their 2^k-strided chunks, i.e.
+  // the same HBM channels, at the same time.  The statistics do not depend on the tile order.
+  const int ntiles = tr.end - tr.begin;
+  const int rot = ntiles > 0 ? (int)((blockIdx.x * 13u + (blockIdx.x >> 5) * 7u) % (unsigned)ntiles) : 0;
+  auto tile_entry = [&](int i) -> int {
+    int j = i + rot;
+    if (j >= ntiles) j -= ntiles;
+    return tr.begin + j;
+  };
+  TileRegs regs;
+  uint32_t mask_cur = 0, mask_next = 0;
+  int k0_cur = 0, k0_next = 0;
+  if (ntiles > 0) {
+    k0_cur = entry_k0(tile_entry(0), mask_cur);
+    tile_load<D, KT>(regs, K, V, k0_cur, nkeys, tid);
+  }
 
   bf16x8 qreg[C::NKS];
 #pragma unroll
@@ -269,7 +328,7 @@ __global__ __launch_bounds__(256, (MODE == kPassSparseRefresh || MODE == kPassIn
   // Internal pass: the cached external partial is independent of everything computed here, so
   // its loads are issued up front and complete under the attention work (the pass is a chain
   // of memory latencies, not of arithmetic).
-  constexpr int NEO = (MODE == kPassInternal) ? C::NDB * 4 : 1;
+  constexpr int NEO = (MODE == kPassInternal) ? NDBL * 4 : 1;
   f32x4 eo[NEO];
   float ext_m_v = -INFINITY, ext_lse_v = -INFINITY;
   if constexpr (MODE == kPassInternal) {
@@ -282,42 +341,15 @@ __global__ __launch_bounds__(256, (MODE == kPassSparseRefresh || MODE == kPassIn
       ext_m_v = *((gptr_f)p.ext_m + grow);
       ext_lse_v = *((gptr_f)p.ext_lse + grow);
 #pragma unroll
-      for (int db = 0; db < C::NDB; ++db)
+      for (int db = 0; db < NDBL; ++db)
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4)
-          eo[db * 4 + q4] = *(gptr_f4)(p.ext_o + grow * D + 32 * db + 8 * q4 + 4 * h);
+          eo[db * 4 + q4] = *(gptr_f4)(p.ext_o + grow * D + 32 * (db_base + db) + 8 * q4 + 4 * h);
     }
   }
-  // tile list of this workgroup
-  int tpb = 1, total;
-  if constexpr (MODE == kPassSparseReuse) {
-    tpb = p.key_block / kKeyTile;
-    total = p.union_cnt[bk] * tpb;
-  } else {
-    total = (nkeys + kKeyTile - 1) / kKeyTile;
-  }
-  const TileRange tr = split_range(total, p.nsplit, split);
-  const uint32_t* __restrict__ bmask = p.blk_mask ? p.blk_mask + (size_t)bk * p.nblk : nullptr;
-  const int32_t* __restrict__ ulist = p.union_list ? p.union_list + (size_t)bk * p.nblk : nullptr;
-  const uint32_t my_bit = 1u << ((row_ok ? row : 0) / p.Bq);
-
-  auto entry_k0 = [&](int e, uint32_t& mask) -> int {
-    if constexpr (MODE == kPassSparseReuse) {
-      const int blk = ulist[e / tpb];
-      mask = bmask[blk];
-      return blk * p.key_block + kKeyTile * (e % tpb);
-    } else if constexpr (MODE == kPassSparseRefresh) {
-      mask = bmask[(e * kKeyTile) / p.key_block];
-      return e * kKeyTile;
-    } else {
-      mask = 0xffffffffu;
-      return e * kKeyTile;
-    }
-  };
-
-  WaveState<C::NDB> sel;
+  WaveState<NDBL> sel;
   sel.init();
-  WaveState<(MODE == kPassSparseRefresh) ? C::NDB : 1> res;
+  WaveState<(MODE == kPassSparseRefresh) ? NDBL : 1> res;
   res.init();
 
   // Steady state per iteration: issue the global loads of tile i+1 (they stay in flight in
@@ -329,30 +361,25 @@ __global__ __launch_bounds__(256, (MODE == kPassSparseRefresh || MODE == kPassIn
     }
     if constexpr (MODE == kPassSparseRefresh) {
       const bool on = row_ok && (mask & my_bit);
-      if (__any(on)) tile_compute<D>(sel, qreg, stage, p.scale_log2, on, nvalid, l32, h);
+      if (__any(on)) tile_compute<D, KT, WS>(sel, qreg, stage, p.scale_log2, on, nvalid, l32, h, db_base);
       const bool off = row_ok && !(mask & my_bit);
-      if (__any(off)) tile_compute<D>(res, qreg, stage, p.scale_log2, off, nvalid, l32, h);
+      if (__any(off)) tile_compute<D, KT, WS>(res, qreg, stage, p.scale_log2, off, nvalid, l32, h, db_base);
     } else if constexpr (MODE == kPassSparseReuse) {
       const bool on = row_ok && (mask & my_bit);
-      if (__any(on)) tile_compute<D>(sel, qreg, stage, p.scale_log2, on, nvalid, l32, h);
+      if (__any(on)) tile_compute<D, KT, WS>(sel, qreg, stage, p.scale_log2, on, nvalid, l32, h, db_base);
     } else {
-      tile_compute<D>(sel, qreg, stage, p.scale_log2, true, nvalid, l32, h);
+      tile_compute<D, KT, WS>(sel, qreg, stage, p.scale_log2, true, nvalid, l32, h, db_base);
     }
   };
 
-  const int ntiles = tr.end - tr.begin;
   if (ntiles > 0) {
-    TileRegs regs;
-    uint32_t mask_cur = 0, mask_next = 0;
-    int k0_cur = entry_k0(tr.begin, mask_cur), k0_next = 0;
-    tile_load<D>(regs, K, V, k0_cur, nkeys, tid);
-    tile_store<D>(regs, smem, tid);
+    tile_store<D, KT>(regs, smem, tid);
     __syncthreads();
     for (int i = 0; i < ntiles - 1; ++i) {
-      k0_next = entry_k0(tr.begin + i + 1, mask_next);
-      tile_load<D>(regs, K, V, k0_next, nkeys, tid);
+      k0_next = entry_k0(tile_entry(i + 1), mask_next);
+      tile_load<D, KT>(regs, K, V, k0_next, nkeys, tid);
       compute(smem + (i & 1) * C::STAGE, k0_cur, mask_cur);
-      tile_store<D>(regs, smem + ((i + 1) & 1) * C::STAGE, tid);
+      tile_store<D, KT>(regs, smem + ((i + 1) & 1) * C::STAGE, tid);
       __syncthreads();
       k0_cur = k0_next;
       mask_cur = mask_next;
@@ -376,10 +403,10 @@ __global__ __launch_bounds__(256, (MODE == kPassSparseRefresh || MODE == kPassIn
     const float inv = den > 0.f ? 1.f / den : 0.f;
     __bf16* out = (__bf16*)p.out + grow * D;
 #pragma unroll
-    for (int db = 0; db < C::NDB; ++db)
+    for (int db = 0; db < NDBL; ++db)
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
-        const int d0 = 32 * db + 8 * q4 + 4 * h;
+        const int d0 = 32 * (db_base + db) + 8 * q4 + 4 * h;
         const f32x4 e = eo[(MODE == kPassInternal) ? db * 4 + q4 : 0];   // o of an empty partial is 0 by contract
         float r[4];
 #pragma unroll
@@ -389,20 +416,20 @@ __global__ __launch_bounds__(256, (MODE == kPassSparseRefresh || MODE == kPassIn
         pk.y = pack_bf16x2(r[2], r[3]);
         *(u32x2*)(out + d0) = pk;
       }
-    if (p.lse_out != nullptr && h == 0) p.lse_out[grow] = den > 0.f ? (M2 + log2f(den)) * kLn2 : -INFINITY;
+    if (p.lse_out != nullptr && h == 0 && db_base == 0) p.lse_out[grow] = den > 0.f ? (M2 + log2f(den)) * kLn2 : -INFINITY;
   } else {
     const size_t rows_total = (size_t)p.B * p.Hq * p.Bq;
     const size_t wrow = (size_t)split * rows_total + grow;
     if (row_ok) {
 #pragma unroll
-      for (int db = 0; db < C::NDB; ++db)
+      for (int db = 0; db < NDBL; ++db)
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
-          const int d0 = 32 * db + 8 * q4 + 4 * h;
+          const int d0 = 32 * (db_base + db) + 8 * q4 + 4 * h;
           f32x4 o4 = {sel.o[db][4 * q4], sel.o[db][4 * q4 + 1], sel.o[db][4 * q4 + 2], sel.o[db][4 * q4 + 3]};
           *(f32x4*)(p.ws_o + wrow * D + d0) = o4;
         }
-      if (h == 0) {
+      if (h == 0 && db_base == 0) {
         p.ws_m[wrow] = sel.m;
         p.ws_l[wrow] = l_sel;
       }
@@ -411,14 +438,14 @@ __global__ __launch_bounds__(256, (MODE == kPassSparseRefresh || MODE == kPassIn
       const float l_res = res.l + __shfl_xor(res.l, 32, 64);
       if (row_ok) {
 #pragma unroll
-        for (int db = 0; db < C::NDB; ++db)
+        for (int db = 0; db < NDBL; ++db)
 #pragma unroll
           for (int q4 = 0; q4 < 4; ++q4) {
-            const int d0 = 32 * db + 8 * q4 + 4 * h;
+            const int d0 = 32 * (db_base + db) + 8 * q4 + 4 * h;
             f32x4 o4 = {res.o[db][4 * q4], res.o[db][4 * q4 + 1], res.o[db][4 * q4 + 2], res.o[db][4 * q4 + 3]};
             *(f32x4*)(p.ws_o2 + wrow * D + d0) = o4;
           }
-        if (h == 0) {
+        if (h == 0 && db_base == 0) {
           p.ws_m2[wrow] = res.m;
           p.ws_l2[wrow] = l_res;
         }
@@ -427,29 +454,47 @@ __global__ __launch_bounds__(256, (MODE == kPassSparseRefresh || MODE == kPassIn
   }
 }
 
-template <int D, int MODE>
+template <int D, int MODE, int KT, int WS>
 hipError_t launch_one(const PassParams& p, hipStream_t s) {
   static bool attr_set = false;   // raising the dynamic-LDS limit is idempotent; the flag only saves calls
-  auto kern = attn_bf16_kernel<D, MODE>;
+  auto kern = attn_bf16_kernel<D, MODE, KT, WS>;
+  constexpr int lds = Cfg<D, KT>::LDS;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, Cfg<D>::LDS);
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
+  constexpr int rows_per_wg = kRowsPerWgBf16 / WS;
   const int nrows = p.G * p.Bq;
-  const int ntile_rows = (nrows + kRowsPerWgBf16 - 1) / kRowsPerWgBf16;
+  const int ntile_rows = (nrows + rows_per_wg - 1) / rows_per_wg;
   const long long nwg = (long long)p.B * p.Hkv * ntile_rows * p.nsplit;
-  hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(256), Cfg<D>::LDS, s, p);
+  if (nwg >= (1ll << 31)) return hipErrorInvalidValue;
+  PassParams q = p;
+  q.div_rowtiles = make_fastdiv((uint32_t)ntile_rows);
+  q.div_nsplit = make_fastdiv((uint32_t)p.nsplit);
+  q.div_hkv = make_fastdiv((uint32_t)p.Hkv);
+  hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(256), lds, s, q);
   return hipGetLastError();
 }
 
 template <int D>
 hipError_t launch_d(const PassParams& p, PassMode mode, hipStream_t s) {
+  constexpr int WSMAX = (D / 32 >= 4) ? 4 : 2;
   switch (mode) {
-    case kPassDense: return launch_one<D, kPassDense>(p, s);
-    case kPassInternal: return launch_one<D, kPassInternal>(p, s);
-    case kPassSparseRefresh: return launch_one<D, kPassSparseRefresh>(p, s);
-    case kPassSparseReuse: return launch_one<D, kPassSparseReuse>(p, s);
+    case kPassDense: return launch_one<D, kPassDense, kKeyTile, 1>(p, s);
+    case kPassInternal: {
+      // Few rows (an LLM-sized block): the pass is one wavefront's run-once instruction stream.
+      // Spread each 32-row group over WSMAX wavefronts (columns split) and, for a block of at
+      // most 32 keys, use the 32-key tile: both shorten that stream.
+      const long long wgs = (long long)p.B * p.Hkv * ((p.G * p.Bq + kRowsPerWgBf16 - 1) / kRowsPerWgBf16);
+      if (wgs < 128) {
+        if (p.nkeys <= 32) return launch_one<D, kPassInternal, 32, WSMAX>(p, s);
+        return launch_one<D, kPassInternal, kKeyTile, WSMAX>(p, s);
+      }
+      return launch_one<D, kPassInternal, kKeyTile, 1>(p, s);
+    }
+    case kPassSparseRefresh: return launch_one<D, kPassSparseRefresh, kKeyTile, 1>(p, s);
+    case kPassSparseReuse: return launch_one<D, kPassSparseReuse, kKeyTile, 1>(p, s);
   }
   return hipErrorInvalidValue;
 }

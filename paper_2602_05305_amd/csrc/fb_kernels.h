@@ -9,6 +9,32 @@ namespace fb {
 
 constexpr int kKeyTile = 64;  // keys per main-loop iteration in every attention kernel
 
+// Division of a non-negative 31-bit integer by a launch-time constant, without the ~25
+// instruction integer-division sequence in the (cold, run-once) kernel prologue:
+// q = (mulhi(n, magic) + n) >> shift with magic = floor(2^32 (2^shift - d) / d) + 1, shift = ceil(log2 d).
+struct FastDiv {
+  uint32_t magic, shift, d;
+};
+
+inline FastDiv make_fastdiv(uint32_t d) {
+  FastDiv f;
+  f.d = d;
+  uint32_t s = 0;
+  while ((1ull << s) < d) ++s;
+  f.shift = s;
+  f.magic = (uint32_t)((((1ull << s) - d) << 32) / d + 1);
+  return f;
+}
+
+__host__ __device__ __forceinline__ uint32_t fastdiv(uint32_t n, const FastDiv& f) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  const uint64_t t = (uint64_t)__umulhi(n, f.magic) + n;
+#else
+  const uint64_t t = (((uint64_t)n * f.magic) >> 32) + n;
+#endif
+  return (uint32_t)(t >> f.shift);
+}
+
 // What a pass iterates over and what it emits.
 enum PassMode : int {
   kPassDense = 0,          // keys [0, nkeys) cut into nsplit tile ranges -> split partials
@@ -38,6 +64,7 @@ struct PassParams {
   const int32_t* union_list;  // [B,Hkv,nblk] ascending blocks with mask != 0
   const int32_t* union_cnt;   // [B,Hkv]
   int key_block, nblk;
+  FastDiv div_rowtiles, div_nsplit, div_hkv;   // bf16 pass: decomposition of the linear workgroup index
 };
 
 // Fold split partials (and optionally a cached residual) into final (o, m, lse) partials.
@@ -84,11 +111,12 @@ struct TileRange {
 };
 
 __device__ __forceinline__ TileRange split_range(int total, int nsplit, int split) {
-  // balanced contiguous cut of `total` entries into nsplit pieces
-  const long long t = total;
+  // balanced contiguous cut of `total` entries into nsplit pieces: the first total % nsplit
+  // pieces get one entry more (one 32-bit division, no 64-bit arithmetic)
+  const int base = total / nsplit, rem = total - base * nsplit;
   TileRange r;
-  r.begin = (int)((t * split) / nsplit);
-  r.end = (int)((t * (split + 1)) / nsplit);
+  r.begin = split * base + min(split, rem);
+  r.end = r.begin + base + (split < rem ? 1 : 0);
   return r;
 }
 
