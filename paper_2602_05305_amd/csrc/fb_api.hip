@@ -46,19 +46,22 @@ long long rows_of(const fb_shape* s) { return (long long)s->batch * s->n_q_heads
 int auto_splits(const fb_shape* s) {
   const int tiles = (s->prefix_len + fb::kKeyTile - 1) / fb::kKeyTile;
   if (s->dtype == FB_BF16) {
-    // Workgroups wanted: between one and two per CU (256 CUs, two 4-wave workgroups fit a CU).
-    // Every split costs a 128-row fp32 partial written and read back, so a split should stream
-    // at least ~16 tiles (1024 keys): measured on MI355X, 32 splits beat 64 at a 32K prefix and
-    // 64 beat 32 at 128K.
+    // Every split costs a 128-row fp32 partial written and read back, so splits are as few as
+    // still fill the GPU.
     const int G = s->n_q_heads / s->n_kv_heads;
     const long long groups =
         (long long)s->batch * s->n_kv_heads * ((G * s->block_len + fb::kRowsPerWgBf16 - 1) / fb::kRowsPerWgBf16);
-    long long lo = (256 + groups - 1) / groups, hi = (512 + groups - 1) / groups;
-    long long ns = tiles / 16;
-    if (ns < lo) ns = lo;
-    if (ns > hi) ns = hi;
-    const long long cap = tiles / 4;          // never fewer than 4 tiles per split
-    if (ns > cap) ns = cap;
+    // Long prefixes: one 8-wavefront workgroup per CU (256 CUs), each streaming >= 8 tiles.
+    // Shorter ones: 4-wavefront workgroups, up to two per CU, never fewer than 4 tiles per split.
+    const long long per_cu = (256 + groups - 1) / groups;
+    long long ns;
+    if (tiles >= 8 * per_cu) {
+      ns = per_cu;
+    } else {
+      ns = tiles / 4;
+      const long long hi = (512 + groups - 1) / groups;
+      if (ns > hi) ns = hi;
+    }
     if (ns > FB_MAX_SPLITS) ns = FB_MAX_SPLITS;
     if (ns < 1) ns = 1;
     return (int)ns;

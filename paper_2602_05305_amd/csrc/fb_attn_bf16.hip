@@ -225,13 +225,20 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
   return __builtin_bit_cast(uint32_t, v);
 }
 
-template <int D, int MODE, int KT, int WS>
-__global__ __launch_bounds__(256, (MODE == kPassSparseRefresh || MODE == kPassInternal) ? 1 : 2) void attn_bf16_kernel(const PassParams p) {
+// NG = wavefront groups per workgroup (1 or 2).  With NG = 2 a workgroup is 8 wavefronts: both
+// groups own the same 128 rows, stream alternate tiles of the workgroup's key range through their
+// own pair of LDS stages, and group 1 hands its statistics to group 0 through LDS at the end.
+// Same wavefronts per CU as two 4-wave workgroups, half as many split partials to write and fold.
+template <int D, int MODE, int KT, int WS, int NG>
+__global__ __launch_bounds__(256 * NG, (NG > 1 || MODE == kPassSparseRefresh || MODE == kPassInternal) ? 1 : 2) void attn_bf16_kernel(const PassParams p) {
   using C = Cfg<D, KT>;
-  extern __shared__ __align__(16) unsigned char smem[];
+  extern __shared__ __align__(16) unsigned char smem_all[];
+  static_assert(NG == 1 || MODE == kPassDense, "wavefront groups are only wired up for the dense pass");
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int grp = (NG > 1) ? (int)(threadIdx.x >> 8) : 0;
+  const int tid = threadIdx.x & 255, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, h = lane >> 5;
+  unsigned char* smem = smem_all + grp * 2 * C::STAGE;
 
   // XCD-aware remap: hardware deals consecutive workgroup ids round-robin to the 8 XCDs; make
   // each XCD own a contiguous range of work items (row tiles of one KV head are adjacent).
@@ -304,15 +311,17 @@ __global__ __launch_bounds__(256, (MODE == kPassSparseRefresh || MODE == kPassIn
   // the same HBM channels, at the same time.  The statistics do not depend on the tile order.
   const int ntiles = tr.end - tr.begin;
   const int rot = ntiles > 0 ? (int)((blockIdx.x * 13u + (blockIdx.x >> 5) * 7u) % (unsigned)ntiles) : 0;
-  auto tile_entry = [&](int i) -> int {
-    int j = i + rot;
+  auto tile_entry = [&](int i) -> int {   // i-th tile of this wavefront group
+    int j = NG * i + grp + rot;
     if (j >= ntiles) j -= ntiles;
     return tr.begin + j;
   };
+  const int common = ntiles / NG;                 // tiles every group has
+  const bool extra = (ntiles % NG) > grp;         // this group has one more
   TileRegs regs;
   uint32_t mask_cur = 0, mask_next = 0;
   int k0_cur = 0, k0_next = 0;
-  if (ntiles > 0) {
+  if (common > 0 || extra) {
     k0_cur = entry_k0(tile_entry(0), mask_cur);
     tile_load<D, KT>(regs, K, V, k0_cur, nkeys, tid);
   }
@@ -373,9 +382,9 @@ __global__ __launch_bounds__(256, (MODE == kPassSparseRefresh || MODE == kPassIn
   };
 
   if (ntiles > 0) {
-    tile_store<D, KT>(regs, smem, tid);
+    if (common > 0 || extra) tile_store<D, KT>(regs, smem, tid);
     __syncthreads();
-    for (int i = 0; i < ntiles - 1; ++i) {
+    for (int i = 0; i < common - 1; ++i) {       // steady state: no conditionals, one barrier per tile
       k0_next = entry_k0(tile_entry(i + 1), mask_next);
       tile_load<D, KT>(regs, K, V, k0_next, nkeys, tid);
       compute(smem + (i & 1) * C::STAGE, k0_cur, mask_cur);
@@ -384,7 +393,47 @@ __global__ __launch_bounds__(256, (MODE == kPassSparseRefresh || MODE == kPassIn
       k0_cur = k0_next;
       mask_cur = mask_next;
     }
-    compute(smem + ((ntiles - 1) & 1) * C::STAGE, k0_cur, mask_cur);
+    if (common > 0) {
+      const int i = common - 1;
+      if (extra) {
+        k0_next = entry_k0(tile_entry(i + 1), mask_next);
+        tile_load<D, KT>(regs, K, V, k0_next, nkeys, tid);
+      }
+      compute(smem + (i & 1) * C::STAGE, k0_cur, mask_cur);
+      if (NG > 1 && (ntiles % NG) != 0) {         // some group has one more tile (workgroup-uniform)
+        if (extra) tile_store<D, KT>(regs, smem + ((i + 1) & 1) * C::STAGE, tid);
+        __syncthreads();
+        if (extra) compute(smem + ((i + 1) & 1) * C::STAGE, k0_next, mask_next);
+      }
+    } else if (extra) {
+      compute(smem, k0_cur, mask_cur);
+    }
+  }
+  if constexpr (NG > 1) {
+    // hand group 1's statistics to group 0: [wave][register][lane] floats in the (now idle) LDS
+    constexpr int REC = NDBL * 16 + 2;
+    float* mbuf = (float*)smem_all + (size_t)wave * REC * 64 + lane;
+    __syncthreads();
+    if (grp == 1) {
+#pragma unroll
+      for (int db = 0; db < NDBL; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mbuf[(db * 16 + r) * 64] = sel.o[db][r];
+      mbuf[(NDBL * 16) * 64] = sel.m;
+      mbuf[(NDBL * 16 + 1) * 64] = sel.l;
+    }
+    __syncthreads();
+    if (grp == 1) return;
+    const float m1 = mbuf[(NDBL * 16) * 64], l1 = mbuf[(NDBL * 16 + 1) * 64];
+    const float M = fmaxf(sel.m, m1);
+    const float Mu = (M == -INFINITY) ? 0.f : M;
+    const float w0 = __builtin_amdgcn_exp2f(sel.m - Mu), w1 = __builtin_amdgcn_exp2f(m1 - Mu);
+#pragma unroll
+    for (int db = 0; db < NDBL; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sel.o[db][r] = sel.o[db][r] * w0 + mbuf[(db * 16 + r) * 64] * w1;
+    sel.l = sel.l * w0 + l1 * w1;
+    sel.m = M;
   }
   // ---------------------------------------------------------------- epilogue
   const float l_sel = sel.l + __shfl_xor(sel.l, 32, 64);
@@ -454,11 +503,11 @@ __global__ __launch_bounds__(256, (MODE == kPassSparseRefresh || MODE == kPassIn
   }
 }
 
-template <int D, int MODE, int KT, int WS>
+template <int D, int MODE, int KT, int WS, int NG>
 hipError_t launch_one(const PassParams& p, hipStream_t s) {
   static bool attr_set = false;   // raising the dynamic-LDS limit is idempotent; the flag only saves calls
-  auto kern = attn_bf16_kernel<D, MODE, KT, WS>;
-  constexpr int lds = Cfg<D, KT>::LDS;
+  auto kern = attn_bf16_kernel<D, MODE, KT, WS, NG>;
+  constexpr int lds = Cfg<D, KT>::LDS * NG;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
@@ -473,7 +522,7 @@ hipError_t launch_one(const PassParams& p, hipStream_t s) {
   q.div_rowtiles = make_fastdiv((uint32_t)ntile_rows);
   q.div_nsplit = make_fastdiv((uint32_t)p.nsplit);
   q.div_hkv = make_fastdiv((uint32_t)p.Hkv);
-  hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(256), lds, s, q);
+  hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(256 * NG), lds, s, q);
   return hipGetLastError();
 }
 
@@ -481,20 +530,26 @@ template <int D>
 hipError_t launch_d(const PassParams& p, PassMode mode, hipStream_t s) {
   constexpr int WSMAX = (D / 32 >= 4) ? 4 : 2;
   switch (mode) {
-    case kPassDense: return launch_one<D, kPassDense, kKeyTile, 1>(p, s);
+    case kPassDense: {
+      // 8-wave workgroups for split-KV streaming when every wavefront group gets >= 4 tiles; the
+      // split heuristic (fb_api) then asks for one such workgroup per CU.
+      const int tiles = (p.nkeys + kKeyTile - 1) / kKeyTile;
+      if (p.nsplit > 1 && tiles >= 8 * p.nsplit) return launch_one<D, kPassDense, kKeyTile, 1, 2>(p, s);
+      return launch_one<D, kPassDense, kKeyTile, 1, 1>(p, s);
+    }
     case kPassInternal: {
       // Few rows (an LLM-sized block): the pass is one wavefront's run-once instruction stream.
       // Spread each 32-row group over WSMAX wavefronts (columns split) and, for a block of at
       // most 32 keys, use the 32-key tile: both shorten that stream.
       const long long wgs = (long long)p.B * p.Hkv * ((p.G * p.Bq + kRowsPerWgBf16 - 1) / kRowsPerWgBf16);
       if (wgs < 128) {
-        if (p.nkeys <= 32) return launch_one<D, kPassInternal, 32, WSMAX>(p, s);
-        return launch_one<D, kPassInternal, kKeyTile, WSMAX>(p, s);
+        if (p.nkeys <= 32) return launch_one<D, kPassInternal, 32, WSMAX, 1>(p, s);
+        return launch_one<D, kPassInternal, kKeyTile, WSMAX, 1>(p, s);
       }
-      return launch_one<D, kPassInternal, kKeyTile, 1>(p, s);
+      return launch_one<D, kPassInternal, kKeyTile, 1, 1>(p, s);
     }
-    case kPassSparseRefresh: return launch_one<D, kPassSparseRefresh, kKeyTile, 1>(p, s);
-    case kPassSparseReuse: return launch_one<D, kPassSparseReuse, kKeyTile, 1>(p, s);
+    case kPassSparseRefresh: return launch_one<D, kPassSparseRefresh, kKeyTile, 1, 1>(p, s);
+    case kPassSparseReuse: return launch_one<D, kPassSparseReuse, kKeyTile, 1, 1>(p, s);
   }
   return hipErrorInvalidValue;
 }

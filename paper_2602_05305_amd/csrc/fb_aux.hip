@@ -116,21 +116,44 @@ __global__ __launch_bounds__(256) void combine_kernel(const CombineParams p) {
 __device__ __forceinline__ Folded fold_strided(const float* __restrict__ ws_o, const float* __restrict__ ws_m,
                                                const float* __restrict__ ws_l, int nsplit, size_t rows,
                                                size_t row, int D, int c4, int first, int stride) {
+  // Chunks of CH splits: all loads of a chunk are independent (one memory round trip), then the
+  // chunk is folded into the running result with an online reference update.
+  constexpr int CH = 4;
   Folded f = empty_folded();
-  float M = -INFINITY;
-  for (int s = first; s < nsplit; s += stride) M = fmaxf(M, ws_m[(size_t)s * rows + row]);
-  f.m2 = M;
-  if (M == -INFINITY) return f;
-#pragma unroll 4
-  for (int s = first; s < nsplit; s += stride) {
-    const size_t r = (size_t)s * rows + row;
-    const float w = exp2f(ws_m[r] - M);
-    const float4 o = *(const float4*)(ws_o + r * D + c4 * 4);
-    f.o.x = fmaf(o.x, w, f.o.x);
-    f.o.y = fmaf(o.y, w, f.o.y);
-    f.o.z = fmaf(o.z, w, f.o.z);
-    f.o.w = fmaf(o.w, w, f.o.w);
-    f.l = fmaf(ws_l[r], w, f.l);
+  for (int s0 = first; s0 < nsplit; s0 += stride * CH) {
+    float mv[CH], lv[CH];
+    float4 ov[CH];
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+      const int s = s0 + c * stride;
+      mv[c] = -INFINITY;
+      lv[c] = 0.f;
+      ov[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (s < nsplit) {
+        const size_t r = (size_t)s * rows + row;
+        mv[c] = ws_m[r];
+        lv[c] = ws_l[r];
+        ov[c] = *(const float4*)(ws_o + r * D + c4 * 4);
+      }
+    }
+    float cm = mv[0];
+#pragma unroll
+    for (int c = 1; c < CH; ++c) cm = fmaxf(cm, mv[c]);
+    const float Mn = fmaxf(f.m2, cm);
+    if (Mn == -INFINITY) continue;
+    const float a = exp2f(f.m2 - Mn);
+    f.o.x *= a; f.o.y *= a; f.o.z *= a; f.o.w *= a;
+    f.l *= a;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+      const float w = exp2f(mv[c] - Mn);
+      f.o.x = fmaf(ov[c].x, w, f.o.x);
+      f.o.y = fmaf(ov[c].y, w, f.o.y);
+      f.o.z = fmaf(ov[c].z, w, f.o.z);
+      f.o.w = fmaf(ov[c].w, w, f.o.w);
+      f.l = fmaf(lv[c], w, f.l);
+    }
+    f.m2 = Mn;
   }
   return f;
 }
