@@ -223,6 +223,77 @@ def cpu_baseline(w, budget_s=12.0):
             "host_cores_visible": len(os.sched_getaffinity(0))}
 
 
+def _ev_median_us(torch, fn, reps=15, warm=3):
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for a, b in evs:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    ts = sorted(a.elapsed_time(b) for a, b in evs)
+    return ts[len(ts) // 2] * 1e3
+
+
+def video_extra(torch, fb, wl):
+    """Video-shaped workload: both passes are dense contractions, priced against bf16 MFMA peak."""
+    w = wl.CONFIGS["video"]
+    d = DeviceBlock(w, 1)
+    q, kb, vb = d.steps[0]
+    t_ext = _ev_median_us(torch, lambda: fb.fb_external_partial(d.shape, q, d.K[0], d.V[0], d.o, d.m, d.lse, d.ws), 7, 2)
+    t_int = _ev_median_us(torch, lambda: fb.fb_internal_merge(d.shape, q, kb, vb, d.o, d.m, d.lse, d.out, None), 7, 2)
+    f_ext = 4.0 * w.batch * w.n_q_heads * w.block_len * w.prefix_len * w.head_dim
+    f_int = 4.0 * w.batch * w.n_q_heads * w.block_len * w.block_len * w.head_dim
+    peak = 2500.0
+    S, R = w.steps, w.refresh
+    return {"workload": describe(w), "bound": "mfma", "peak": peak, "unit": "TFLOP/s",
+            "external_us": round(t_ext, 1), "external_tflops": round(f_ext / t_ext / 1e6, 1),
+            "external_frac": round(f_ext / t_ext / 1e6 / peak, 4),
+            "internal_us": round(t_int, 1), "internal_tflops": round(f_int / t_int / 1e6, 1),
+            "internal_frac": round(f_int / t_int / 1e6 / peak, 4),
+            "block_speedup_cached_vs_full": round(S * (t_ext + t_int) / (-(-S // R) * t_ext + S * t_int), 3)}
+
+
+def sparse_extra(torch, fb, wl):
+    """Sparse + residual reuse at the 64K prefix: selection on the GPU, refresh and reuse calls."""
+    w = wl.CONFIGS["sparse_64k"]
+    d = DeviceBlock(w, 2)
+    nblk = -(-w.prefix_len // w.key_block)
+    ws = torch.empty(fb.fb_workspace_bytes(d.shape, w.key_block, w.topk), device="cuda", dtype=torch.uint8)
+    pooled = [torch.empty((w.batch, w.n_kv_heads, nblk, w.head_dim), device="cuda") for _ in range(2)]
+    idx = torch.empty((w.batch, w.n_q_heads, w.topk), device="cuda", dtype=torch.int32)
+    rows = (w.batch, w.n_q_heads, w.block_len)
+    ro = torch.empty(rows + (w.head_dim,), device="cuda")
+    rm, rl = torch.empty(rows, device="cuda"), torch.empty(rows, device="cuda")
+    q = d.steps[0][0]
+    t_pool = _ev_median_us(torch, lambda: fb.fb_pool_keys(d.shape, d.K[0], w.key_block, pooled[0]))
+    fb.fb_pool_keys(d.shape, d.K[1], w.key_block, pooled[1])
+    t_sel = _ev_median_us(torch, lambda: fb.fb_select_topk(d.shape, q, pooled[0], w.key_block, w.topk, idx))
+    i = [0]
+
+    def call(mode):
+        s = i[0] % 2
+        i[0] += 1
+        fb.fb_sparse_external_residual(d.shape, mode, q, d.K[s], d.V[s], w.key_block, w.topk, idx, ro, rm, rl,
+                                       d.o, d.m, d.lse, ws)
+    t_refresh = _ev_median_us(torch, lambda: call(fb.FB_SPARSE_REFRESH))
+    t_reuse = _ev_median_us(torch, lambda: call(fb.FB_SPARSE_REUSE))
+    t_dense = _ev_median_us(torch, lambda: fb.fb_external_partial(d.shape, q, d.K[i[0] % 2], d.V[i[0] % 2], d.o, d.m, d.lse, ws))
+    sel = idx.cpu().numpy()
+    G = w.n_q_heads // w.n_kv_heads
+    union = sum(len(set(sel[0, kv * G:(kv + 1) * G].ravel().tolist())) for kv in range(w.n_kv_heads))
+    union_bytes = union * w.key_block * w.head_dim * 2 * 2
+    return {"workload": describe(w) + f", key_block {w.key_block}, topk {w.topk}",
+            "pool_keys_us": round(t_pool, 1), "select_topk_us": round(t_sel, 1),
+            "sparse_refresh_call_us": round(t_refresh, 1), "sparse_reuse_call_us": round(t_reuse, 1),
+            "dense_external_call_us": round(t_dense, 1),
+            "union_fraction_of_prefix": round(union / (nblk * w.n_kv_heads), 3),
+            "reuse_union_bytes": union_bytes, "reuse_GBps_vs_union_bytes": round(union_bytes / t_reuse / 1e3, 1),
+            "refresh_GBps_vs_kv_bytes": round(w.kv_bytes / t_refresh / 1e3, 1)}
+
+
 def describe(w):
     return (f"{w.name}: batch {w.batch}, {w.n_q_heads} q heads / {w.n_kv_heads} kv heads, head_dim {w.head_dim}, "
             f"prefix {w.prefix_len}, block {w.block_len}, {w.steps} steps/block, refresh every {w.refresh}, {w.dtype}")
@@ -237,8 +308,11 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch every step eagerly instead of per-block HIP graphs")
     ap.add_argument("--no-long", action="store_true", help="skip the 128K-context external-pass measurement")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-extras", action="store_true", help="skip the video-shaped (MFMA) and sparse measurements")
     ap.add_argument("--profile-external", type=int, default=0, metavar="N",
                     help="only run N refresh steps of the workload (for rocprofv3), print nothing else")
+    ap.add_argument("--profile-sparse", type=int, default=0, metavar="N",
+                    help="only run N sparse refresh + reuse call pairs of the sparse_64k workload (for rocprofv3)")
     ap.add_argument("--profile-copy", type=int, default=0, metavar="N",
                     help="only run N plain device copies of 256 MiB (calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -263,6 +337,26 @@ def main():
             y.copy_(x)
         torch.cuda.synchronize()
         print(f"ran {args.profile_copy} device copies of {x.numel()} bytes (read {x.numel()} + write {x.numel()} per copy)")
+        return
+    if args.profile_sparse > 0:
+        ws_ = wl.CONFIGS["sparse_64k"]
+        d = DeviceBlock(ws_, 2)
+        nblk = -(-ws_.prefix_len // ws_.key_block)
+        wsb = torch.empty(fb.fb_workspace_bytes(d.shape, ws_.key_block, ws_.topk), device="cuda", dtype=torch.uint8)
+        pooled = torch.empty((ws_.batch, ws_.n_kv_heads, nblk, ws_.head_dim), device="cuda")
+        idx = torch.empty((ws_.batch, ws_.n_q_heads, ws_.topk), device="cuda", dtype=torch.int32)
+        rows = (ws_.batch, ws_.n_q_heads, ws_.block_len)
+        ro, rm, rl = torch.empty(rows + (ws_.head_dim,), device="cuda"), torch.empty(rows, device="cuda"), torch.empty(rows, device="cuda")
+        q = d.steps[0][0]
+        for i in range(args.profile_sparse):
+            s_ = i % 2
+            fb.fb_pool_keys(d.shape, d.K[s_], ws_.key_block, pooled)
+            fb.fb_select_topk(d.shape, q, pooled, ws_.key_block, ws_.topk, idx)
+            for mode in (fb.FB_SPARSE_REFRESH, fb.FB_SPARSE_REUSE):
+                fb.fb_sparse_external_residual(d.shape, mode, q, d.K[s_], d.V[s_], ws_.key_block, ws_.topk, idx,
+                                               ro, rm, rl, d.o, d.m, d.lse, wsb)
+        torch.cuda.synchronize()
+        print(f"ran {args.profile_sparse} sparse refresh+reuse pairs of {ws_.name}")
         return
     if args.profile_external > 0:
         d = DeviceBlock(w, max(2, min(4, int(-(-600e6 // w.kv_bytes)))))
@@ -323,6 +417,12 @@ def main():
         r2["reuse_step_us"] = round(p2["reuse_step_ms"] * 1e3, 2)
         line["external_128k"] = r2
         del d2
+        torch.cuda.empty_cache()
+
+    if not args.no_extras:
+        line["video_mfma"] = video_extra(torch, fb, wl)
+        torch.cuda.empty_cache()
+        line["sparse_64k"] = sparse_extra(torch, fb, wl)
         torch.cuda.empty_cache()
 
     if not args.no_cpu:

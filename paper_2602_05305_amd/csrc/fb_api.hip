@@ -75,6 +75,23 @@ int auto_splits(const fb_shape* s) {
   return (int)ns;
 }
 
+// Split counts of the sparse passes (bf16): one workgroup per CU in both modes - 8 wavefronts in
+// the reuse pass, 4 wavefronts with two accumulator sets in the refresh pass.
+int sparse_splits(const fb_shape* s, bool refresh) {
+  (void)refresh;
+  if (s->dtype != FB_BF16) return auto_splits(s);
+  const int tiles = (s->prefix_len + fb::kKeyTile - 1) / fb::kKeyTile;
+  const int G = s->n_q_heads / s->n_kv_heads;
+  const long long groups =
+      (long long)s->batch * s->n_kv_heads * ((G * s->block_len + fb::kRowsPerWgBf16 - 1) / fb::kRowsPerWgBf16);
+  long long ns = (256 + groups - 1) / groups;
+  const long long cap = tiles / 4;
+  if (ns > cap) ns = cap;
+  if (ns > FB_MAX_SPLITS) ns = FB_MAX_SPLITS;
+  if (ns < 1) ns = 1;
+  return (int)ns;
+}
+
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct WsLayout {
@@ -157,12 +174,13 @@ size_t fb_workspace_bytes(const fb_shape* shape, int32_t key_block, int32_t topk
   if (check_shape(shape) != FB_OK) return 0;
   if (n_splits < 0 || n_splits > FB_MAX_SPLITS) return 0;
   const int ns = n_splits > 0 ? n_splits : auto_splits(shape);
-  int nblk = 0, nsets = 1;
+  size_t t = ws_layout(shape, ns, 1, 0).total;
   if (key_block != 0) {
+    int nblk = 0;
     if (check_key_block(shape, key_block, topk, &nblk) != FB_OK) return 0;
-    nsets = 2;
+    const size_t ts = ws_layout(shape, sparse_splits(shape, false), 2, nblk).total;
+    if (ts > t) t = ts;
   }
-  const size_t t = ws_layout(shape, ns, nsets, nblk).total;
   return t > 0 ? t : 256;
 }
 
@@ -293,9 +311,10 @@ fb_status fb_sparse_external_residual(const fb_shape* shape, int32_t mode, const
       !aligned16(res_o) || !aligned16(res_m) || !aligned16(res_lse) || !aligned16(o_part) ||
       !aligned16(m_part) || !aligned16(lse_part) || !aligned16(workspace))
     return FB_ERR_ALIGN;
-  const int ns = auto_splits(shape);
+  const int ns = sparse_splits(shape, mode == FB_SPARSE_REFRESH);
   const WsLayout w = ws_layout(shape, ns, 2, nblk);
-  if (!workspace || workspace_bytes < w.total) return FB_ERR_WORKSPACE;
+  if (!workspace || workspace_bytes < ws_layout(shape, sparse_splits(shape, false), 2, nblk).total)
+    return FB_ERR_WORKSPACE;
 
   hipStream_t stream = (hipStream_t)hip_stream;
   char* ws = (char*)workspace;

@@ -66,8 +66,7 @@ __device__ __forceinline__ u32x4 gload128(const __bf16* p) { return *(gptr128)(p
 // the last key: the loads stay in bounds and branch-free, the duplicated rows are finite, and
 // their scores are masked to -inf before the softmax so they never contribute.
 template <int D, int KT>
-__device__ __forceinline__ void tile_load(TileRegs& t, const __bf16* __restrict__ K,
-                                          const __bf16* __restrict__ V, int k0, int nkeys, int tid) {
+__device__ __forceinline__ void load_k(u32x4 (&r)[4], const __bf16* __restrict__ K, int k0, int nkeys, int tid) {
   using C = Cfg<D, KT>;
   const int last = nkeys - 1;
 #pragma unroll
@@ -75,31 +74,41 @@ __device__ __forceinline__ void tile_load(TileRegs& t, const __bf16* __restrict_
     const int c = tid + 256 * i;
     const int row = c / (D / 8), col = c % (D / 8);
     const int key = min(k0 + row, last);
-    if (C::KCHUNKS % 256 == 0 || c < C::KCHUNKS) t.k[i] = gload128(K + (size_t)key * D + col * 8);
+    if (C::KCHUNKS % 256 == 0 || c < C::KCHUNKS) r[i] = gload128(K + (size_t)key * D + col * 8);
   }
+}
+
+template <int D, int KT>
+__device__ __forceinline__ void load_v(u32x4 (&r)[4], const __bf16* __restrict__ V, int k0, int nkeys, int tid) {
+  using C = Cfg<D, KT>;
+  const int last = nkeys - 1;
   if (C::VUNITS >= 256 || tid < C::VUNITS) {
-    const int kq = tid % (C::KT / 4), doct = tid / (C::KT / 4);   // see tile_store: lanes vary the key quad
+    const int kq = tid % (C::KT / 4), doct = tid / (C::KT / 4);   // see store_v: lanes vary the key quad
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int key = min(k0 + 4 * kq + j, last);
-      t.v[j] = gload128(V + (size_t)key * D + doct * 8);
+      r[j] = gload128(V + (size_t)key * D + doct * 8);
     }
   }
 }
 
 template <int D, int KT>
-__device__ __forceinline__ void tile_store(const TileRegs& t, unsigned char* __restrict__ stage, int tid) {
+__device__ __forceinline__ void store_k(const u32x4 (&r)[4], unsigned char* __restrict__ stage, int tid) {
   using C = Cfg<D, KT>;
-  unsigned char* Ks = stage;
-  unsigned char* Vt = stage + C::KBYTES;
 #pragma unroll
   for (int i = 0; i < C::NK; ++i) {
     const int c = tid + 256 * i;
     const int row = c / (D / 8), col = c % (D / 8);
-    if (C::KCHUNKS % 256 == 0 || c < C::KCHUNKS) *(u32x4*)(Ks + row * C::KSTR + col * 16) = t.k[i];
+    if (C::KCHUNKS % 256 == 0 || c < C::KCHUNKS) *(u32x4*)(stage + row * C::KSTR + col * 16) = r[i];
   }
+}
+
+template <int D, int KT>
+__device__ __forceinline__ void store_v(const u32x4 (&r)[4], unsigned char* __restrict__ stage, int tid) {
+  using C = Cfg<D, KT>;
+  unsigned char* Vt = stage + C::KBYTES;
   if (C::VUNITS >= 256 || tid < C::VUNITS) {
-    const int kq = tid % (C::KT / 4), doct = tid / (C::KT / 4);   // see tile_store: lanes vary the key quad
+    const int kq = tid % (C::KT / 4), doct = tid / (C::KT / 4);
     // Lane -> unit mapping: the 16 key quads vary fastest across lanes.  One ds_write_b64 of a
     // wavefront then covers 16 x 8 contiguous bytes of two adjacent V^T rows per 32 lanes, which
     // is bank-conflict-free; with the d-octet varying fastest, lanes would hit rows 8 apart
@@ -111,7 +120,7 @@ __device__ __forceinline__ void tile_store(const TileRegs& t, unsigned char* __r
     const int slot = 16 * (kq >> 2) + 4 * sq;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
-      const uint32_t a = t.v[0][w], b = t.v[1][w], c = t.v[2][w], d = t.v[3][w];
+      const uint32_t a = r[0][w], b = r[1][w], c = r[2][w], d = r[3][w];
       u32x2 lo, hi;   // column 2w (low halves) and 2w+1 (high halves) of the 4 keys
       lo.x = (a & 0xffffu) | (b << 16);
       lo.y = (c & 0xffffu) | (d << 16);
@@ -121,6 +130,31 @@ __device__ __forceinline__ void tile_store(const TileRegs& t, unsigned char* __r
       *(u32x2*)(Vt + dcol * C::VSTR + slot * 2) = lo;
       *(u32x2*)(Vt + (dcol + 1) * C::VSTR + slot * 2) = hi;
     }
+  }
+}
+
+// Whole tile by one 256-thread group, or (SPLIT) K by wavefront group 0 and V by group 1, each
+// into the same four staging registers.
+template <int D, int KT, bool SPLIT>
+__device__ __forceinline__ void tile_load(TileRegs& t, const __bf16* __restrict__ K, const __bf16* __restrict__ V,
+                                          int k0, int nkeys, int tid, int grp) {
+  if constexpr (SPLIT) {
+    if (grp == 0) load_k<D, KT>(t.k, K, k0, nkeys, tid);
+    else load_v<D, KT>(t.k, V, k0, nkeys, tid);
+  } else {
+    load_k<D, KT>(t.k, K, k0, nkeys, tid);
+    load_v<D, KT>(t.v, V, k0, nkeys, tid);
+  }
+}
+
+template <int D, int KT, bool SPLIT>
+__device__ __forceinline__ void tile_store(const TileRegs& t, unsigned char* __restrict__ stage, int tid, int grp) {
+  if constexpr (SPLIT) {
+    if (grp == 0) store_k<D, KT>(t.k, stage, tid);
+    else store_v<D, KT>(t.k, stage, tid);
+  } else {
+    store_k<D, KT>(t.k, stage, tid);
+    store_v<D, KT>(t.v, stage, tid);
   }
 }
 
@@ -230,15 +264,22 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
 // own pair of LDS stages, and group 1 hands its statistics to group 0 through LDS at the end.
 // Same wavefronts per CU as two 4-wave workgroups, half as many split partials to write and fold.
 template <int D, int MODE, int KT, int WS, int NG>
-__global__ __launch_bounds__(256 * NG, (NG > 1 || MODE == kPassSparseRefresh || MODE == kPassInternal) ? 1 : 2) void attn_bf16_kernel(const PassParams p) {
+__global__ __launch_bounds__(256 * NG, (NG > 1 || MODE == kPassInternal || MODE == kPassSparseRefresh) ? 1 : 2) void attn_bf16_kernel(const PassParams p) {
   using C = Cfg<D, KT>;
   extern __shared__ __align__(16) unsigned char smem_all[];
-  static_assert(NG == 1 || MODE == kPassDense, "wavefront groups are only wired up for the dense pass");
+  // Sparse refresh with NG = 2: the two wavefront groups are specialised by accumulator set
+  // instead (group 0 = selected keys, group 1 = residual keys).  Both see every tile in shared
+  // LDS stages (group 0 loads K, group 1 loads V), each wavefront computes a tile only if its
+  // head routes it to its set, and every wavefront keeps ONE set: two wavefronts per SIMD
+  // instead of the one that two sets in a single wavefront allow.
+  constexpr bool kSetSplit = (MODE == kPassSparseRefresh && NG == 2);
+  constexpr int TG = kSetSplit ? 1 : NG;          // wavefront groups that own separate tile streams
+  static_assert(NG == 1 || MODE == kPassDense || MODE == kPassSparseReuse || kSetSplit, "unsupported group mode");
 
   const int grp = (NG > 1) ? (int)(threadIdx.x >> 8) : 0;
   const int tid = threadIdx.x & 255, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, h = lane >> 5;
-  unsigned char* smem = smem_all + grp * 2 * C::STAGE;
+  unsigned char* smem = smem_all + (kSetSplit ? 0 : grp) * 2 * C::STAGE;
 
   // XCD-aware remap: hardware deals consecutive workgroup ids round-robin to the 8 XCDs; make
   // each XCD own a contiguous range of work items (row tiles of one KV head are adjacent).
@@ -312,18 +353,23 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || MODE == kPassSparseRefresh || 
   const int ntiles = tr.end - tr.begin;
   const int rot = ntiles > 0 ? (int)((blockIdx.x * 13u + (blockIdx.x >> 5) * 7u) % (unsigned)ntiles) : 0;
   auto tile_entry = [&](int i) -> int {   // i-th tile of this wavefront group
-    int j = NG * i + grp + rot;
+    int j = TG * i + (kSetSplit ? 0 : grp) + rot;
     if (j >= ntiles) j -= ntiles;
     return tr.begin + j;
   };
-  const int common = ntiles / NG;                 // tiles every group has
-  const bool extra = (ntiles % NG) > grp;         // this group has one more
+  const int common = ntiles / TG;                 // tiles every group has
+  const bool extra = !kSetSplit && (ntiles % TG) > grp;   // this group has one more
   TileRegs regs;
-  uint32_t mask_cur = 0, mask_next = 0;
-  int k0_cur = 0, k0_next = 0;
-  if (common > 0 || extra) {
+  // Tile descriptors (first key, selection mask) are looked up two tiles ahead: in the list-driven
+  // sparse reuse pass they come from dependent scalar loads, whose latency would otherwise sit
+  // in front of every tile's global loads.
+  const int mine = common + (extra ? 1 : 0);
+  uint32_t mask_cur = 0, mask_next = 0, mask_nn = 0;
+  int k0_cur = 0, k0_next = 0, k0_nn = 0;
+  if (mine > 0) {
     k0_cur = entry_k0(tile_entry(0), mask_cur);
-    tile_load<D, KT>(regs, K, V, k0_cur, nkeys, tid);
+    tile_load<D, KT, kSetSplit>(regs, K, V, k0_cur, nkeys, tid, grp);
+    if (mine > 1) k0_next = entry_k0(tile_entry(1), mask_next);
   }
 
   bf16x8 qreg[C::NKS];
@@ -358,7 +404,7 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || MODE == kPassSparseRefresh || 
   }
   WaveState<NDBL> sel;
   sel.init();
-  WaveState<(MODE == kPassSparseRefresh) ? NDBL : 1> res;
+  WaveState<(MODE == kPassSparseRefresh && !kSetSplit) ? NDBL : 1> res;
   res.init();
 
   // Steady state per iteration: issue the global loads of tile i+1 (they stay in flight in
@@ -368,7 +414,10 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || MODE == kPassSparseRefresh || 
     if constexpr (MODE == kPassSparseReuse) {
       if (nvalid <= 0) return;
     }
-    if constexpr (MODE == kPassSparseRefresh) {
+    if constexpr (kSetSplit) {
+      const bool on = row_ok && (((mask & my_bit) != 0u) == (grp == 0));
+      if (__any(on)) tile_compute<D, KT, WS>(sel, qreg, stage, p.scale_log2, on, nvalid, l32, h, db_base);
+    } else if constexpr (MODE == kPassSparseRefresh) {
       const bool on = row_ok && (mask & my_bit);
       if (__any(on)) tile_compute<D, KT, WS>(sel, qreg, stage, p.scale_log2, on, nvalid, l32, h, db_base);
       const bool off = row_ok && !(mask & my_bit);
@@ -382,26 +431,25 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || MODE == kPassSparseRefresh || 
   };
 
   if (ntiles > 0) {
-    if (common > 0 || extra) tile_store<D, KT>(regs, smem, tid);
+    if (common > 0 || extra) tile_store<D, KT, kSetSplit>(regs, smem, tid, grp);
     __syncthreads();
-    for (int i = 0; i < common - 1; ++i) {       // steady state: no conditionals, one barrier per tile
-      k0_next = entry_k0(tile_entry(i + 1), mask_next);
-      tile_load<D, KT>(regs, K, V, k0_next, nkeys, tid);
+    for (int i = 0; i < common - 1; ++i) {       // steady state: one barrier per tile
+      if (i + 2 < mine) k0_nn = entry_k0(tile_entry(i + 2), mask_nn);
+      tile_load<D, KT, kSetSplit>(regs, K, V, k0_next, nkeys, tid, grp);
       compute(smem + (i & 1) * C::STAGE, k0_cur, mask_cur);
-      tile_store<D, KT>(regs, smem + ((i + 1) & 1) * C::STAGE, tid);
+      tile_store<D, KT, kSetSplit>(regs, smem + ((i + 1) & 1) * C::STAGE, tid, grp);
       __syncthreads();
       k0_cur = k0_next;
       mask_cur = mask_next;
+      k0_next = k0_nn;
+      mask_next = mask_nn;
     }
     if (common > 0) {
       const int i = common - 1;
-      if (extra) {
-        k0_next = entry_k0(tile_entry(i + 1), mask_next);
-        tile_load<D, KT>(regs, K, V, k0_next, nkeys, tid);
-      }
+      if (extra) tile_load<D, KT, kSetSplit>(regs, K, V, k0_next, nkeys, tid, grp);
       compute(smem + (i & 1) * C::STAGE, k0_cur, mask_cur);
-      if (NG > 1 && (ntiles % NG) != 0) {         // some group has one more tile (workgroup-uniform)
-        if (extra) tile_store<D, KT>(regs, smem + ((i + 1) & 1) * C::STAGE, tid);
+      if (TG > 1 && (ntiles % TG) != 0) {         // some group has one more tile (workgroup-uniform)
+        if (extra) tile_store<D, KT, kSetSplit>(regs, smem + ((i + 1) & 1) * C::STAGE, tid, grp);
         __syncthreads();
         if (extra) compute(smem + ((i + 1) & 1) * C::STAGE, k0_next, mask_next);
       }
@@ -409,7 +457,7 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || MODE == kPassSparseRefresh || 
       compute(smem, k0_cur, mask_cur);
     }
   }
-  if constexpr (NG > 1) {
+  if constexpr (TG > 1) {
     // hand group 1's statistics to group 0: [wave][register][lane] floats in the (now idle) LDS
     constexpr int REC = NDBL * 16 + 2;
     float* mbuf = (float*)smem_all + (size_t)wave * REC * 64 + lane;
@@ -469,6 +517,9 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || MODE == kPassSparseRefresh || 
   } else {
     const size_t rows_total = (size_t)p.B * p.Hq * p.Bq;
     const size_t wrow = (size_t)split * rows_total + grow;
+    float* __restrict__ w_o = (kSetSplit && grp == 1) ? p.ws_o2 : p.ws_o;
+    float* __restrict__ w_m = (kSetSplit && grp == 1) ? p.ws_m2 : p.ws_m;
+    float* __restrict__ w_l = (kSetSplit && grp == 1) ? p.ws_l2 : p.ws_l;
     if (row_ok) {
 #pragma unroll
       for (int db = 0; db < NDBL; ++db)
@@ -476,14 +527,14 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || MODE == kPassSparseRefresh || 
         for (int q4 = 0; q4 < 4; ++q4) {
           const int d0 = 32 * (db_base + db) + 8 * q4 + 4 * h;
           f32x4 o4 = {sel.o[db][4 * q4], sel.o[db][4 * q4 + 1], sel.o[db][4 * q4 + 2], sel.o[db][4 * q4 + 3]};
-          *(f32x4*)(p.ws_o + wrow * D + d0) = o4;
+          *(f32x4*)(w_o + wrow * D + d0) = o4;
         }
       if (h == 0 && db_base == 0) {
-        p.ws_m[wrow] = sel.m;
-        p.ws_l[wrow] = l_sel;
+        w_m[wrow] = sel.m;
+        w_l[wrow] = l_sel;
       }
     }
-    if constexpr (MODE == kPassSparseRefresh) {
+    if constexpr (MODE == kPassSparseRefresh && !kSetSplit) {
       const float l_res = res.l + __shfl_xor(res.l, 32, 64);
       if (row_ok) {
 #pragma unroll
@@ -507,7 +558,7 @@ template <int D, int MODE, int KT, int WS, int NG>
 hipError_t launch_one(const PassParams& p, hipStream_t s) {
   static bool attr_set = false;   // raising the dynamic-LDS limit is idempotent; the flag only saves calls
   auto kern = attn_bf16_kernel<D, MODE, KT, WS, NG>;
-  constexpr int lds = Cfg<D, KT>::LDS * NG;
+  constexpr int lds = Cfg<D, KT>::LDS * ((MODE == kPassSparseRefresh) ? 1 : NG);
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
@@ -548,8 +599,12 @@ hipError_t launch_d(const PassParams& p, PassMode mode, hipStream_t s) {
       }
       return launch_one<D, kPassInternal, kKeyTile, 1, 1>(p, s);
     }
-    case kPassSparseRefresh: return launch_one<D, kPassSparseRefresh, kKeyTile, 1, 1>(p, s);
-    case kPassSparseReuse: return launch_one<D, kPassSparseReuse, kKeyTile, 1, 1>(p, s);
+    case kPassSparseRefresh:
+      // 8 wavefronts, the two groups specialised by accumulator set (see the kernel)
+      return launch_one<D, kPassSparseRefresh, kKeyTile, 1, 2>(p, s);
+    case kPassSparseReuse:
+      if (p.nsplit > 1) return launch_one<D, kPassSparseReuse, kKeyTile, 1, 2>(p, s);
+      return launch_one<D, kPassSparseReuse, kKeyTile, 1, 1>(p, s);
   }
   return hipErrorInvalidValue;
 }

@@ -204,14 +204,34 @@ __global__ __launch_bounds__(256) void pool_keys_kernel(const PoolParams p) {
 }
 
 // ------------------------------------------------------------------------------ top-k
-// grid (B*Hq), 256 threads, dynamic LDS: qbar[D] | red[256] | score[nblk] | flag[nblk]
+// Order-preserving map of a float onto uint32 (larger float <-> larger key).
+__device__ __forceinline__ uint32_t order_key(float x) {
+  const uint32_t u = __float_as_uint(x);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// Workgroup-wide sum of a per-thread count (256 threads); every thread gets the total.
+__device__ __forceinline__ int block_sum(int v, int* sh4, int tid) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  __syncthreads();                 // previous readers of sh4 are done
+  if ((tid & 63) == 0) sh4[tid >> 6] = v;
+  __syncthreads();
+  return sh4[0] + sh4[1] + sh4[2] + sh4[3];
+}
+
+// grid (B*Hq), 256 threads, dynamic LDS: qbar[D] | red[256] | key[nblk] | flag[nblk]
+// Selection = the k largest scores, ties to the lower block index: the k-th largest key T is
+// found by bisection over its 32 bits (count(key >= candidate) per step), then blocks with
+// key > T are taken plus the first k - count(key > T) blocks with key == T in index order.
 __global__ __launch_bounds__(256) void select_topk_kernel(const SelectParams p) {
   extern __shared__ __align__(16) float lds[];
   float* qbar = lds;
   float* red = qbar + p.D;
-  float* score = red + 256;
-  int* flag = (int*)(score + p.nblk);
+  uint32_t* key = (uint32_t*)(red + 256);
+  int* flag = (int*)(key + p.nblk);
   __shared__ int chunk_cnt[256];
+  __shared__ int sh4[4];
 
   const int bh = blockIdx.x, b = bh / p.Hq, h = bh % p.Hq, kvh = h / p.G;
   const int D = p.D, tid = threadIdx.x, nblk = p.nblk;
@@ -240,25 +260,39 @@ __global__ __launch_bounds__(256) void select_topk_kernel(const SelectParams p) 
       s = fmaf(a.z, qbar[4 * i + 2], s);
       s = fmaf(a.w, qbar[4 * i + 3], s);
     }
-    score[c] = s;
+    key[c] = order_key(s);
   }
   __syncthreads();
-  // rank by counting: block c is kept iff fewer than k blocks beat it (ties: lower index wins)
-  for (int c = tid; c < nblk; c += 256) {
-    const float sc = score[c];
-    int beat = 0;
-    for (int j = 0; j < nblk; ++j) {
-      const float sj = score[j];
-      beat += (sj > sc) || (sj == sc && j < c);
-    }
-    flag[c] = beat < k;
+
+  uint32_t T = 0u;
+  for (int bit = 31; bit >= 0; --bit) {
+    const uint32_t cand = T | (1u << bit);
+    int mine = 0;
+    for (int c = tid; c < nblk; c += 256) mine += key[c] >= cand;
+    if (block_sum(mine, sh4, tid) >= k) T = cand;
   }
-  __syncthreads();
-  // ascending compaction: thread t owns blocks [t*per, (t+1)*per)
+  int gt = 0;
+  for (int c = tid; c < nblk; c += 256) gt += key[c] > T;
+  const int need_eq = k - block_sum(gt, sh4, tid);   // ties with the k-th key to take, lowest index first
+
+  // ascending passes over contiguous chunks: thread t owns blocks [t*per, (t+1)*per)
   const int per = (nblk + 255) / 256;
   const int c0 = min(nblk, tid * per), c1 = min(nblk, c0 + per);
   int mine = 0;
-  for (int c = c0; c < c1; ++c) mine += flag[c];
+  for (int c = c0; c < c1; ++c) mine += key[c] == T;
+  chunk_cnt[tid] = mine;
+  __syncthreads();
+  int eq_before = 0;
+  for (int t = 0; t < tid; ++t) eq_before += chunk_cnt[t];
+  __syncthreads();
+  mine = 0;
+  for (int c = c0; c < c1; ++c) {
+    const uint32_t kc = key[c];
+    int f = kc > T;
+    if (kc == T) f = (eq_before++ < need_eq);
+    flag[c] = f;
+    mine += f;
+  }
   chunk_cnt[tid] = mine;
   __syncthreads();
   int pos = 0;
