@@ -188,17 +188,30 @@ __device__ __forceinline__ void tile_compute(WaveState<Cfg<D, KT>::NDB / WS>& st
   constexpr int NKB = KT / 32;
   f32x16 s[NKB];
 #pragma unroll
-  for (int kb = 0; kb < NKB; ++kb) {
+  for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
     for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
+  // LDS operands are fetched in batches (2 k-steps x NKB key blocks) ahead of the MFMAs that use
+  // them, and the key blocks' independent accumulator chains alternate.
 #pragma unroll
-    for (int ks = 0; ks < C::NKS; ++ks) {
-      const bf16x8 a = *(const bf16x8*)(Ks + (kb * 32 + l32) * C::KSTR + (ks * 16 + 8 * h) * 2);
-      s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], s[kb], 0, 0, 0);
-    }
+  for (int ks0 = 0; ks0 < C::NKS; ks0 += 2) {
+    bf16x8 a[2][NKB];
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int kb = 0; kb < NKB; ++kb)
+        a[u][kb] = *(const bf16x8*)(Ks + (kb * 32 + l32) * C::KSTR + ((ks0 + u) * 16 + 8 * h) * 2);
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int kb = 0; kb < NKB; ++kb)
+        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u][kb], qreg[ks0 + u], s[kb], 0, 0, 0);
   }
   // s[kb][r] is the raw dot product of query row l32 with key kb*32 + 8*(r/4) + 4*h + r%4
   if (nvalid < C::KT) {
+    // the empty asm keeps this a real (wavefront-uniform) branch: left alone, the compiler turns the
+    // test into 62 compare/select instructions executed on every tile
+    asm volatile("" ::: "memory");
 #pragma unroll
     for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
@@ -243,12 +256,19 @@ __device__ __forceinline__ void tile_compute(WaveState<Cfg<D, KT>::NDB / WS>& st
       for (int r = 0; r < 16; ++r) st.o[db][r] *= alpha;
   }
 #pragma unroll
-  for (int db = 0; db < NDBL; ++db)
+  for (int t0 = 0; t0 < 2 * NKB; t0 += 2) {
+    bf16x8 a[2][NDBL];
 #pragma unroll
-    for (int t = 0; t < 2 * NKB; ++t) {
-      const bf16x8 a = *(const bf16x8*)(Vt + ((db_base + db) * 32 + l32) * C::VSTR + (t * 16 + 8 * h) * 2);
-      st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[t], st.o[db], 0, 0, 0);
-    }
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int db = 0; db < NDBL; ++db)
+        a[u][db] = *(const bf16x8*)(Vt + ((db_base + db) * 32 + l32) * C::VSTR + ((t0 + u) * 16 + 8 * h) * 2);
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int db = 0; db < NDBL; ++db)
+        st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u][db], pb[t0 + u], st.o[db], 0, 0, 0);
+  }
 }
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
@@ -409,6 +429,9 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || MODE == kPassInternal || MODE 
 
   // Steady state per iteration: issue the global loads of tile i+1 (they stay in flight in
   // registers), compute tile i from LDS, park tile i+1 in the other LDS stage, one barrier.
+  auto run_tile = [&](auto& st, const unsigned char* stage, bool on, int nvalid) {
+    tile_compute<D, KT, WS>(st, qreg, stage, p.scale_log2, on, nvalid, l32, h, db_base);
+  };
   auto compute = [&](const unsigned char* stage, int k0, uint32_t mask) {
     const int nvalid = min(C::KT, nkeys - k0);      // <= 0 only for a reuse-list tile past the end
     if constexpr (MODE == kPassSparseReuse) {
@@ -416,17 +439,17 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || MODE == kPassInternal || MODE 
     }
     if constexpr (kSetSplit) {
       const bool on = row_ok && (((mask & my_bit) != 0u) == (grp == 0));
-      if (__any(on)) tile_compute<D, KT, WS>(sel, qreg, stage, p.scale_log2, on, nvalid, l32, h, db_base);
+      if (__any(on)) run_tile(sel, stage, on, nvalid);
     } else if constexpr (MODE == kPassSparseRefresh) {
       const bool on = row_ok && (mask & my_bit);
-      if (__any(on)) tile_compute<D, KT, WS>(sel, qreg, stage, p.scale_log2, on, nvalid, l32, h, db_base);
+      if (__any(on)) run_tile(sel, stage, on, nvalid);
       const bool off = row_ok && !(mask & my_bit);
-      if (__any(off)) tile_compute<D, KT, WS>(res, qreg, stage, p.scale_log2, off, nvalid, l32, h, db_base);
+      if (__any(off)) run_tile(res, stage, off, nvalid);
     } else if constexpr (MODE == kPassSparseReuse) {
       const bool on = row_ok && (mask & my_bit);
-      if (__any(on)) tile_compute<D, KT, WS>(sel, qreg, stage, p.scale_log2, on, nvalid, l32, h, db_base);
+      if (__any(on)) run_tile(sel, stage, on, nvalid);
     } else {
-      tile_compute<D, KT, WS>(sel, qreg, stage, p.scale_log2, true, nvalid, l32, h, db_base);
+      run_tile(sel, stage, true, nvalid);
     }
   };
 
