@@ -188,10 +188,21 @@ def profile_external(dev, n_blocks, R):
             "refresh_step_ms": med(refresh), "reuse_step_ms": med(reuse), "launches": len(attn)}
 
 
+def read_traffic(workload_name):
+    """HBM bytes per launch of the external-pass kernel as measured with rocprofv3 --pmc FETCH_SIZE /
+    WRITE_SIZE and recorded (with the commands) in profiles/; None if no such record exists."""
+    tpath = os.path.join(ROOT, "profiles", f"attn_bf16_external_{workload_name}_hbm_traffic.txt")
+    if os.path.exists(tpath):
+        for ln in open(tpath):
+            if ln.startswith("hbm_bytes_per_launch"):
+                return int(float(ln.split("=")[1].split()[0]))
+    return None
+
+
 def roofline_obj(w, attn_ms, traffic=None):
     alg = external_algorithmic_bytes(w)
     ach = alg / (attn_ms * 1e-3) / 1e9
-    return {"bound": "hbm", "kernel": "fb::attn_bf16_kernel<128, dense> (external pass)",
+    return {"bound": "hbm", "kernel": "fb::attn_bf16_kernel<128, 0, 64, 1, 2> (external pass, streaming attention kernel)",
             "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": traffic,
             "algorithmic_bytes_per_launch": alg, "avg_launch_us": round(attn_ms * 1e3, 2)}
@@ -377,12 +388,7 @@ def main():
     sec_eager = time_steps(dev, min(K, 800), min(W, 80), w.refresh, False)
     prof = profile_external(dev, 41, w.refresh)
 
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"attn_bf16_external_{w.name}_hbm_traffic.txt")
-    if os.path.exists(tpath):       # measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, see that file
-        for ln in open(tpath):
-            if ln.startswith("hbm_bytes_per_launch"):
-                traffic = int(float(ln.split("=")[1].split()[0]))
+    traffic = read_traffic(w.name)
     line = {
         "metric": "attention us per diffusion step (cached block-external attention, 32K context); "
                   "external-pass HBM GB/s in roofline / external_128k",
@@ -410,7 +416,7 @@ def main():
         for _ in range(3):
             d2.step(0, 0, wl128.refresh)
         p2 = profile_external(d2, 21, wl128.refresh)
-        r2 = roofline_obj(wl128, p2["attn_ms"])
+        r2 = roofline_obj(wl128, p2["attn_ms"], read_traffic(wl128.name))
         r2["workload"] = describe(wl128)
         r2["external_call_us"] = round((p2["attn_ms"] + p2["combine_ms"]) * 1e3, 2)
         r2["refresh_step_us"] = round(p2["refresh_step_ms"] * 1e3, 2)
