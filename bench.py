@@ -321,7 +321,7 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-extras", action="store_true", help="skip the video-shaped (MFMA) and sparse measurements")
     ap.add_argument("--profile-external", type=int, default=0, metavar="N",
-                    help="only run N refresh steps of the workload (for rocprofv3), print nothing else")
+                    help="only run N whole blocks of the workload, eagerly (for rocprofv3), print nothing else")
     ap.add_argument("--profile-sparse", type=int, default=0, metavar="N",
                     help="only run N sparse refresh + reuse call pairs of the sparse_64k workload (for rocprofv3)")
     ap.add_argument("--profile-copy", type=int, default=0, metavar="N",
@@ -370,11 +370,14 @@ def main():
         print(f"ran {args.profile_sparse} sparse refresh+reuse pairs of {ws_.name}")
         return
     if args.profile_external > 0:
+        # the same loop as the event-timed pass of the benchmark: whole blocks, one refresh step and
+        # steps-1 reuse steps each, K/V sets rotated per block
         d = DeviceBlock(w, max(2, min(4, int(-(-600e6 // w.kv_bytes)))))
-        for i in range(args.profile_external):
-            d.step(0, i % d.nsets, w.refresh)
+        for b in range(args.profile_external):
+            for t in range(w.steps):
+                d.step(t, b % d.nsets, w.refresh)
         torch.cuda.synchronize()
-        print(f"ran {args.profile_external} refresh steps of {w.name}")
+        print(f"ran {args.profile_external} blocks of {w.steps} steps of {w.name}")
         return
     K, W = args.steps, args.warmup
     nsets = max(2, min(4, int(-(-600e6 // w.kv_bytes))))     # working set well beyond the last-level cache

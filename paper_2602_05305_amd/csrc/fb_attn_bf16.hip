@@ -333,6 +333,7 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || MODE == kPassInternal || MODE 
   const int row = rt * ROWS + (wave / WS) * 32 + l32;      // group-flattened row of this lane
   const bool row_ok = row < nrows;
   const size_t grow = (size_t)(b * p.Hq + kvh * p.G) * p.Bq + row;   // global row index
+  const size_t grow_last = (size_t)(b * p.Hq + kvh * p.G) * p.Bq + (nrows - 1);
 
   const __bf16* __restrict__ Q = (const __bf16*)p.q;
   const __bf16* __restrict__ K = (const __bf16*)p.k + (size_t)bk * nkeys * D;
@@ -395,8 +396,9 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || MODE == kPassInternal || MODE 
   bf16x8 qreg[C::NKS];
 #pragma unroll
   for (int ks = 0; ks < C::NKS; ++ks) {
-    u32x4 u = {0u, 0u, 0u, 0u};
-    if (row_ok) u = gload128(Q + grow * D + ks * 16 + 8 * h);
+    // rows past the end load the group's last row instead (branch-free, in bounds); whatever
+    // they compute is never stored
+    const u32x4 u = gload128(Q + (row_ok ? grow : grow_last) * D + ks * 16 + 8 * h);
     qreg[ks] = __builtin_bit_cast(bf16x8, u);
   }
 
@@ -550,7 +552,9 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || MODE == kPassInternal || MODE 
         for (int q4 = 0; q4 < 4; ++q4) {
           const int d0 = 32 * (db_base + db) + 8 * q4 + 4 * h;
           f32x4 o4 = {sel.o[db][4 * q4], sel.o[db][4 * q4 + 1], sel.o[db][4 * q4 + 2], sel.o[db][4 * q4 + 3]};
-          *(f32x4*)(w_o + wrow * D + d0) = o4;
+          // streaming store: the partials are read next by another kernel, never again by this
+          // one; written through, they do not pile up as dirty L2 lines to flush at kernel end
+          __builtin_nontemporal_store(o4, (f32x4*)(w_o + wrow * D + d0));
         }
       if (h == 0 && db_base == 0) {
         w_m[wrow] = sel.m;

@@ -114,6 +114,22 @@ def test_bf16_split_counts(n_splits):
     _compare_block(_wl("bf16", 1, 8, 2, 128, 2000, 32), seed=23, n_splits=n_splits)
 
 
+@pytest.mark.parametrize("P,n_splits", [(1617, 3), (1088, 2), (2048, 4), (64 * 9, 1), (64 * 16 + 1, 2)])
+def test_bf16_wavefront_group_paths(P, n_splits):
+    """Split counts that select the 8-wavefront workgroups (>= 8 tiles per split): even and odd
+    tile counts per workgroup (one group streams one tile more), ragged last tile."""
+    _compare_block(_wl("bf16", 1, 8, 2, 128, P, 32), seed=25, n_splits=n_splits)
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,d,P,Bq", [
+    (1, 16, 2, 128, 700, 16),    # 8 query heads per KV head
+    (1, 32, 1, 64, 300, 4),      # 32 query heads per KV head (the maximum), d = 64
+    (3, 4, 2, 128, 500, 32),     # batch 3
+])
+def test_bf16_head_groupings(B, Hq, Hkv, d, P, Bq):
+    _compare_block(_wl("bf16", B, Hq, Hkv, d, P, Bq), seed=27)
+
+
 def test_bf16_llm_scaling_inputs():
     """Inputs drawn as in the LLM-shaped configs (N(0,1)/sqrt(128)), prefix a few thousand."""
     w = wl.CONFIGS["llm_32k"].with_(prefix_len=4096 + 37, steps=4, refresh=4)

@@ -288,6 +288,17 @@ def test_topk_ties_go_to_lower_index_and_bruteforce():
             assert idx[b, h].tolist() == sorted(np.argsort(-np.array(sc), kind="stable")[:5].tolist())
 
 
+def test_selection_key_mask_hand_example():
+    """Block c covers tokens [c*kb, min(P, (c+1)*kb)): 7 tokens in blocks of 3, last block short."""
+    idx = np.array([[[1], [2]]], dtype=np.int32)
+    m = orc.selection_key_mask(idx, 7, 3)
+    assert m[0, 0].tolist() == [False, False, False, True, True, True, False]
+    assert m[0, 1].tolist() == [False] * 6 + [True]
+    both = orc.selection_key_mask(np.array([[[0, 2], [-1, 1]]], dtype=np.int32), 7, 3)
+    assert both[0, 0].tolist() == [True, True, True, False, False, False, True]
+    assert both[0, 1].tolist() == [False, False, False, True, True, True, False]      # negative entries are skipped
+
+
 def _sparse_steps(seed):
     Q0, Kp, Vp, Kb0, Vb0 = _small_problem(seed, B=1, Hq=4, Hkv=2, d=8, P=45, Bq=4)
     steps = [(Q0, Kb0, Vb0)]
@@ -305,7 +316,10 @@ def test_sparse_reuse_equals_augmented_sdpa():
     res = orc.run_block_sparse(Kp, Vp, steps, R=4, key_block=kb, topk=topk)
     idx = res[0]["idx"]
     assert all((r["idx"] == idx).all() for r in res)            # selection frozen within the block
-    kmask = orc.selection_key_mask(idx, P, kb)
+    kmask = np.zeros((1, 4, P), dtype=bool)          # built here, not by the oracle's own helper
+    for h in range(4):
+        for c in idx[0, h]:
+            kmask[0, h, int(c) * kb:min(P, (int(c) + 1) * kb)] = True
     assert kmask.sum(axis=-1).max() <= topk * kb
     Q0 = steps[0][0]
     for t, (Q, Kb, Vb) in enumerate(steps):
