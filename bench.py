@@ -255,6 +255,9 @@ def video_extra(torch, fb, wl):
     q, kb, vb = d.steps[0]
     t_ext = _ev_median_us(torch, lambda: fb.fb_external_partial(d.shape, q, d.K[0], d.V[0], d.o, d.m, d.lse, d.ws), 7, 2)
     t_int = _ev_median_us(torch, lambda: fb.fb_internal_merge(d.shape, q, kb, vb, d.o, d.m, d.lse, d.out, None), 7, 2)
+    hm = torch.zeros((w.batch, w.n_q_heads), device="cuda", dtype=torch.uint8)
+    hm[:, ::2] = 1                       # head-wise selective refresh: every other head recomputed
+    t_half = _ev_median_us(torch, lambda: fb.fb_external_partial_heads(d.shape, q, d.K[0], d.V[0], hm, d.o, d.m, d.lse, d.ws), 7, 2)
     f_ext = 4.0 * w.batch * w.n_q_heads * w.block_len * w.prefix_len * w.head_dim
     f_int = 4.0 * w.batch * w.n_q_heads * w.block_len * w.block_len * w.head_dim
     peak = 2500.0
@@ -262,6 +265,7 @@ def video_extra(torch, fb, wl):
     return {"workload": describe(w), "bound": "mfma", "peak": peak, "unit": "TFLOP/s",
             "external_us": round(t_ext, 1), "external_tflops": round(f_ext / t_ext / 1e6, 1),
             "external_frac": round(f_ext / t_ext / 1e6 / peak, 4),
+            "external_half_of_heads_us": round(t_half, 1),
             "internal_us": round(t_int, 1), "internal_tflops": round(f_int / t_int / 1e6, 1),
             "internal_frac": round(f_int / t_int / 1e6 / peak, 4),
             "block_speedup_cached_vs_full": round(S * (t_ext + t_int) / (-(-S // R) * t_ext + S * t_int), 3)}

@@ -138,6 +138,30 @@ fb_status fb_external_partial_prof(const fb_shape* shape, const void* q, const v
                                    void* ev_end, void* hip_stream);
 
 /*
+ * Head-wise selective refresh (Section 4.2, "Selective reuse": for video models only heads whose
+ * block-external attention is not stable enough across steps are recomputed): fb_external_partial
+ * restricted to the query heads with head_mask[b * n_q_heads + h] != 0.  The (o, m, lse) rows of
+ * the other heads are left exactly as they are (their cached partial stays in force).  Which
+ * heads to refresh is the caller's policy.  head_mask: device, uint8 [B,Hq], required.
+ * KV groups none of whose query heads is flagged are not streamed at all.
+ */
+fb_status fb_external_partial_heads(const fb_shape* shape, const void* q, const void* k_prefix,
+                                    const void* v_prefix, const uint8_t* head_mask, float* o_part,
+                                    float* m_part, float* lse_part, void* workspace,
+                                    size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Cross-step similarity of block-external attention per head (Section 3 / Figure 1, used to
+ * calibrate the head-wise reuse threshold of Section 4.2): sim[b,h] = mean over the block's rows
+ * of the cosine similarity between the external attention outputs A_out of two partials, e.g.
+ * the cached one and a freshly computed one.  Only the o tensors are needed: A_out is o times a
+ * positive per-row scalar.  A row that is zero in either partial counts as similarity 0.
+ *   in : o_a, o_b [B,Hq,Bq,d] float;  out: sim [B,Hq] float.
+ */
+fb_status fb_head_similarity(const fb_shape* shape, const float* o_a, const float* o_b, float* sim,
+                             void* hip_stream);
+
+/*
  * One diffusion step with a cached external partial (Algorithm 1): block-internal attention
  * of q against the block's own current k_block/v_block, bidirectional (Eq. 7), composed in
  * the kernel's epilogue with the cached (o_part, m_part, lse_part) by Eq. 8-9.

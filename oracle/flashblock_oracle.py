@@ -312,6 +312,20 @@ def run_block_sparse(K_prefix, V_prefix, steps, R, key_block, topk, scale=None):
 
 
 # --------------------------------------------------------------------------------------
+# Cross-step similarity (Section 3, Figure 1; calibration of the head-wise threshold, Section 4.2)
+# --------------------------------------------------------------------------------------
+def head_similarity(part_a, part_b):
+    """[B,Hq]: mean over the block's rows of the cosine similarity between the normalised
+    block-external outputs A_out of two partials (a zero row counts as similarity 0)."""
+    A, Bm = normalized(part_a), normalized(part_b)
+    num = (A * Bm).sum(axis=-1)
+    den = np.sqrt((A * A).sum(axis=-1)) * np.sqrt((Bm * Bm).sum(axis=-1))
+    with np.errstate(divide="ignore", invalid="ignore"):
+        cos = np.where(den > 0, num / np.where(den > 0, den, 1.0), 0.0)
+    return cos.mean(axis=-1)
+
+
+# --------------------------------------------------------------------------------------
 # Cache footprint (Section 4.4 complexity paragraph; Table 5 "Extra Mem.")
 # --------------------------------------------------------------------------------------
 def cache_bytes_paper_layout(n_layers, n_heads, block_rows, head_dim, batch=1,

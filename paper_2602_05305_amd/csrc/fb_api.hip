@@ -184,13 +184,19 @@ size_t fb_workspace_bytes(const fb_shape* shape, int32_t key_block, int32_t topk
   return t > 0 ? t : 256;
 }
 
-fb_status fb_external_partial_prof(const fb_shape* shape, const void* q, const void* k_prefix,
-                                   const void* v_prefix, float* o_part, float* m_part, float* lse_part,
-                                   int32_t n_splits, void* workspace, size_t workspace_bytes,
-                                   void* ev_begin, void* ev_attn_end, void* ev_end, void* hip_stream) {
+}  // extern "C"
+
+namespace {
+
+fb_status external_partial_impl(const fb_shape* shape, const void* q, const void* k_prefix,
+                                const void* v_prefix, const uint8_t* head_mask, bool use_head_mask,
+                                float* o_part, float* m_part, float* lse_part,
+                                int32_t n_splits, void* workspace, size_t workspace_bytes,
+                                void* ev_begin, void* ev_attn_end, void* ev_end, void* hip_stream) {
   fb_status st = check_shape(shape);
   if (st != FB_OK) return st;
   if (!q || !o_part || !m_part || !lse_part) return FB_ERR_NULL;
+  if (use_head_mask && !head_mask) return FB_ERR_NULL;
   if (shape->prefix_len > 0 && (!k_prefix || !v_prefix)) return FB_ERR_NULL;
   if (n_splits < 0 || n_splits > FB_MAX_SPLITS) return FB_ERR_SHAPE;
   if (!aligned16(q) || !aligned16(k_prefix) || !aligned16(v_prefix) || !aligned16(o_part) ||
@@ -204,9 +210,10 @@ fb_status fb_external_partial_prof(const fb_shape* shape, const void* q, const v
   char* ws = (char*)workspace;
   fb::PassParams p = base_pass(shape, q, k_prefix, v_prefix, shape->prefix_len, ns);
   p.ws_o = (float*)(ws + w.o[0]); p.ws_m = (float*)(ws + w.m[0]); p.ws_l = (float*)(ws + w.l[0]);
+  p.head_on = use_head_mask ? head_mask : nullptr;
   hipError_t e = hipSuccess;
   if (ev_begin && (e = hipEventRecord((hipEvent_t)ev_begin, stream)) != hipSuccess) return hip_fail(e);
-  e = launch_attn(shape, p, fb::kPassDense, stream);
+  e = launch_attn(shape, p, use_head_mask ? fb::kPassDenseHeads : fb::kPassDense, stream);
   if (e != hipSuccess) return hip_fail(e);
   if (ev_attn_end && (e = hipEventRecord((hipEvent_t)ev_attn_end, stream)) != hipSuccess) return hip_fail(e);
 
@@ -215,10 +222,31 @@ fb_status fb_external_partial_prof(const fb_shape* shape, const void* q, const v
   c.rows = (int)rows_of(shape); c.D = shape->head_dim; c.nsplit = ns;
   c.ws_o = p.ws_o; c.ws_m = p.ws_m; c.ws_l = p.ws_l;
   c.o = o_part; c.m = m_part; c.lse = lse_part;
+  c.head_on = p.head_on; c.Bq = shape->block_len;
   e = fb::launch_combine(c, stream);
   if (e != hipSuccess) return hip_fail(e);
   if (ev_end && (e = hipEventRecord((hipEvent_t)ev_end, stream)) != hipSuccess) return hip_fail(e);
   return FB_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+fb_status fb_external_partial_prof(const fb_shape* shape, const void* q, const void* k_prefix,
+                                   const void* v_prefix, float* o_part, float* m_part, float* lse_part,
+                                   int32_t n_splits, void* workspace, size_t workspace_bytes,
+                                   void* ev_begin, void* ev_attn_end, void* ev_end, void* hip_stream) {
+  return external_partial_impl(shape, q, k_prefix, v_prefix, nullptr, false, o_part, m_part, lse_part, n_splits,
+                               workspace, workspace_bytes, ev_begin, ev_attn_end, ev_end, hip_stream);
+}
+
+fb_status fb_external_partial_heads(const fb_shape* shape, const void* q, const void* k_prefix,
+                                    const void* v_prefix, const uint8_t* head_mask, float* o_part,
+                                    float* m_part, float* lse_part, void* workspace, size_t workspace_bytes,
+                                    void* hip_stream) {
+  return external_partial_impl(shape, q, k_prefix, v_prefix, head_mask, true, o_part, m_part, lse_part, 0,
+                               workspace, workspace_bytes, nullptr, nullptr, nullptr, hip_stream);
 }
 
 fb_status fb_external_partial_ex(const fb_shape* shape, const void* q, const void* k_prefix,
@@ -234,6 +262,18 @@ fb_status fb_external_partial(const fb_shape* shape, const void* q, const void* 
                               void* workspace, size_t workspace_bytes, void* hip_stream) {
   return fb_external_partial_ex(shape, q, k_prefix, v_prefix, o_part, m_part, lse_part, 0, workspace,
                                 workspace_bytes, hip_stream);
+}
+
+fb_status fb_head_similarity(const fb_shape* shape, const float* o_a, const float* o_b, float* sim,
+                             void* hip_stream) {
+  fb_status st = check_shape(shape);
+  if (st != FB_OK) return st;
+  if (!o_a || !o_b || !sim) return FB_ERR_NULL;
+  if (!aligned16(o_a) || !aligned16(o_b) || !aligned16(sim)) return FB_ERR_ALIGN;
+  hipError_t e = fb::launch_head_similarity(o_a, o_b, sim, shape->batch * shape->n_q_heads, shape->block_len,
+                                            shape->head_dim, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return hip_fail(e);
+  return FB_OK;
 }
 
 fb_status fb_internal_merge(const fb_shape* shape, const void* q, const void* k_block,

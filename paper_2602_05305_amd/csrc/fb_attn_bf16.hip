@@ -284,7 +284,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
 // own pair of LDS stages, and group 1 hands its statistics to group 0 through LDS at the end.
 // Same wavefronts per CU as two 4-wave workgroups, half as many split partials to write and fold.
 template <int D, int MODE, int KT, int WS, int NG>
-__global__ __launch_bounds__(256 * NG, (NG > 1 || MODE == kPassInternal || MODE == kPassSparseRefresh) ? 1 : 2) void attn_bf16_kernel(const PassParams p) {
+__global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS > 1) || MODE == kPassSparseRefresh) ? 1 : 2) void attn_bf16_kernel(const PassParams p) {
   using C = Cfg<D, KT>;
   extern __shared__ __align__(16) unsigned char smem_all[];
   // Sparse refresh with NG = 2: the two wavefront groups are specialised by accumulator set
@@ -294,7 +294,7 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || MODE == kPassInternal || MODE 
   // instead of the one that two sets in a single wavefront allow.
   constexpr bool kSetSplit = (MODE == kPassSparseRefresh && NG == 2);
   constexpr int TG = kSetSplit ? 1 : NG;          // wavefront groups that own separate tile streams
-  static_assert(NG == 1 || MODE == kPassDense || MODE == kPassSparseReuse || kSetSplit, "unsupported group mode");
+  static_assert(NG == 1 || MODE == kPassDense || MODE == kPassDenseHeads || MODE == kPassSparseReuse || kSetSplit, "unsupported group mode");
 
   const int grp = (NG > 1) ? (int)(threadIdx.x >> 8) : 0;
   const int tid = threadIdx.x & 255, lane = tid & 63, wave = tid >> 6;
@@ -334,6 +334,13 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || MODE == kPassInternal || MODE 
   const bool row_ok = row < nrows;
   const size_t grow = (size_t)(b * p.Hq + kvh * p.G) * p.Bq + row;   // global row index
   const size_t grow_last = (size_t)(b * p.Hq + kvh * p.G) * p.Bq + (nrows - 1);
+  bool head_active = true;
+  if constexpr (MODE == kPassDenseHeads) {
+    // per-head refresh: rows of heads whose flag is 0 sit every tile out; a workgroup none of
+    // whose rows is active leaves before it touches K/V
+    head_active = row_ok && p.head_on[b * p.Hq + kvh * p.G + row / p.Bq] != 0;
+    if (!__syncthreads_or(head_active ? 1 : 0)) return;
+  }
 
   const __bf16* __restrict__ Q = (const __bf16*)p.q;
   const __bf16* __restrict__ K = (const __bf16*)p.k + (size_t)bk * nkeys * D;
@@ -402,13 +409,15 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || MODE == kPassInternal || MODE 
     qreg[ks] = __builtin_bit_cast(bf16x8, u);
   }
 
-  // Internal pass: the cached external partial is independent of everything computed here, so
-  // its loads are issued up front and complete under the attention work (the pass is a chain
-  // of memory latencies, not of arithmetic).
+  // Internal pass: the cached external partial is independent of everything computed here.  In
+  // the small (column-split) pass, which is a chain of memory latencies, its loads are issued up
+  // front and complete under the attention work; in the large pass, where registers decide how
+  // many wavefronts fit a SIMD, they are issued only in front of the epilogue.
   constexpr int NEO = (MODE == kPassInternal) ? NDBL * 4 : 1;
+  constexpr bool kExtEarly = (WS > 1);
   f32x4 eo[NEO];
   float ext_m_v = -INFINITY, ext_lse_v = -INFINITY;
-  if constexpr (MODE == kPassInternal) {
+  auto load_ext = [&]() {
     typedef const __attribute__((address_space(1))) f32x4* gptr_f4;
     typedef const __attribute__((address_space(1))) float* gptr_f;
     const bool have = (p.ext_o != nullptr) && row_ok;
@@ -423,7 +432,8 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || MODE == kPassInternal || MODE 
         for (int q4 = 0; q4 < 4; ++q4)
           eo[db * 4 + q4] = *(gptr_f4)(p.ext_o + grow * D + 32 * (db_base + db) + 8 * q4 + 4 * h);
     }
-  }
+  };
+  if constexpr (MODE == kPassInternal && kExtEarly) load_ext();
   WaveState<NDBL> sel;
   sel.init();
   WaveState<(MODE == kPassSparseRefresh && !kSetSplit) ? NDBL : 1> res;
@@ -450,6 +460,8 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || MODE == kPassInternal || MODE 
     } else if constexpr (MODE == kPassSparseReuse) {
       const bool on = row_ok && (mask & my_bit);
       if (__any(on)) run_tile(sel, stage, on, nvalid);
+    } else if constexpr (MODE == kPassDenseHeads) {
+      if (__any(head_active)) run_tile(sel, stage, head_active, nvalid);
     } else {
       run_tile(sel, stage, true, nvalid);
     }
@@ -511,6 +523,7 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || MODE == kPassInternal || MODE 
   // ---------------------------------------------------------------- epilogue
   const float l_sel = sel.l + __shfl_xor(sel.l, 32, 64);
   if constexpr (MODE == kPassInternal) {
+    if constexpr (!kExtEarly) load_ext();
     if (!row_ok) return;
     float me2 = -INFINITY, le = 0.f;
     if (ext_lse_v != -INFINITY) {
@@ -629,6 +642,11 @@ hipError_t launch_d(const PassParams& p, PassMode mode, hipStream_t s) {
     case kPassSparseRefresh:
       // 8 wavefronts, the two groups specialised by accumulator set (see the kernel)
       return launch_one<D, kPassSparseRefresh, kKeyTile, 1, 2>(p, s);
+    case kPassDenseHeads: {
+      const int tiles = (p.nkeys + kKeyTile - 1) / kKeyTile;
+      if (p.nsplit > 1 && tiles >= 8 * p.nsplit) return launch_one<D, kPassDenseHeads, kKeyTile, 1, 2>(p, s);
+      return launch_one<D, kPassDenseHeads, kKeyTile, 1, 1>(p, s);
+    }
     case kPassSparseReuse:
       if (p.nsplit > 1) return launch_one<D, kPassSparseReuse, kKeyTile, 1, 2>(p, s);
       return launch_one<D, kPassSparseReuse, kKeyTile, 1, 1>(p, s);

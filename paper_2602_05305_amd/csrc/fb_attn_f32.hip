@@ -76,6 +76,9 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const PassParams p) {
   const int split = blockIdx.z;
   const int row = chunk * 4 + wave;
   const bool valid = row < p.Bq;
+  if constexpr (MODE == kPassDenseHeads) {
+    if (p.head_on[bh] == 0) return;     // workgroup-uniform: this head keeps its cached partial
+  }
   const int nkeys = p.nkeys;
   const int bk = b * p.Hkv + kvh;
 
@@ -202,6 +205,7 @@ hipError_t launch_d(const PassParams& p, PassMode mode, hipStream_t s) {
     case kPassInternal: hipLaunchKernelGGL((attn_f32_kernel<D, kPassInternal>), grid, block, 0, s, p); break;
     case kPassSparseRefresh: hipLaunchKernelGGL((attn_f32_kernel<D, kPassSparseRefresh>), grid, block, 0, s, p); break;
     case kPassSparseReuse: hipLaunchKernelGGL((attn_f32_kernel<D, kPassSparseReuse>), grid, block, 0, s, p); break;
+    case kPassDenseHeads: hipLaunchKernelGGL((attn_f32_kernel<D, kPassDenseHeads>), grid, block, 0, s, p); break;
   }
   return hipGetLastError();
 }

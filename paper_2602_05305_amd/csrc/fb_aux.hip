@@ -104,6 +104,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const CombineParams p) {
   if (idx >= (size_t)p.rows * per_row) return;
   const size_t row = idx / per_row;
   const int c4 = (int)(idx % per_row);
+  if (p.head_on != nullptr && p.head_on[row / p.Bq] == 0) return;
   Folded sel = empty_folded(), res = empty_folded();
   if (p.ws_o != nullptr && p.nsplit > 0) sel = fold_splits(p.ws_o, p.ws_m, p.ws_l, p.nsplit, p.rows, row, p.D, c4);
   const bool have_res_set = p.ws_o2 != nullptr;
@@ -163,6 +164,7 @@ __global__ __launch_bounds__(256) void combine_wide_kernel(const CombineParams p
   const int per_row = p.D / 4, nsl = 256 / per_row;
   const int tid = threadIdx.x, sl = tid / per_row, c4 = tid % per_row;
   const size_t row = blockIdx.x;
+  if (p.head_on != nullptr && p.head_on[row / p.Bq] == 0) return;   // workgroup-uniform
   const bool have_res_set = p.ws_o2 != nullptr;
   sh[0][tid] = fold_strided(p.ws_o, p.ws_m, p.ws_l, p.nsplit, p.rows, row, p.D, c4, sl, nsl);
   if (have_res_set) sh[1][tid] = fold_strided(p.ws_o2, p.ws_m2, p.ws_l2, p.nsplit, p.rows, row, p.D, c4, sl, nsl);
@@ -339,7 +341,45 @@ __global__ __launch_bounds__(256) void build_masks_kernel(const MaskParams p) {
   if (tid == 255) p.union_cnt[bk] = pos;
 }
 
+// ------------------------------------------------------------------------------ similarity
+// Mean over a head's rows of the cosine similarity between two partials' output rows.  The
+// normalised output A = o * e^{m-lse} is o times a positive scalar, so cos(A_a, A_b) = cos(o_a, o_b).
+// grid (B*Hq), 256 threads: wavefront w takes rows w, w+4, ...; lanes stride the columns.
+__global__ __launch_bounds__(256) void head_similarity_kernel(const float* __restrict__ oa, const float* __restrict__ ob,
+                                                              float* __restrict__ sim, int Bq, int D) {
+  __shared__ float part[4];
+  const int bh = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  float acc = 0.f;
+  for (int r = wave; r < Bq; r += 4) {
+    const float* a = oa + ((size_t)bh * Bq + r) * D;
+    const float* b = ob + ((size_t)bh * Bq + r) * D;
+    float ab = 0.f, aa = 0.f, bb = 0.f;
+    for (int d = lane; d < D; d += 64) {
+      const float x = a[d], y = b[d];
+      ab = fmaf(x, y, ab);
+      aa = fmaf(x, x, aa);
+      bb = fmaf(y, y, bb);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      ab += __shfl_xor(ab, o, 64);
+      aa += __shfl_xor(aa, o, 64);
+      bb += __shfl_xor(bb, o, 64);
+    }
+    const float den = sqrtf(aa) * sqrtf(bb);
+    acc += den > 0.f ? ab / den : 0.f;       // a zero row (empty key set) counts as similarity 0
+  }
+  if (lane == 0) part[wave] = acc;
+  __syncthreads();
+  if (tid == 0) sim[bh] = (part[0] + part[1] + part[2] + part[3]) / (float)Bq;
+}
+
 }  // namespace
+
+hipError_t launch_head_similarity(const float* o_a, const float* o_b, float* sim, int BH, int Bq, int D, hipStream_t s) {
+  hipLaunchKernelGGL(head_similarity_kernel, dim3(BH), dim3(256), 0, s, o_a, o_b, sim, Bq, D);
+  return hipGetLastError();
+}
 
 hipError_t launch_combine(const CombineParams& p, hipStream_t s) {
   const size_t n = (size_t)p.rows * (p.D / 4);

@@ -40,7 +40,8 @@ enum PassMode : int {
   kPassDense = 0,          // keys [0, nkeys) cut into nsplit tile ranges -> split partials
   kPassInternal = 1,       // keys [0, nkeys), no split; epilogue = Eq. 8-9 merge with cached partial
   kPassSparseRefresh = 2,  // like dense, but every key block is routed to the selected or the residual set
-  kPassSparseReuse = 3     // only key blocks of the per-KV-group union list; selected set only
+  kPassSparseReuse = 3,    // only key blocks of the per-KV-group union list; selected set only
+  kPassDenseHeads = 4      // dense, but only query heads flagged in head_on take part (others keep their cache)
 };
 
 // One attention pass.  Rows of one KV group are addressed "group-flattened": query head
@@ -64,6 +65,7 @@ struct PassParams {
   const int32_t* union_list;  // [B,Hkv,nblk] ascending blocks with mask != 0
   const int32_t* union_cnt;   // [B,Hkv]
   int key_block, nblk;
+  const uint8_t* head_on;     // [B,Hq] per-head refresh flags (kPassDenseHeads), else null
   FastDiv div_rowtiles, div_nsplit, div_hkv;   // bf16 pass: decomposition of the linear workgroup index
 };
 
@@ -75,6 +77,7 @@ struct CombineParams {
   const float* res_in_o; const float* res_in_m; const float* res_in_lse;   // cached residual (reuse) or null
   float* res_out_o; float* res_out_m; float* res_out_lse;                  // residual out (refresh) or null
   float* o; float* m; float* lse;                                          // total out
+  const uint8_t* head_on; int Bq;   // if head_on != null: rows of heads with a zero flag are left untouched
 };
 
 struct SelectParams {
@@ -99,6 +102,7 @@ hipError_t launch_combine(const CombineParams& p, hipStream_t s);
 hipError_t launch_pool_keys(const PoolParams& p, hipStream_t s);
 hipError_t launch_select_topk(const SelectParams& p, hipStream_t s);
 hipError_t launch_build_masks(const MaskParams& p, hipStream_t s);
+hipError_t launch_head_similarity(const float* o_a, const float* o_b, float* sim, int BH, int Bq, int D, hipStream_t s);
 
 // Row tiles (workgroups along the group-flattened row axis) per KV group, per kernel family.
 constexpr int kRowsPerWgBf16 = 128;  // 4 waves x 32 rows

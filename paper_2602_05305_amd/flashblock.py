@@ -44,6 +44,8 @@ _SIGNATURES = {
     "fb_external_partial": (c_int, [POINTER(fb_shape)] + [c_void_p] * 7 + [c_size_t, c_void_p]),
     "fb_external_partial_ex": (c_int, [POINTER(fb_shape)] + [c_void_p] * 6 + [c_int32, c_void_p, c_size_t, c_void_p]),
     "fb_external_partial_prof": (c_int, [POINTER(fb_shape)] + [c_void_p] * 6 + [c_int32, c_void_p, c_size_t] + [c_void_p] * 4),
+    "fb_external_partial_heads": (c_int, [POINTER(fb_shape)] + [c_void_p] * 8 + [c_size_t, c_void_p]),
+    "fb_head_similarity": (c_int, [POINTER(fb_shape)] + [c_void_p] * 4),
     "fb_internal_merge": (c_int, [POINTER(fb_shape)] + [c_void_p] * 9),
     "fb_pool_keys": (c_int, [POINTER(fb_shape), c_void_p, c_int32, c_void_p, c_void_p]),
     "fb_select_topk": (c_int, [POINTER(fb_shape), c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p]),
@@ -135,6 +137,19 @@ def fb_external_partial_prof(shape, q, k_prefix, v_prefix, o_part, m_part, lse_p
                                                  workspace.numel() * workspace.element_size(), ev_begin, ev_attn_end,
                                                  ev_end, _stream(stream))
     _check(st, "fb_external_partial_prof")
+
+
+def fb_external_partial_heads(shape, q, k_prefix, v_prefix, head_mask, o_part, m_part, lse_part, workspace, stream=None):
+    st = load_library().fb_external_partial_heads(ctypes.byref(shape), _ptr(q), _ptr(k_prefix), _ptr(v_prefix),
+                                                  _ptr(head_mask), _ptr(o_part), _ptr(m_part), _ptr(lse_part),
+                                                  _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                                  _stream(stream))
+    _check(st, "fb_external_partial_heads")
+
+
+def fb_head_similarity(shape, o_a, o_b, sim, stream=None):
+    st = load_library().fb_head_similarity(ctypes.byref(shape), _ptr(o_a), _ptr(o_b), _ptr(sim), _stream(stream))
+    _check(st, "fb_head_similarity")
 
 
 def fb_internal_merge(shape, q, k_block, v_block, o_part, m_part, lse_part, out, lse_out=None, stream=None):

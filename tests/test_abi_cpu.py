@@ -106,6 +106,16 @@ def test_external_partial_error_paths():
         fb.FB_ERR_WORKSPACE,)
 
 
+def test_external_partial_heads_error_paths():
+    lib = fb.load_library()
+    s = _ok_shape()
+    ws_bytes = fb.fb_workspace_bytes(s)
+    call = lib.fb_external_partial_heads
+    assert call(ctypes.byref(s), FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE, ws_bytes, None) == fb.FB_ERR_NULL
+    assert call(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, ws_bytes - 1, None) == fb.FB_ERR_WORKSPACE
+    assert call(ctypes.byref(s), FAKE, FAKE, FAKE, ODD, ODD, FAKE, FAKE, FAKE, ws_bytes, None) == fb.FB_ERR_ALIGN  # mask may be unaligned, o may not
+
+
 def test_internal_merge_error_paths():
     lib = fb.load_library()
     s = _ok_shape()

@@ -145,3 +145,71 @@ def test_bf16_bitwise_reproducible():
     for x, y in zip(a, b):
         assert np.array_equal(x["out"], y["out"]) and np.array_equal(x["ext"]["o"], y["ext"]["o"])
         assert np.array_equal(x["lse"], y["lse"])
+
+
+# ------------------------------------------------------------------ head-wise selective refresh
+@pytest.mark.parametrize("dtype,B,Hq,Hkv,d,P,Bq,mask", [
+    ("bf16", 1, 6, 6, 128, 700, 48, [1, 0, 0, 1, 1, 0]),                 # MHA (video-like): 3 of 6 heads refreshed
+    ("bf16", 1, 8, 2, 128, 2000, 32, [0, 0, 0, 0, 1, 0, 0, 1]),          # GQA: one KV group entirely off
+    ("bf16", 2, 4, 2, 128, 5000, 32, [1, 0, 0, 0, 0, 0, 1, 1]),          # batch 2, split-KV with wavefront groups
+    ("bf16", 1, 4, 4, 64, 300, 16, [0, 0, 0, 0]),                        # nothing refreshed: cache untouched
+    ("f32", 1, 4, 2, 64, 300, 6, [0, 1, 1, 0]),
+])
+def test_head_wise_selective_refresh(dtype, B, Hq, Hkv, d, P, Bq, mask):
+    """fb_external_partial_heads: flagged heads get the fresh partial of the new query, the others
+    keep the cached one bit for bit; the merged step output follows."""
+    w = _wl(dtype, B, Hq, Hkv, d, P, Bq, S=2, R=2)
+    print(f"[case] heads {w.name} mask={mask}", flush=True)
+    Kp, Vp = wl.make_prefix(w, 61)
+    (Q0, _, _), (Q1, Kb1, Vb1) = wl.make_block_steps(w, 61)
+    shape = T.shape_of(w)
+    ws = T.workspace(shape)
+    kp, vp = T.to_dev(Kp, dtype), T.to_dev(Vp, dtype)
+    part = T.Partial(w)
+    fb.fb_external_partial(shape, T.to_dev(Q0, dtype), kp, vp, part.o, part.m, part.lse, ws)
+    torch.cuda.synchronize()
+    before = {k: v.clone() for k, v in (("o", part.o), ("m", part.m), ("lse", part.lse))}
+    hm = torch.tensor(mask, dtype=torch.uint8, device=T.DEV).reshape(B, Hq)
+    q1 = T.to_dev(Q1, dtype)
+    fb.fb_external_partial_heads(shape, q1, kp, vp, hm, part.o, part.m, part.lse, ws)
+    out = torch.empty_like(q1)
+    fb.fb_internal_merge(shape, q1, T.to_dev(Kb1, dtype), T.to_dev(Vb1, dtype), part.o, part.m, part.lse, out, None)
+    torch.cuda.synchronize()
+    fresh, stale = orc.partial(Q1, Kp, Vp), orc.partial(Q0, Kp, Vp)
+    got = part.numpy()
+    inn = orc.partial(Q1, Kb1, Vb1)
+    want_fresh, _ = orc.merge(fresh, inn)
+    want_stale, _ = orc.merge(stale, inn)
+    on = np.array(mask, dtype=bool).reshape(B, Hq)
+    for b in range(B):
+        for h in range(Hq):
+            sl = (slice(b, b + 1), slice(h, h + 1))
+            if on[b, h]:
+                T.check_partial({k: v[sl] for k, v in got.items()}, {k: v[sl] for k, v in fresh.items()}, dtype,
+                                f"refreshed head {b},{h}")
+                T.assert_close(out[sl].double().cpu().numpy(), want_fresh[sl], dtype, f"out refreshed head {b},{h}")
+            else:
+                assert torch.equal(part.o[sl], before["o"][sl]) and torch.equal(part.lse[sl], before["lse"][sl]) \
+                    and torch.equal(part.m[sl], before["m"][sl]), f"cached head {b},{h} was modified"
+                T.assert_close(out[sl].double().cpu().numpy(), want_stale[sl], dtype, f"out cached head {b},{h}")
+
+
+def test_head_similarity_matches_oracle():
+    """fb_head_similarity on the cached vs. refreshed external partial of a perturbed query."""
+    w = _wl("bf16", 2, 6, 6, 128, 900, 48, S=2, R=1)
+    Kp, Vp = wl.make_prefix(w, 71)
+    (Q0, _, _), (Q1, _, _) = wl.make_block_steps(w, 71)
+    shape = T.shape_of(w)
+    ws = T.workspace(shape)
+    kp, vp = T.to_dev(Kp, "bf16"), T.to_dev(Vp, "bf16")
+    pa, pb = T.Partial(w), T.Partial(w)
+    fb.fb_external_partial(shape, T.to_dev(Q0, "bf16"), kp, vp, pa.o, pa.m, pa.lse, ws)
+    fb.fb_external_partial(shape, T.to_dev(Q1, "bf16"), kp, vp, pb.o, pb.m, pb.lse, ws)
+    sim = torch.empty((2, 6), device=T.DEV)
+    fb.fb_head_similarity(shape, pa.o, pb.o, sim)
+    torch.cuda.synchronize()
+    want = orc.head_similarity(orc.partial(Q0, Kp, Vp), orc.partial(Q1, Kp, Vp))
+    assert np.abs(sim.double().cpu().numpy() - want).max() < 1e-2
+    same = torch.empty((2, 6), device=T.DEV)
+    fb.fb_head_similarity(shape, pa.o, pa.o, same)
+    assert torch.allclose(same, torch.ones_like(same), atol=1e-5)

@@ -396,3 +396,16 @@ def test_workload_generator_shapes_and_determinism():
     wb = wl.CONFIGS["llm_32k"].with_(prefix_len=64)
     Kb, _ = wl.make_prefix(wb, 3)
     assert np.array_equal(Kb, wl.round_bf16(Kb)) and abs(Kb.std() - 1 / math.sqrt(128)) < 0.01
+
+
+def test_head_similarity_hand_cases():
+    """Cosine similarity of A_out rows: identical partials -> 1, orthogonal outputs -> 0, and the
+    value must not depend on the row normalisers (A = o * positive scalar)."""
+    o = np.zeros((1, 2, 2, 4)); o[0, 0, :, 0] = 1.0; o[0, 1, 0, 0] = 3.0; o[0, 1, 1, 1] = 2.0
+    a = {"o": o, "m": np.zeros((1, 2, 2)), "lse": np.log(np.full((1, 2, 2), 5.0))}
+    o2 = np.zeros((1, 2, 2, 4)); o2[0, 0, :, 1] = 7.0; o2[0, 1, 0, 0] = 1.0; o2[0, 1, 1, 1] = 1.0; o2[0, 1, 1, 0] = 1.0
+    b = {"o": o2, "m": np.ones((1, 2, 2)), "lse": np.log(np.full((1, 2, 2), 11.0))}
+    assert np.allclose(orc.head_similarity(a, a), 1.0)
+    s = orc.head_similarity(a, b)
+    assert abs(s[0, 0]) < 1e-15                                  # orthogonal rows
+    assert abs(s[0, 1] - 0.5 * (1.0 + 1.0 / math.sqrt(2.0))) < 1e-12   # rows: parallel, 45 degrees
