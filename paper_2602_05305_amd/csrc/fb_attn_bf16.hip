@@ -624,8 +624,21 @@ hipError_t launch_d(const PassParams& p, PassMode mode, hipStream_t s) {
     case kPassDense: {
       // 8-wave workgroups for split-KV streaming when every wavefront group gets >= 4 tiles; the
       // split heuristic (fb_api) then asks for one such workgroup per CU.
+      // Small blocks (the paper's 4- and 8-token blocks: G*Bq <= 32 or 64 rows per KV group) would
+      // leave three of the four row groups of a workgroup computing padding rows; there the
+      // wavefronts share one or two 32-row groups and split the output columns instead.
       const int tiles = (p.nkeys + kKeyTile - 1) / kKeyTile;
-      if (p.nsplit > 1 && tiles >= 8 * p.nsplit) return launch_one<D, kPassDense, kKeyTile, 1, 2>(p, s);
+      const bool groups2 = p.nsplit > 1 && tiles >= 8 * p.nsplit;
+      const int nrows = p.G * p.Bq;
+      if (nrows <= 32) {
+        if (groups2) return launch_one<D, kPassDense, kKeyTile, WSMAX, 2>(p, s);
+        return launch_one<D, kPassDense, kKeyTile, WSMAX, 1>(p, s);
+      }
+      if (nrows <= 64) {
+        if (groups2) return launch_one<D, kPassDense, kKeyTile, 2, 2>(p, s);
+        return launch_one<D, kPassDense, kKeyTile, 2, 1>(p, s);
+      }
+      if (groups2) return launch_one<D, kPassDense, kKeyTile, 1, 2>(p, s);
       return launch_one<D, kPassDense, kKeyTile, 1, 1>(p, s);
     }
     case kPassInternal: {

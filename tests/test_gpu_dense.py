@@ -213,3 +213,11 @@ def test_head_similarity_matches_oracle():
     same = torch.empty((2, 6), device=T.DEV)
     fb.fb_head_similarity(shape, pa.o, pa.o, same)
     assert torch.allclose(same, torch.ones_like(same), atol=1e-5)
+
+
+@pytest.mark.parametrize("Bq,P,n_splits", [(4, 1617, 3), (4, 300, 0), (8, 2048, 2), (8, 777, 0), (16, 1617, 3), (16, 500, 0)])
+def test_bf16_small_blocks_column_split(Bq, P, n_splits):
+    """The paper's own block sizes (4, 8 tokens): G*Bq <= 64 rows per KV group take the
+    column-split wavefront layout of the dense pass, with and without wavefront groups."""
+    _compare_block(_wl("bf16", 1, 8, 2, 128, P, Bq), seed=29, n_splits=n_splits)
+    _compare_block(_wl("bf16", 2, 4, 2, 64, P, Bq), seed=30, n_splits=n_splits)
