@@ -188,7 +188,7 @@ __device__ __forceinline__ float load_elem(const void* base, size_t i, int is_bf
   return ((const float*)base)[i];
 }
 
-// grid (nblk, B*Hkv), 256 threads: column d = tid % D, token lane = tid / D.
+// grid (nblk, B*Hkv), 256 threads: column d = tid % D, token lane = tid / D (fp32 storage).
 __global__ __launch_bounds__(256) void pool_keys_kernel(const PoolParams p) {
   __shared__ float red[256];
   const int c = blockIdx.x, bh = blockIdx.y;
@@ -205,6 +205,37 @@ __global__ __launch_bounds__(256) void pool_keys_kernel(const PoolParams p) {
   }
 }
 
+// bf16 storage: 16-byte loads (8 columns per thread), D/8 threads per key row, 256/(D/8) rows in
+// flight per step; the row lanes are folded through LDS in a fixed order.
+template <int D>
+__global__ __launch_bounds__(256) void pool_keys_bf16_kernel(const PoolParams p) {
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  typedef const __attribute__((address_space(1))) u32x4* gptr128;
+  constexpr int CPR = D / 8, NRL = 256 / CPR;
+  __shared__ float red[NRL][D + 1];
+  const int c = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x;
+  const int col = tid % CPR, rl = tid / CPR;
+  const int k0 = c * p.key_block, k1 = min(p.nkeys, k0 + p.key_block);
+  const uint16_t* base = (const uint16_t*)p.k + (size_t)bh * p.nkeys * D + col * 8;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int k = k0 + rl; k < k1; k += NRL) {
+    const u32x4 u = *(gptr128)(base + (size_t)k * D);
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      acc[2 * w] += __uint_as_float(u[w] << 16);
+      acc[2 * w + 1] += __uint_as_float(u[w] & 0xffff0000u);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) red[rl][col * 8 + i] = acc[i];
+  __syncthreads();
+  if (tid < D) {
+    float s = 0.f;
+    for (int j = 0; j < NRL; ++j) s += red[j][tid];
+    p.k_pooled[((size_t)bh * p.nblk + c) * D + tid] = s / (float)(k1 - k0);
+  }
+}
+
 // ------------------------------------------------------------------------------ top-k
 // Order-preserving map of a float onto uint32 (larger float <-> larger key).
 __device__ __forceinline__ uint32_t order_key(float x) {
@@ -212,12 +243,18 @@ __device__ __forceinline__ uint32_t order_key(float x) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-// Workgroup-wide sum of a per-thread count (256 threads); every thread gets the total.
-__device__ __forceinline__ int block_sum(int v, int* sh4, int tid) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+// Workgroup-wide count of a predicate over key[0..nblk): per element one wavefront ballot and a
+// scalar popcount (no cross-lane data movement), then the four wavefront counts meet in LDS.
+template <typename Pred>
+__device__ __forceinline__ int block_count(const uint32_t* key, int nblk, int* sh4, int tid, Pred pred) {
+  int cnt = 0;
+  for (int c0 = 0; c0 < nblk; c0 += 256) {
+    const int c = c0 + tid;
+    const bool hit = (c < nblk) && pred(key[c < nblk ? c : 0]);
+    cnt += __popcll(__ballot(hit));
+  }
   __syncthreads();                 // previous readers of sh4 are done
-  if ((tid & 63) == 0) sh4[tid >> 6] = v;
+  if ((tid & 63) == 0) sh4[tid >> 6] = cnt;
   __syncthreads();
   return sh4[0] + sh4[1] + sh4[2] + sh4[3];
 }
@@ -269,13 +306,10 @@ __global__ __launch_bounds__(256) void select_topk_kernel(const SelectParams p) 
   uint32_t T = 0u;
   for (int bit = 31; bit >= 0; --bit) {
     const uint32_t cand = T | (1u << bit);
-    int mine = 0;
-    for (int c = tid; c < nblk; c += 256) mine += key[c] >= cand;
-    if (block_sum(mine, sh4, tid) >= k) T = cand;
+    if (block_count(key, nblk, sh4, tid, [cand](uint32_t kc) { return kc >= cand; }) >= k) T = cand;
   }
-  int gt = 0;
-  for (int c = tid; c < nblk; c += 256) gt += key[c] > T;
-  const int need_eq = k - block_sum(gt, sh4, tid);   // ties with the k-th key to take, lowest index first
+  // ties with the k-th key to take, lowest index first
+  const int need_eq = k - block_count(key, nblk, sh4, tid, [T](uint32_t kc) { return kc > T; });
 
   // ascending passes over contiguous chunks: thread t owns blocks [t*per, (t+1)*per)
   const int per = (nblk + 255) / 256;
@@ -393,7 +427,10 @@ hipError_t launch_combine(const CombineParams& p, hipStream_t s) {
 
 hipError_t launch_pool_keys(const PoolParams& p, hipStream_t s) {
   if (p.nblk == 0 || p.BH == 0) return hipSuccess;
-  hipLaunchKernelGGL(pool_keys_kernel, dim3(p.nblk, p.BH), dim3(256), 0, s, p);
+  const dim3 grid(p.nblk, p.BH), block(256);
+  if (p.is_bf16 && p.D == 128) hipLaunchKernelGGL(pool_keys_bf16_kernel<128>, grid, block, 0, s, p);
+  else if (p.is_bf16 && p.D == 64) hipLaunchKernelGGL(pool_keys_bf16_kernel<64>, grid, block, 0, s, p);
+  else hipLaunchKernelGGL(pool_keys_kernel, grid, block, 0, s, p);
   return hipGetLastError();
 }
 
