@@ -309,6 +309,50 @@ def sparse_extra(torch, fb, wl):
             "refresh_GBps_vs_kv_bytes": round(w.kv_bytes / t_refresh / 1e3, 1)}
 
 
+def sparse_accuracy(torch, fb, wl, prefix_len=32768):
+    """Synthetic analogue of the paper's Table 3: mean L1 distance to full attention on reuse steps
+    of sparse attention alone vs. sparse attention + the cached residual, per attention density.
+    All three outputs come from the HIP path (full attention = dense path refreshed every step)."""
+    rows = []
+    base = wl.CONFIGS["sparse_64k"].with_(prefix_len=prefix_len)
+    nblk = -(-base.prefix_len // base.key_block)
+    for density in (0.10, 0.20, 0.30, 0.40, 0.50):
+        w = base.with_(topk=int(round(density * nblk)))
+        d = DeviceBlock(w, 1, seed=77)
+        ws = torch.empty(fb.fb_workspace_bytes(d.shape, w.key_block, w.topk), device="cuda", dtype=torch.uint8)
+        pooled = torch.empty((w.batch, w.n_kv_heads, nblk, w.head_dim), device="cuda")
+        idx = torch.empty((w.batch, w.n_q_heads, w.topk), device="cuda", dtype=torch.int32)
+        shp = (w.batch, w.n_q_heads, w.block_len)
+        mk = lambda: (torch.empty(shp + (w.head_dim,), device="cuda"), torch.empty(shp, device="cuda"), torch.empty(shp, device="cuda"))
+        res, ext, full = mk(), mk(), mk()
+        empty = (torch.zeros(shp + (w.head_dim,), device="cuda"), torch.full(shp, float("-inf"), device="cuda"),
+                 torch.full(shp, float("-inf"), device="cuda"))
+        fb.fb_pool_keys(d.shape, d.K[0], w.key_block, pooled)
+        out_a, out_b, out_f = torch.empty_like(d.out), torch.empty_like(d.out), torch.empty_like(d.out)
+        l1_res, l1_only = [], []
+        for t, (q, kb, vb) in enumerate(d.steps):
+            if t == 0:
+                fb.fb_select_topk(d.shape, q, pooled, w.key_block, w.topk, idx)
+                fb.fb_sparse_external_residual(d.shape, fb.FB_SPARSE_REFRESH, q, d.K[0], d.V[0], w.key_block, w.topk,
+                                               idx, *res, *ext, ws)
+                continue
+            fb.fb_sparse_external_residual(d.shape, fb.FB_SPARSE_REUSE, q, d.K[0], d.V[0], w.key_block, w.topk, idx,
+                                           *res, *ext, ws)
+            fb.fb_internal_merge(d.shape, q, kb, vb, *ext, out_a, None)
+            fb.fb_sparse_external_residual(d.shape, fb.FB_SPARSE_REUSE, q, d.K[0], d.V[0], w.key_block, w.topk, idx,
+                                           *empty, *ext, ws)
+            fb.fb_internal_merge(d.shape, q, kb, vb, *ext, out_b, None)
+            fb.fb_external_partial(d.shape, q, d.K[0], d.V[0], *full, ws)
+            fb.fb_internal_merge(d.shape, q, kb, vb, *full, out_f, None)
+            l1_res.append((out_a.float() - out_f.float()).abs().mean().item())
+            l1_only.append((out_b.float() - out_f.float()).abs().mean().item())
+        rows.append({"density": density, "l1_sparse_only": sum(l1_only) / len(l1_only),
+                     "l1_sparse_plus_cached_residual": sum(l1_res) / len(l1_res)})
+        del d
+        torch.cuda.empty_cache()
+    return {"workload": describe(base) + ", densities swept", "mean_abs_output": None, "rows": rows}
+
+
 def describe(w):
     return (f"{w.name}: batch {w.batch}, {w.n_q_heads} q heads / {w.n_kv_heads} kv heads, head_dim {w.head_dim}, "
             f"prefix {w.prefix_len}, block {w.block_len}, {w.steps} steps/block, refresh every {w.refresh}, {w.dtype}")
@@ -326,6 +370,8 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="skip the video-shaped (MFMA) and sparse measurements")
     ap.add_argument("--profile-external", type=int, default=0, metavar="N",
                     help="only run N whole blocks of the workload, eagerly (for rocprofv3), print nothing else")
+    ap.add_argument("--sparse-accuracy", action="store_true",
+                    help="only print the sparse-vs-full L1 table (synthetic analogue of the paper's Table 3)")
     ap.add_argument("--profile-sparse", type=int, default=0, metavar="N",
                     help="only run N sparse refresh + reuse call pairs of the sparse_64k workload (for rocprofv3)")
     ap.add_argument("--profile-copy", type=int, default=0, metavar="N",
@@ -352,6 +398,9 @@ def main():
             y.copy_(x)
         torch.cuda.synchronize()
         print(f"ran {args.profile_copy} device copies of {x.numel()} bytes (read {x.numel()} + write {x.numel()} per copy)")
+        return
+    if args.sparse_accuracy:
+        print(json.dumps(sparse_accuracy(torch, fb, wl)))
         return
     if args.profile_sparse > 0:
         ws_ = wl.CONFIGS["sparse_64k"]
