@@ -151,6 +151,49 @@ fb_status fb_external_partial_heads(const fb_shape* shape, const void* q, const 
                                     size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Paged prefix cache with per-sequence prefix lengths: the deployment shape of the language-model
+ * experiments (Section 5, implementation details: a serving framework with a paged KV cache,
+ * batches of up to 128 sequences under one token budget; the limitations section asks for kernels
+ * compatible with such a cache).  Same operation as fb_external_partial (Eq. 3-4 / Eq. 6 over the
+ * block-external keys), but sequence b attends to its own prefix_lens[b] keys, which live in
+ * fixed-size pages of a shared pool.
+ *
+ *   k_pool, v_pool  device, element type shape->dtype, layout [num_pages, n_kv_heads, page_size, head_dim]
+ *                   (one KV head's keys of a page are contiguous: a 64-key tile is one 8/16/32 KB run)
+ *   block_table     device, int32 [batch, max_pages]: block_table[b][j] = pool page holding keys
+ *                   [j*page_size, (j+1)*page_size) of sequence b.  Only entries j < ceil(prefix_lens[b]
+ *                   / page_size) are read; each is clamped to [0, num_pages) inside the kernel, so a bad
+ *                   id gives a wrong result, never an out-of-pool access.
+ *   prefix_lens     device, int32 [batch]; clamped to [0, shape->prefix_len] inside the kernel.
+ *                   A sequence with 0 keys gets the empty partial (o = 0, m = lse = -inf).
+ *   page_size       multiple of 64 (FB_ERR_UNSUPPORTED otherwise); max_pages * page_size >= shape->prefix_len.
+ * shape->prefix_len is the maximum prefix length over the batch: it sizes the work split and the
+ * workspace.  n_splits: 0 = library heuristic (fb_paged_splits), else as in fb_external_partial_ex;
+ * every sequence's own tile list is cut into that many ranges.  Workspace:
+ * fb_workspace_bytes(shape, 0, 0, n_splits > 0 ? n_splits : fb_paged_splits(shape)).  All pointers are borrowed for the
+ * duration of the enqueued work; nothing is written except o_part / m_part / lse_part / workspace.
+ */
+typedef struct fb_paged_kv {
+  uint32_t struct_size;        /* sizeof(fb_paged_kv), checked */
+  int32_t num_pages;
+  int32_t page_size;
+  int32_t max_pages;           /* row length of block_table */
+  const void* k_pool;
+  const void* v_pool;
+  const int32_t* block_table;
+  const int32_t* prefix_lens;
+} fb_paged_kv;
+
+/* Split count fb_external_partial_paged uses for n_splits = 0: ragged lengths make workgroups of
+ * unequal length, so it asks for several workgroups per compute unit and lets the hardware
+ * dispatcher balance them.  0 if the shape is invalid. */
+int32_t fb_paged_splits(const fb_shape* shape);
+
+fb_status fb_external_partial_paged(const fb_shape* shape, const void* q, const fb_paged_kv* kv,
+                                    float* o_part, float* m_part, float* lse_part, int32_t n_splits,
+                                    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Cross-step similarity of block-external attention per head (Section 3 / Figure 1, used to
  * calibrate the head-wise reuse threshold of Section 4.2): sim[b,h] = mean over the block's rows
  * of the cosine similarity between the external attention outputs A_out of two partials, e.g.

@@ -92,10 +92,26 @@ int sparse_splits(const fb_shape* s, bool refresh) {
   return (int)ns;
 }
 
+// Paged pass: sequences differ in length, so equal split counts give unequal workgroups.  Aim at
+// ~4 workgroups per CU (the dispatcher evens them out), each with at least 8 tiles on the longest sequence.
+int paged_splits(const fb_shape* s) {
+  if (s->dtype != FB_BF16) return auto_splits(s);
+  const int tiles = (s->prefix_len + fb::kKeyTile - 1) / fb::kKeyTile;
+  const int G = s->n_q_heads / s->n_kv_heads;
+  const long long groups =
+      (long long)s->batch * s->n_kv_heads * ((G * s->block_len + fb::kRowsPerWgBf16 - 1) / fb::kRowsPerWgBf16);
+  long long ns = (1024 + groups - 1) / groups;
+  const long long cap = tiles / 8;
+  if (ns > cap) ns = cap;
+  if (ns > FB_MAX_SPLITS) ns = FB_MAX_SPLITS;
+  if (ns < 1) ns = 1;
+  return (int)ns;
+}
+
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct WsLayout {
-  size_t o[2], m[2], l[2], mask, ulist, ucnt, total;
+  size_t o[2], m[2], l[2], mask, ulist, ucnt, order, total;
 };
 
 WsLayout ws_layout(const fb_shape* s, int nsplit, int nsets, int nblk) {
@@ -112,6 +128,7 @@ WsLayout ws_layout(const fb_shape* s, int nsplit, int nsets, int nblk) {
   w.mask = off;  off = align256(off + nb * sizeof(uint32_t));
   w.ulist = off; off = align256(off + nb * sizeof(int32_t));
   w.ucnt = off;  off = align256(off + (nblk > 0 ? (size_t)s->batch * s->n_kv_heads * sizeof(int32_t) : 0));
+  w.order = off; off = align256(off + (size_t)s->batch * sizeof(int32_t));   // paged pass: sequences by length
   w.total = off;
   return w;
 }
@@ -170,6 +187,11 @@ int32_t fb_external_splits(const fb_shape* shape) {
   return auto_splits(shape);
 }
 
+int32_t fb_paged_splits(const fb_shape* shape) {
+  if (check_shape(shape) != FB_OK) return 0;
+  return paged_splits(shape);
+}
+
 size_t fb_workspace_bytes(const fb_shape* shape, int32_t key_block, int32_t topk, int32_t n_splits) {
   if (check_shape(shape) != FB_OK) return 0;
   if (n_splits < 0 || n_splits > FB_MAX_SPLITS) return 0;
@@ -189,20 +211,29 @@ size_t fb_workspace_bytes(const fb_shape* shape, int32_t key_block, int32_t topk
 namespace {
 
 fb_status external_partial_impl(const fb_shape* shape, const void* q, const void* k_prefix,
-                                const void* v_prefix, const uint8_t* head_mask, bool use_head_mask,
-                                float* o_part, float* m_part, float* lse_part,
+                                const void* v_prefix, const fb_paged_kv* paged, const uint8_t* head_mask,
+                                bool use_head_mask, float* o_part, float* m_part, float* lse_part,
                                 int32_t n_splits, void* workspace, size_t workspace_bytes,
                                 void* ev_begin, void* ev_attn_end, void* ev_end, void* hip_stream) {
   fb_status st = check_shape(shape);
   if (st != FB_OK) return st;
   if (!q || !o_part || !m_part || !lse_part) return FB_ERR_NULL;
   if (use_head_mask && !head_mask) return FB_ERR_NULL;
+  if (paged) {
+    if (paged->struct_size != sizeof(fb_paged_kv)) return FB_ERR_SHAPE;
+    if (!paged->block_table || !paged->prefix_lens) return FB_ERR_NULL;
+    if (paged->num_pages <= 0 || paged->page_size <= 0 || paged->max_pages <= 0) return FB_ERR_SHAPE;
+    if (paged->page_size % fb::kKeyTile != 0) return FB_ERR_UNSUPPORTED;
+    if ((long long)paged->max_pages * paged->page_size < shape->prefix_len) return FB_ERR_SHAPE;
+    k_prefix = paged->k_pool;
+    v_prefix = paged->v_pool;
+  }
   if (shape->prefix_len > 0 && (!k_prefix || !v_prefix)) return FB_ERR_NULL;
   if (n_splits < 0 || n_splits > FB_MAX_SPLITS) return FB_ERR_SHAPE;
   if (!aligned16(q) || !aligned16(k_prefix) || !aligned16(v_prefix) || !aligned16(o_part) ||
       !aligned16(m_part) || !aligned16(lse_part) || !aligned16(workspace))
     return FB_ERR_ALIGN;
-  const int ns = n_splits > 0 ? n_splits : auto_splits(shape);
+  const int ns = n_splits > 0 ? n_splits : (paged ? paged_splits(shape) : auto_splits(shape));
   const WsLayout w = ws_layout(shape, ns, 1, 0);
   if (!workspace || workspace_bytes < w.total) return FB_ERR_WORKSPACE;
 
@@ -211,20 +242,37 @@ fb_status external_partial_impl(const fb_shape* shape, const void* q, const void
   fb::PassParams p = base_pass(shape, q, k_prefix, v_prefix, shape->prefix_len, ns);
   p.ws_o = (float*)(ws + w.o[0]); p.ws_m = (float*)(ws + w.m[0]); p.ws_l = (float*)(ws + w.l[0]);
   p.head_on = use_head_mask ? head_mask : nullptr;
+  fb::PassMode mode = use_head_mask ? fb::kPassDenseHeads : fb::kPassDense;
+  if (paged) {
+    mode = fb::kPassDensePaged;
+    p.block_table = paged->block_table; p.prefix_lens = paged->prefix_lens;
+    p.page_size = paged->page_size; p.max_pages = paged->max_pages; p.num_pages = paged->num_pages;
+    if (shape->batch > 1) {
+      p.seq_order = (int32_t*)(ws + w.order);
+      hipError_t eo = fb::launch_seq_order(paged->prefix_lens, (int32_t*)(ws + w.order), shape->batch, stream);
+      if (eo != hipSuccess) return hip_fail(eo);
+    }
+  }
+  if (ns == 1) {   // the attention kernel writes the final partial itself
+    p.direct = 1;
+    p.ws_o = o_part; p.ws_m = m_part; p.ws_l = lse_part;
+  }
   hipError_t e = hipSuccess;
   if (ev_begin && (e = hipEventRecord((hipEvent_t)ev_begin, stream)) != hipSuccess) return hip_fail(e);
-  e = launch_attn(shape, p, use_head_mask ? fb::kPassDenseHeads : fb::kPassDense, stream);
+  e = launch_attn(shape, p, mode, stream);
   if (e != hipSuccess) return hip_fail(e);
   if (ev_attn_end && (e = hipEventRecord((hipEvent_t)ev_attn_end, stream)) != hipSuccess) return hip_fail(e);
 
-  fb::CombineParams c;
-  memset(&c, 0, sizeof(c));
-  c.rows = (int)rows_of(shape); c.D = shape->head_dim; c.nsplit = ns;
-  c.ws_o = p.ws_o; c.ws_m = p.ws_m; c.ws_l = p.ws_l;
-  c.o = o_part; c.m = m_part; c.lse = lse_part;
-  c.head_on = p.head_on; c.Bq = shape->block_len;
-  e = fb::launch_combine(c, stream);
-  if (e != hipSuccess) return hip_fail(e);
+  if (!p.direct) {
+    fb::CombineParams c;
+    memset(&c, 0, sizeof(c));
+    c.rows = (int)rows_of(shape); c.D = shape->head_dim; c.nsplit = ns;
+    c.ws_o = p.ws_o; c.ws_m = p.ws_m; c.ws_l = p.ws_l;
+    c.o = o_part; c.m = m_part; c.lse = lse_part;
+    c.head_on = p.head_on; c.Bq = shape->block_len;
+    e = fb::launch_combine(c, stream);
+    if (e != hipSuccess) return hip_fail(e);
+  }
   if (ev_end && (e = hipEventRecord((hipEvent_t)ev_end, stream)) != hipSuccess) return hip_fail(e);
   return FB_OK;
 }
@@ -237,7 +285,7 @@ fb_status fb_external_partial_prof(const fb_shape* shape, const void* q, const v
                                    const void* v_prefix, float* o_part, float* m_part, float* lse_part,
                                    int32_t n_splits, void* workspace, size_t workspace_bytes,
                                    void* ev_begin, void* ev_attn_end, void* ev_end, void* hip_stream) {
-  return external_partial_impl(shape, q, k_prefix, v_prefix, nullptr, false, o_part, m_part, lse_part, n_splits,
+  return external_partial_impl(shape, q, k_prefix, v_prefix, nullptr, nullptr, false, o_part, m_part, lse_part, n_splits,
                                workspace, workspace_bytes, ev_begin, ev_attn_end, ev_end, hip_stream);
 }
 
@@ -245,7 +293,15 @@ fb_status fb_external_partial_heads(const fb_shape* shape, const void* q, const 
                                     const void* v_prefix, const uint8_t* head_mask, float* o_part,
                                     float* m_part, float* lse_part, void* workspace, size_t workspace_bytes,
                                     void* hip_stream) {
-  return external_partial_impl(shape, q, k_prefix, v_prefix, head_mask, true, o_part, m_part, lse_part, 0,
+  return external_partial_impl(shape, q, k_prefix, v_prefix, nullptr, head_mask, true, o_part, m_part, lse_part, 0,
+                               workspace, workspace_bytes, nullptr, nullptr, nullptr, hip_stream);
+}
+
+fb_status fb_external_partial_paged(const fb_shape* shape, const void* q, const fb_paged_kv* kv, float* o_part,
+                                    float* m_part, float* lse_part, int32_t n_splits, void* workspace,
+                                    size_t workspace_bytes, void* hip_stream) {
+  if (!kv) return FB_ERR_NULL;
+  return external_partial_impl(shape, q, nullptr, nullptr, kv, nullptr, false, o_part, m_part, lse_part, n_splits,
                                workspace, workspace_bytes, nullptr, nullptr, nullptr, hip_stream);
 }
 

@@ -294,9 +294,14 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
   // instead of the one that two sets in a single wavefront allow.
   constexpr bool kSetSplit = (MODE == kPassSparseRefresh && NG == 2);
   constexpr int TG = kSetSplit ? 1 : NG;          // wavefront groups that own separate tile streams
-  static_assert(NG == 1 || MODE == kPassDense || MODE == kPassDenseHeads || MODE == kPassSparseReuse || kSetSplit, "unsupported group mode");
+  static_assert(NG == 1 || MODE == kPassDense || MODE == kPassDenseHeads || MODE == kPassDensePaged || MODE == kPassSparseReuse || kSetSplit,
+                "unsupported group mode");
 
-  const int grp = (NG > 1) ? (int)(threadIdx.x >> 8) : 0;
+  // wavefront-uniform by construction; in the paged pass, telling the compiler so keeps the block-table
+  // lookups and page address arithmetic in scalar registers
+  const int grp = (NG > 1) ? ((MODE == kPassDensePaged) ? __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 8))
+                                                        : (int)(threadIdx.x >> 8))
+                           : 0;
   const int tid = threadIdx.x & 255, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, h = lane >> 5;
   unsigned char* smem = smem_all + (kSetSplit ? 0 : grp) * 2 * C::STAGE;
@@ -304,25 +309,39 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
   // XCD-aware remap: hardware deals consecutive workgroup ids round-robin to the 8 XCDs; make
   // each XCD own a contiguous range of work items (row tiles of one KV head are adjacent).
   const int nwg = gridDim.x;
-  int w;
-  {
+  const int nrows = p.G * p.Bq;
+  uint32_t rest;
+  int rt;
+  if constexpr (MODE == kPassDensePaged) {
+    // Ragged sequences: contiguous ranges per XCD would give the XCDs unequal work.  Deal the
+    // (sequence, KV head, split) units round-robin instead; the row tiles of one unit, which share
+    // its K/V, stay on one XCD.  The grid is rounded up to a multiple of 8 units.
+    const uint32_t j = blockIdx.x >> 3, xcd = blockIdx.x & 7;
+    const uint32_t jq = fastdiv(j, p.div_rowtiles);
+    rt = (int)(j - jq * p.div_rowtiles.d);
+    rest = jq * 8 + xcd;
+    if (rest >= (uint32_t)(p.B * p.Hkv * p.nsplit)) return;   // workgroup-uniform
+  } else {
     const int bid = blockIdx.x, q8 = nwg / 8, r8 = nwg % 8;
     const int xcd = bid % 8, j = bid / 8;
-    w = (xcd < r8 ? xcd * (q8 + 1) : r8 * (q8 + 1) + (xcd - r8) * q8) + j;
+    const int w = (xcd < r8 ? xcd * (q8 + 1) : r8 * (q8 + 1) + (xcd - r8) * q8) + j;
+    rest = fastdiv((uint32_t)w, p.div_rowtiles);
+    rt = w - (int)(rest * p.div_rowtiles.d);
   }
-  const int nrows = p.G * p.Bq;
-  uint32_t rest = fastdiv((uint32_t)w, p.div_rowtiles);
-  const int rt = w - (int)(rest * p.div_rowtiles.d);
   int split = 0;
   if constexpr (MODE != kPassInternal) {
     const uint32_t r2 = fastdiv(rest, p.div_nsplit);
     split = (int)(rest - r2 * p.div_nsplit.d);
     rest = r2;
   }
-  const int b = (int)fastdiv(rest, p.div_hkv);
+  int b = (int)fastdiv(rest, p.div_hkv);
   const int kvh = (int)(rest - (uint32_t)b * p.div_hkv.d);
+  if constexpr (MODE == kPassDensePaged) {
+    if (p.seq_order != nullptr) b = p.seq_order[b];
+  }
   const int bk = b * p.Hkv + kvh;
-  const int nkeys = p.nkeys;
+  int nkeys = p.nkeys;
+  if constexpr (MODE == kPassDensePaged) nkeys = min(p.nkeys, max(0, p.prefix_lens[b]));   // this sequence's prefix
 
   // WS wavefronts share one 32-row group and split the output columns between them (each repeats
   // the cheap score / softmax work): used when the pass has too few rows to fill the GPU, where
@@ -343,8 +362,9 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
   }
 
   const __bf16* __restrict__ Q = (const __bf16*)p.q;
-  const __bf16* __restrict__ K = (const __bf16*)p.k + (size_t)bk * nkeys * D;
-  const __bf16* __restrict__ V = (const __bf16*)p.v + (size_t)bk * nkeys * D;
+  // contiguous cache: this KV head's [nkeys, D] slab; paged cache: the pool (tiles add their page offset)
+  const __bf16* __restrict__ K = (const __bf16*)p.k + ((MODE == kPassDensePaged) ? (size_t)0 : (size_t)bk * nkeys * D);
+  const __bf16* __restrict__ V = (const __bf16*)p.v + ((MODE == kPassDensePaged) ? (size_t)0 : (size_t)bk * nkeys * D);
 
   // tile list of this workgroup
   int tpb = 1, total;
@@ -366,6 +386,11 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
       return blk * p.key_block + KT * (e % tpb);
     } else if constexpr (MODE == kPassSparseRefresh) {
       mask = bmask[(e * KT) / p.key_block];
+      return e * KT;
+    } else if constexpr (MODE == kPassDensePaged) {
+      // descriptor word = page id, clamped into the pool
+      const uint32_t slot = fastdiv((uint32_t)(e * KT), p.div_page);
+      mask = (uint32_t)min(max(p.block_table[(size_t)b * p.max_pages + slot], 0), p.num_pages - 1);
       return e * KT;
     } else {
       mask = 0xffffffffu;
@@ -392,11 +417,22 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
   // sparse reuse pass they come from dependent scalar loads, whose latency would otherwise sit
   // in front of every tile's global loads.
   const int mine = common + (extra ? 1 : 0);
+  auto load_tile = [&](int k0, uint32_t aux) {
+    if constexpr (MODE == kPassDensePaged) {
+      // page `aux` holds keys [j * page_size, (j+1) * page_size) of this sequence; rebase so that key
+      // index k0 + r addresses row (k0 % page_size) + r of this KV head's slab of the page
+      const int in_page = k0 - (int)(fastdiv((uint32_t)k0, p.div_page) * p.div_page.d);
+      const long long off = (((long long)aux * p.Hkv + kvh) * p.page_size + in_page - k0) * D;
+      tile_load<D, KT, kSetSplit>(regs, K + off, V + off, k0, nkeys, tid, grp);
+    } else {
+      tile_load<D, KT, kSetSplit>(regs, K, V, k0, nkeys, tid, grp);
+    }
+  };
   uint32_t mask_cur = 0, mask_next = 0, mask_nn = 0;
   int k0_cur = 0, k0_next = 0, k0_nn = 0;
   if (mine > 0) {
     k0_cur = entry_k0(tile_entry(0), mask_cur);
-    tile_load<D, KT, kSetSplit>(regs, K, V, k0_cur, nkeys, tid, grp);
+    load_tile(k0_cur, mask_cur);
     if (mine > 1) k0_next = entry_k0(tile_entry(1), mask_next);
   }
 
@@ -472,7 +508,7 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
     __syncthreads();
     for (int i = 0; i < common - 1; ++i) {       // steady state: one barrier per tile
       if (i + 2 < mine) k0_nn = entry_k0(tile_entry(i + 2), mask_nn);
-      tile_load<D, KT, kSetSplit>(regs, K, V, k0_next, nkeys, tid, grp);
+      load_tile(k0_next, mask_next);
       compute(smem + (i & 1) * C::STAGE, k0_cur, mask_cur);
       tile_store<D, KT, kSetSplit>(regs, smem + ((i + 1) & 1) * C::STAGE, tid, grp);
       __syncthreads();
@@ -483,7 +519,7 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
     }
     if (common > 0) {
       const int i = common - 1;
-      if (extra) tile_load<D, KT, kSetSplit>(regs, K, V, k0_next, nkeys, tid, grp);
+      if (extra) load_tile(k0_next, mask_next);
       compute(smem + (i & 1) * C::STAGE, k0_cur, mask_cur);
       if (TG > 1 && (ntiles % TG) != 0) {         // some group has one more tile (workgroup-uniform)
         if (extra) tile_store<D, KT, kSetSplit>(regs, smem + ((i + 1) & 1) * C::STAGE, tid, grp);
@@ -553,6 +589,34 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
       }
     if (p.lse_out != nullptr && h == 0 && db_base == 0) p.lse_out[grow] = den > 0.f ? (M2 + log2f(den)) * kLn2 : -INFINITY;
   } else {
+    if constexpr (MODE == kPassDense || MODE == kPassDenseHeads || MODE == kPassDensePaged) {
+      if (p.direct) {
+        // single split: this is the final partial.  Same conversion as the split combine: m is
+        // rounded when converted to natural-log units, o is rescaled to the reference consumers
+        // recover from it.
+        if (!(row_ok && head_active)) return;
+        float m_nat = -INFINITY, L = -INFINITY, adj = 0.f;
+        if (l_sel > 0.f) {
+          m_nat = sel.m * kLn2;
+          adj = exp2f(sel.m - m_nat * kLog2e);
+          L = (sel.m + log2f(l_sel)) * kLn2;
+        }
+#pragma unroll
+        for (int db = 0; db < NDBL; ++db)
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4) {
+            const int d0 = 32 * (db_base + db) + 8 * q4 + 4 * h;
+            f32x4 o4 = {sel.o[db][4 * q4] * adj, sel.o[db][4 * q4 + 1] * adj, sel.o[db][4 * q4 + 2] * adj,
+                        sel.o[db][4 * q4 + 3] * adj};
+            *(f32x4*)(p.ws_o + grow * D + d0) = o4;
+          }
+        if (h == 0 && db_base == 0) {
+          p.ws_m[grow] = m_nat;
+          p.ws_l[grow] = L;
+        }
+        return;
+      }
+    }
     const size_t rows_total = (size_t)p.B * p.Hq * p.Bq;
     const size_t wrow = (size_t)split * rows_total + grow;
     float* __restrict__ w_o = (kSetSplit && grp == 1) ? p.ws_o2 : p.ws_o;
@@ -607,9 +671,11 @@ hipError_t launch_one(const PassParams& p, hipStream_t s) {
   constexpr int rows_per_wg = kRowsPerWgBf16 / WS;
   const int nrows = p.G * p.Bq;
   const int ntile_rows = (nrows + rows_per_wg - 1) / rows_per_wg;
-  const long long nwg = (long long)p.B * p.Hkv * ntile_rows * p.nsplit;
+  long long nwg = (long long)p.B * p.Hkv * ntile_rows * p.nsplit;
+  if (MODE == kPassDensePaged) nwg = (((long long)p.B * p.Hkv * p.nsplit + 7) / 8) * 8 * ntile_rows;
   if (nwg >= (1ll << 31)) return hipErrorInvalidValue;
   PassParams q = p;
+  if (MODE == kPassDensePaged) q.div_page = make_fastdiv((uint32_t)p.page_size);
   q.div_rowtiles = make_fastdiv((uint32_t)ntile_rows);
   q.div_nsplit = make_fastdiv((uint32_t)p.nsplit);
   q.div_hkv = make_fastdiv((uint32_t)p.Hkv);
@@ -659,6 +725,11 @@ hipError_t launch_d(const PassParams& p, PassMode mode, hipStream_t s) {
       const int tiles = (p.nkeys + kKeyTile - 1) / kKeyTile;
       if (p.nsplit > 1 && tiles >= 8 * p.nsplit) return launch_one<D, kPassDenseHeads, kKeyTile, 1, 2>(p, s);
       return launch_one<D, kPassDenseHeads, kKeyTile, 1, 1>(p, s);
+    }
+    case kPassDensePaged: {
+      const int tiles = (p.nkeys + kKeyTile - 1) / kKeyTile;
+      if (p.nsplit > 1 && tiles >= 8 * p.nsplit) return launch_one<D, kPassDensePaged, kKeyTile, 1, 2>(p, s);
+      return launch_one<D, kPassDensePaged, kKeyTile, 1, 1>(p, s);
     }
     case kPassSparseReuse:
       if (p.nsplit > 1) return launch_one<D, kPassSparseReuse, kKeyTile, 1, 2>(p, s);

@@ -71,7 +71,11 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const PassParams p) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int chunk = blockIdx.x;
   const int bh = blockIdx.y;
-  const int b = bh / p.Hq, h = bh % p.Hq;
+  int b = bh / p.Hq;
+  const int h = bh % p.Hq;
+  if constexpr (MODE == kPassDensePaged) {
+    if (p.seq_order != nullptr) b = p.seq_order[b];
+  }
   const int kvh = h / p.G, g = h % p.G;
   const int split = blockIdx.z;
   const int row = chunk * 4 + wave;
@@ -79,12 +83,14 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const PassParams p) {
   if constexpr (MODE == kPassDenseHeads) {
     if (p.head_on[bh] == 0) return;     // workgroup-uniform: this head keeps its cached partial
   }
-  const int nkeys = p.nkeys;
+  int nkeys = p.nkeys;
+  if constexpr (MODE == kPassDensePaged) nkeys = min(p.nkeys, max(0, p.prefix_lens[b]));   // this sequence's prefix
   const int bk = b * p.Hkv + kvh;
 
   const float* __restrict__ Q = (const float*)p.q + (size_t)(b * p.Hq + h) * p.Bq * D;
-  const float* __restrict__ K = (const float*)p.k + (size_t)bk * nkeys * D;
-  const float* __restrict__ V = (const float*)p.v + (size_t)bk * nkeys * D;
+  // contiguous cache: this KV head's [nkeys, D] slab; paged cache: the pool (tiles add their page offset)
+  const float* __restrict__ K = (const float*)p.k + ((MODE == kPassDensePaged) ? (size_t)0 : (size_t)bk * nkeys * D);
+  const float* __restrict__ V = (const float*)p.v + ((MODE == kPassDensePaged) ? (size_t)0 : (size_t)bk * nkeys * D);
 
   for (int i = tid; i < 4 * D; i += 256) {
     const int r = chunk * 4 + i / D;
@@ -118,12 +124,21 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const PassParams p) {
       if constexpr (MODE == kPassSparseRefresh)
         is_sel = (p.blk_mask[(size_t)bk * p.nblk + k0 / p.key_block] >> g) & 1u;
     }
+    const float* Kt = K;
+    const float* Vt = V;
+    if constexpr (MODE == kPassDensePaged) {
+      // rebase so that key index k0 + r addresses row (k0 % page_size) + r of this head's slab of the page
+      const long long page = min(max(p.block_table[(size_t)b * p.max_pages + k0 / p.page_size], 0), p.num_pages - 1);
+      const long long off = ((page * p.Hkv + kvh) * p.page_size + (k0 % p.page_size) - k0) * D;
+      Kt = K + off;
+      Vt = V + off;
+    }
     __syncthreads();   // all wavefronts are done with the previous K tile (and Qs is written)
     for (int c = tid; c < kKeyTile * (D / 4); c += 256) {
       const int r = c / (D / 4), c4 = c % (D / 4);
       const int key = k0 + r;
       float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (key < nkeys) val = *(const float4*)(K + (size_t)key * D + c4 * 4);
+      if (key < nkeys) val = *(const float4*)(Kt + (size_t)key * D + c4 * 4);
       *(float4*)(Ks + r * KSTR + c4 * 4) = val;
     }
     __syncthreads();
@@ -143,9 +158,9 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const PassParams p) {
       if (k0 + lane >= nkeys) s = -INFINITY;
       const int nvalid = min(kKeyTile, nkeys - k0);
       if (MODE == kPassSparseRefresh && !is_sel)
-        row_update<D, NACC>(res, s, V, k0, nvalid, lane);
+        row_update<D, NACC>(res, s, Vt, k0, nvalid, lane);
       else
-        row_update<D, NACC>(sel, s, V, k0, nvalid, lane);
+        row_update<D, NACC>(sel, s, Vt, k0, nvalid, lane);
     }
   }
 
@@ -177,6 +192,25 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const PassParams p) {
     if (p.lse_out != nullptr && lane == 0)
       p.lse_out[grow] = den > 0.f ? (M2 + log2f(den)) * kLn2 : -INFINITY;
   } else {
+    if constexpr (MODE == kPassDense || MODE == kPassDenseHeads || MODE == kPassDensePaged) {
+      if (p.direct) {
+        // single split: this is the final partial; same unit conversion as the split combine
+        constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
+        float m_nat = -INFINITY, L = -INFINITY, adj = 0.f;
+        if (sel.l > 0.f) {
+          m_nat = sel.m * kLn2;
+          adj = exp2f(sel.m - m_nat * kLog2e);
+          L = (sel.m + log2f(sel.l)) * kLn2;
+        }
+#pragma unroll
+        for (int i = 0; i < NACC; ++i) p.ws_o[grow * D + lane + 64 * i] = sel.acc[i] * adj;
+        if (lane == 0) {
+          p.ws_m[grow] = m_nat;
+          p.ws_l[grow] = L;
+        }
+        return;
+      }
+    }
     const size_t rows_total = (size_t)p.B * p.Hq * p.Bq;
     const size_t wrow = (size_t)split * rows_total + grow;
 #pragma unroll
@@ -206,6 +240,7 @@ hipError_t launch_d(const PassParams& p, PassMode mode, hipStream_t s) {
     case kPassSparseRefresh: hipLaunchKernelGGL((attn_f32_kernel<D, kPassSparseRefresh>), grid, block, 0, s, p); break;
     case kPassSparseReuse: hipLaunchKernelGGL((attn_f32_kernel<D, kPassSparseReuse>), grid, block, 0, s, p); break;
     case kPassDenseHeads: hipLaunchKernelGGL((attn_f32_kernel<D, kPassDenseHeads>), grid, block, 0, s, p); break;
+    case kPassDensePaged: hipLaunchKernelGGL((attn_f32_kernel<D, kPassDensePaged>), grid, block, 0, s, p); break;
   }
   return hipGetLastError();
 }

@@ -410,6 +410,25 @@ __global__ __launch_bounds__(256) void head_similarity_kernel(const float* __res
 
 }  // namespace
 
+// order[r] = index of the sequence with the r-th longest prefix (ties: lower index first).  Rank by
+// counting: B is a batch size, so the B^2 comparisons are a few microseconds at most.
+__global__ __launch_bounds__(256) void seq_order_kernel(const int32_t* __restrict__ lens, int32_t* __restrict__ order, int B) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= B) return;
+  const int li = lens[i];
+  int rank = 0;
+  for (int j = 0; j < B; ++j) {
+    const int lj = lens[j];
+    rank += (lj > li || (lj == li && j < i)) ? 1 : 0;
+  }
+  order[rank] = i;
+}
+
+hipError_t launch_seq_order(const int32_t* prefix_lens, int32_t* seq_order, int B, hipStream_t s) {
+  hipLaunchKernelGGL(seq_order_kernel, dim3((B + 255) / 256), dim3(256), 0, s, prefix_lens, seq_order, B);
+  return hipGetLastError();
+}
+
 hipError_t launch_head_similarity(const float* o_a, const float* o_b, float* sim, int BH, int Bq, int D, hipStream_t s) {
   hipLaunchKernelGGL(head_similarity_kernel, dim3(BH), dim3(256), 0, s, o_a, o_b, sim, Bq, D);
   return hipGetLastError();

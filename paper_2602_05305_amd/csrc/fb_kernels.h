@@ -41,7 +41,8 @@ enum PassMode : int {
   kPassInternal = 1,       // keys [0, nkeys), no split; epilogue = Eq. 8-9 merge with cached partial
   kPassSparseRefresh = 2,  // like dense, but every key block is routed to the selected or the residual set
   kPassSparseReuse = 3,    // only key blocks of the per-KV-group union list; selected set only
-  kPassDenseHeads = 4      // dense, but only query heads flagged in head_on take part (others keep their cache)
+  kPassDenseHeads = 4,     // dense, but only query heads flagged in head_on take part (others keep their cache)
+  kPassDensePaged = 5      // dense over a paged KV pool with a block table and per-sequence prefix lengths
 };
 
 // One attention pass.  Rows of one KV group are addressed "group-flattened": query head
@@ -66,7 +67,16 @@ struct PassParams {
   const int32_t* union_cnt;   // [B,Hkv]
   int key_block, nblk;
   const uint8_t* head_on;     // [B,Hq] per-head refresh flags (kPassDenseHeads), else null
+  // paged pass: k/v point at the pools [num_pages, Hkv, page_size, D]
+  const int32_t* block_table; // [B, max_pages] page ids
+  const int32_t* prefix_lens; // [B] keys per sequence (<= nkeys)
+  int page_size, max_pages, num_pages;
+  const int32_t* seq_order;   // [B] sequences by descending prefix length (longest work is dispatched first), or null
+  // dense / heads / paged pass with nsplit == 1: ws_o / ws_m / ws_l are the caller's final (o, m, lse)
+  // arrays and the kernel emits natural-log units itself (no combine pass)
+  int direct;
   FastDiv div_rowtiles, div_nsplit, div_hkv;   // bf16 pass: decomposition of the linear workgroup index
+  FastDiv div_page;                            // bf16 paged pass: key index -> page slot
 };
 
 // Fold split partials (and optionally a cached residual) into final (o, m, lse) partials.
@@ -102,6 +112,7 @@ hipError_t launch_combine(const CombineParams& p, hipStream_t s);
 hipError_t launch_pool_keys(const PoolParams& p, hipStream_t s);
 hipError_t launch_select_topk(const SelectParams& p, hipStream_t s);
 hipError_t launch_build_masks(const MaskParams& p, hipStream_t s);
+hipError_t launch_seq_order(const int32_t* prefix_lens, int32_t* seq_order, int B, hipStream_t s);
 hipError_t launch_head_similarity(const float* o_a, const float* o_b, float* sim, int BH, int Bq, int D, hipStream_t s);
 
 // Row tiles (workgroups along the group-flattened row axis) per KV group, per kernel family.

@@ -26,6 +26,11 @@ class fb_shape(Structure):
                 ("prefix_len", c_int32), ("dtype", c_int32), ("scale", c_float)]
 
 
+class fb_paged_kv(Structure):
+    _fields_ = [("struct_size", c_uint32), ("num_pages", c_int32), ("page_size", c_int32), ("max_pages", c_int32),
+                ("k_pool", c_void_p), ("v_pool", c_void_p), ("block_table", c_void_p), ("prefix_lens", c_void_p)]
+
+
 class FlashBlockError(RuntimeError):
     def __init__(self, status: int, where: str, detail: str = ""):
         self.status = status
@@ -45,6 +50,9 @@ _SIGNATURES = {
     "fb_external_partial_ex": (c_int, [POINTER(fb_shape)] + [c_void_p] * 6 + [c_int32, c_void_p, c_size_t, c_void_p]),
     "fb_external_partial_prof": (c_int, [POINTER(fb_shape)] + [c_void_p] * 6 + [c_int32, c_void_p, c_size_t] + [c_void_p] * 4),
     "fb_external_partial_heads": (c_int, [POINTER(fb_shape)] + [c_void_p] * 8 + [c_size_t, c_void_p]),
+    "fb_paged_splits": (c_int32, [POINTER(fb_shape)]),
+    "fb_external_partial_paged": (c_int, [POINTER(fb_shape), c_void_p, POINTER(fb_paged_kv)] + [c_void_p] * 3
+                                  + [c_int32, c_void_p, c_size_t, c_void_p]),
     "fb_head_similarity": (c_int, [POINTER(fb_shape)] + [c_void_p] * 4),
     "fb_internal_merge": (c_int, [POINTER(fb_shape)] + [c_void_p] * 9),
     "fb_pool_keys": (c_int, [POINTER(fb_shape), c_void_p, c_int32, c_void_p, c_void_p]),
@@ -145,6 +153,23 @@ def fb_external_partial_heads(shape, q, k_prefix, v_prefix, head_mask, o_part, m
                                                   _ptr(workspace), workspace.numel() * workspace.element_size(),
                                                   _stream(stream))
     _check(st, "fb_external_partial_heads")
+
+
+def make_paged_kv(k_pool, v_pool, block_table, prefix_lens) -> fb_paged_kv:
+    """k_pool / v_pool: [num_pages, Hkv, page_size, d]; block_table int32 [B, max_pages]; prefix_lens int32 [B]."""
+    return fb_paged_kv(ctypes.sizeof(fb_paged_kv), k_pool.shape[0], k_pool.shape[2], block_table.shape[1],
+                       k_pool.data_ptr(), v_pool.data_ptr(), block_table.data_ptr(), prefix_lens.data_ptr())
+
+
+def fb_paged_splits(shape) -> int:
+    return int(load_library().fb_paged_splits(ctypes.byref(shape)))
+
+
+def fb_external_partial_paged(shape, q, kv, o_part, m_part, lse_part, workspace, n_splits=0, stream=None):
+    st = load_library().fb_external_partial_paged(ctypes.byref(shape), _ptr(q), ctypes.byref(kv), _ptr(o_part),
+                                                  _ptr(m_part), _ptr(lse_part), n_splits, _ptr(workspace),
+                                                  workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(st, "fb_external_partial_paged")
 
 
 def fb_head_similarity(shape, o_a, o_b, sim, stream=None):

@@ -104,3 +104,40 @@ def make_block_steps(w: Workload, seed: int, steps: int | None = None):
         V = round_storage(V + sg * rng.standard_normal(ks, dtype=np.float32), w.dtype)
         out.append((Q, K, V))
     return out
+
+
+def make_paged_prefix(w: Workload, seed: int, page_size: int, lens, spare_pages: int = 3):
+    """A paged prefix cache for per-sequence prefix lengths `lens` (one per batch element, each
+    <= w.prefix_len).  Returns (seqs, K_pool, V_pool, block_table, lens):
+      seqs        list over the batch of (K_b, V_b), float32 [Hkv, lens[b], d]: the contiguous view
+      K_pool/V_pool  float32 [num_pages, Hkv, page_size, d]; pages are handed out in a seeded random
+                  order, rows past a sequence's length and the spare pages hold random values (reading
+                  them would change the result)
+      block_table int32 [B, max_pages], -1 where a sequence has no page
+      lens        int32 [B]
+    """
+    rng = np.random.default_rng([seed, 3])
+    lens = np.asarray(lens, dtype=np.int32)
+    assert lens.shape == (w.batch,) and (lens >= 0).all() and (lens <= w.prefix_len).all()
+    max_pages = max(1, -(-w.prefix_len // page_size))
+    need = [-(-int(n) // page_size) for n in lens]
+    num_pages = sum(need) + spare_pages
+    sc = np.float32(w.input_scale)
+    pshape = (num_pages, w.n_kv_heads, page_size, w.head_dim)
+    K_pool = round_storage(rng.standard_normal(pshape, dtype=np.float32) * sc, w.dtype)
+    V_pool = round_storage(rng.standard_normal(pshape, dtype=np.float32) * sc, w.dtype)
+    order = rng.permutation(num_pages)
+    table = np.full((w.batch, max_pages), -1, dtype=np.int32)
+    seqs, nxt = [], 0
+    for b in range(w.batch):
+        table[b, :need[b]] = order[nxt:nxt + need[b]]
+        nxt += need[b]
+        n = int(lens[b])
+        Kb = np.empty((w.n_kv_heads, n, w.head_dim), dtype=np.float32)
+        Vb = np.empty_like(Kb)
+        for j in range(need[b]):
+            lo, hi = j * page_size, min(n, (j + 1) * page_size)
+            Kb[:, lo:hi] = K_pool[table[b, j], :, :hi - lo]
+            Vb[:, lo:hi] = V_pool[table[b, j], :, :hi - lo]
+        seqs.append((Kb, Vb))
+    return seqs, K_pool, V_pool, table, lens

@@ -116,6 +116,35 @@ def test_external_partial_heads_error_paths():
     assert call(ctypes.byref(s), FAKE, FAKE, FAKE, ODD, ODD, FAKE, FAKE, FAKE, ws_bytes, None) == fb.FB_ERR_ALIGN  # mask may be unaligned, o may not
 
 
+def _paged(**kw):
+    base = dict(struct_size=ctypes.sizeof(fb.fb_paged_kv), num_pages=8, page_size=64, max_pages=4,
+                k_pool=0x1000, v_pool=0x1000, block_table=0x1000, prefix_lens=0x1000)
+    base.update(kw)
+    return fb.fb_paged_kv(**base)
+
+
+def test_external_partial_paged_error_paths():
+    lib = fb.load_library()
+    s = _ok_shape()                       # prefix_len 256 = 4 pages of 64
+    ws_bytes = fb.fb_workspace_bytes(s, 0, 0, fb.fb_paged_splits(s))
+    call = lib.fb_external_partial_paged
+    tail = (FAKE, FAKE, FAKE, 0, FAKE, ws_bytes, None)
+    assert ctypes.sizeof(fb.fb_paged_kv) == 48
+    assert call(ctypes.byref(s), FAKE, None, *tail) == fb.FB_ERR_NULL
+    assert call(ctypes.byref(s), None, ctypes.byref(_paged()), *tail) == fb.FB_ERR_NULL
+    assert call(ctypes.byref(s), FAKE, ctypes.byref(_paged(struct_size=40)), *tail) == fb.FB_ERR_SHAPE
+    assert call(ctypes.byref(s), FAKE, ctypes.byref(_paged(block_table=None)), *tail) == fb.FB_ERR_NULL
+    assert call(ctypes.byref(s), FAKE, ctypes.byref(_paged(prefix_lens=None)), *tail) == fb.FB_ERR_NULL
+    assert call(ctypes.byref(s), FAKE, ctypes.byref(_paged(k_pool=None)), *tail) == fb.FB_ERR_NULL
+    assert call(ctypes.byref(s), FAKE, ctypes.byref(_paged(page_size=96)), *tail) == fb.FB_ERR_UNSUPPORTED
+    assert call(ctypes.byref(s), FAKE, ctypes.byref(_paged(page_size=0)), *tail) == fb.FB_ERR_SHAPE
+    assert call(ctypes.byref(s), FAKE, ctypes.byref(_paged(num_pages=0)), *tail) == fb.FB_ERR_SHAPE
+    assert call(ctypes.byref(s), FAKE, ctypes.byref(_paged(max_pages=3)), *tail) == fb.FB_ERR_SHAPE   # 3*64 < 256
+    assert call(ctypes.byref(s), FAKE, ctypes.byref(_paged(v_pool=0x1004)), *tail) == fb.FB_ERR_ALIGN
+    assert call(ctypes.byref(s), FAKE, ctypes.byref(_paged()), FAKE, FAKE, FAKE, 0, FAKE, ws_bytes - 1, None) == fb.FB_ERR_WORKSPACE
+    assert call(ctypes.byref(s), FAKE, ctypes.byref(_paged()), FAKE, FAKE, FAKE, 300, FAKE, 1 << 30, None) == fb.FB_ERR_SHAPE
+
+
 def test_internal_merge_error_paths():
     lib = fb.load_library()
     s = _ok_shape()
