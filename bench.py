@@ -309,6 +309,49 @@ def sparse_extra(torch, fb, wl):
             "refresh_GBps_vs_kv_bytes": round(w.kv_bytes / t_refresh / 1e3, 1)}
 
 
+def paged_extra(torch, fb, wl):
+    """Paged prefix cache with ragged per-sequence lengths (the serving shape): batch 32, prefix
+    lengths uniform in [512, 8192], 256-token pages handed out in random order.  Bandwidth is priced
+    against the K/V bytes of the tokens that exist, not of the padded maximum."""
+    import numpy as np
+    base = wl.CONFIGS["llm_32k"]
+    B, pmax, page = 32, 8192, 256
+    rng = np.random.default_rng([2602, 5305])
+    lens = rng.integers(512, pmax + 1, size=B).astype(np.int32)
+    lens[0] = pmax
+    need = [-(-int(n) // page) for n in lens]
+    npages = sum(need) + 3
+    table = np.full((B, pmax // page), -1, dtype=np.int32)
+    order, nxt = rng.permutation(npages), 0
+    for b in range(B):
+        table[b, :need[b]] = order[nxt:nxt + need[b]]
+        nxt += need[b]
+    shape = fb.make_shape(B, base.n_q_heads, base.n_kv_heads, base.head_dim, base.block_len, pmax, "bf16")
+    sc = float(base.input_scale)
+    pools = [tuple((torch.randn((npages, base.n_kv_heads, page, base.head_dim), device="cuda") * sc).to(torch.bfloat16)
+                   for _ in range(2)) for _ in range(2)]
+    tbl, ln = torch.from_numpy(table).cuda(), torch.from_numpy(lens).cuda()
+    kvs = [fb.make_paged_kv(k, v, tbl, ln) for k, v in pools]
+    q = (torch.randn((B, base.n_q_heads, base.block_len, base.head_dim), device="cuda") * sc).to(torch.bfloat16)
+    rows = (B, base.n_q_heads, base.block_len)
+    o = torch.empty(rows + (base.head_dim,), device="cuda")
+    m, l = torch.empty(rows, device="cuda"), torch.empty(rows, device="cuda")
+    ns = fb.fb_paged_splits(shape)
+    ws = torch.empty(fb.fb_workspace_bytes(shape, 0, 0, ns), device="cuda", dtype=torch.uint8)
+    i = [0]
+
+    def call():
+        fb.fb_external_partial_paged(shape, q, kvs[i[0] % 2], o, m, l, ws)
+        i[0] += 1
+    t = _ev_median_us(torch, call)
+    kv_bytes = int(lens.sum()) * base.n_kv_heads * base.head_dim * 2 * 2
+    return {"workload": f"paged external pass: batch {B}, prefix lengths uniform 512..{pmax} ({int(lens.sum())} tokens), "
+                        f"{page}-token pages in random order, {base.n_q_heads} q / {base.n_kv_heads} kv heads, "
+                        f"head_dim {base.head_dim}, block {base.block_len}, bf16",
+            "splits": ns, "external_call_us": round(t, 1), "kv_bytes": kv_bytes,
+            "GBps_vs_kv_bytes": round(kv_bytes / t / 1e3, 1), "frac_of_8TBps": round(kv_bytes / t / 1e3 / 8000.0, 4)}
+
+
 def sparse_accuracy(torch, fb, wl, prefix_len=32768):
     """Synthetic analogue of the paper's Table 3: mean L1 distance to full attention on reuse steps
     of sparse attention alone vs. sparse attention + the cached residual, per attention density.
@@ -367,7 +410,7 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch every step eagerly instead of per-block HIP graphs")
     ap.add_argument("--no-long", action="store_true", help="skip the 128K-context external-pass measurement")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--no-extras", action="store_true", help="skip the video-shaped (MFMA) and sparse measurements")
+    ap.add_argument("--no-extras", action="store_true", help="skip the video-shaped (MFMA), sparse and paged measurements")
     ap.add_argument("--profile-external", type=int, default=0, metavar="N",
                     help="only run N whole blocks of the workload, eagerly (for rocprofv3), print nothing else")
     ap.add_argument("--sparse-accuracy", action="store_true",
@@ -485,6 +528,8 @@ def main():
         line["video_mfma"] = video_extra(torch, fb, wl)
         torch.cuda.empty_cache()
         line["sparse_64k"] = sparse_extra(torch, fb, wl)
+        torch.cuda.empty_cache()
+        line["paged_b32"] = paged_extra(torch, fb, wl)
         torch.cuda.empty_cache()
 
     if not args.no_cpu:

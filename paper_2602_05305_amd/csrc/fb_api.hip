@@ -93,15 +93,16 @@ int sparse_splits(const fb_shape* s, bool refresh) {
 }
 
 // Paged pass: sequences differ in length, so equal split counts give unequal workgroups.  Aim at
-// ~4 workgroups per CU (the dispatcher evens them out), each with at least 8 tiles on the longest sequence.
+// ~2 eight-wavefront workgroups per CU (dispatched longest sequence first, the hardware dispatcher
+// evens them out), each with at least 16 tiles on the longest sequence.
 int paged_splits(const fb_shape* s) {
   if (s->dtype != FB_BF16) return auto_splits(s);
   const int tiles = (s->prefix_len + fb::kKeyTile - 1) / fb::kKeyTile;
   const int G = s->n_q_heads / s->n_kv_heads;
   const long long groups =
       (long long)s->batch * s->n_kv_heads * ((G * s->block_len + fb::kRowsPerWgBf16 - 1) / fb::kRowsPerWgBf16);
-  long long ns = (1024 + groups - 1) / groups;
-  const long long cap = tiles / 8;
+  long long ns = (512 + groups - 1) / groups;
+  const long long cap = tiles / 16;
   if (ns > cap) ns = cap;
   if (ns > FB_MAX_SPLITS) ns = FB_MAX_SPLITS;
   if (ns < 1) ns = 1;

@@ -728,7 +728,8 @@ hipError_t launch_d(const PassParams& p, PassMode mode, hipStream_t s) {
     }
     case kPassDensePaged: {
       const int tiles = (p.nkeys + kKeyTile - 1) / kKeyTile;
-      if (p.nsplit > 1 && tiles >= 8 * p.nsplit) return launch_one<D, kPassDensePaged, kKeyTile, 1, 2>(p, s);
+      // two wavefront groups also without splits: the longest sequence's workgroup sets the pass time
+      if (tiles >= 16 * p.nsplit) return launch_one<D, kPassDensePaged, kKeyTile, 1, 2>(p, s);
       return launch_one<D, kPassDensePaged, kKeyTile, 1, 1>(p, s);
     }
     case kPassSparseReuse:

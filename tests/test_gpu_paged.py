@@ -114,3 +114,14 @@ def test_paged_lengths_are_clamped_and_bad_pages_stay_in_pool():
     fb.fb_external_partial_paged(shape, q, fb.make_paged_kv(kpool, vpool, bad, big), ext.o, ext.m, ext.lse, ws)
     torch.cuda.synchronize()
     assert torch.isfinite(ext.o).all() and torch.isfinite(ext.lse).all()
+
+
+def test_paged_serving_shape_batch32_full_tensors():
+    """The benchmark's paged shape at full size, library-chosen split count: batch 32, 32 q / 8 kv
+    heads, d128, block 32, prefix lengths uniform in [512, 8192] (one at the maximum, one a single
+    ragged tile), 256-token pages.  The oracle computes every sequence."""
+    w = wl.Workload("paged_b32", 32, 32, 8, 128, 8192, 32, 1, 1, "bf16", 1.0 / np.sqrt(128.0))
+    rng = np.random.default_rng(4100)
+    lens = rng.integers(512, 8193, size=32)
+    lens[0], lens[5] = 8192, 37
+    _run_paged(w, seed=4100, page_size=256, lens=lens)
