@@ -56,19 +56,21 @@ class HipEvents:
         self.hip.hipEventDestroy(ev)
 
 
-def external_algorithmic_bytes(w):
+def external_algorithmic_bytes(w, fused=False):
     """Bytes the external pass must move per launch: prefix K and V once, Q once, and the
-    (o, m, lse) partial written once.  Split-KV scratch traffic is overhead, not counted."""
+    (o, m, lse) partial written once.  Split-KV scratch traffic is overhead, not counted.
+    The fused refresh launch also reads the block's own K and V."""
     esz = 4 if w.dtype == "f32" else 2
     rows = w.batch * w.n_q_heads * w.block_len
-    return w.kv_bytes + rows * w.head_dim * esz + rows * (w.head_dim + 2) * 4
+    blk = 2 * w.batch * w.n_kv_heads * w.block_len * w.head_dim * esz if fused else 0
+    return w.kv_bytes + rows * w.head_dim * esz + rows * (w.head_dim + 2) * 4 + blk
 
 
 class DeviceBlock:
     """Device-resident synthetic data of one workload: NSETS prefix K/V sets, one block's per-step
     (Q, K_block, V_block), the cached partial, outputs and workspace."""
 
-    def __init__(self, w, nsets, seed=1234):
+    def __init__(self, w, nsets, seed=1234, fused=False):
         import torch
         from paper_2602_05305_amd import flashblock as fb
         self.w, self.fb, self.torch = w, fb, torch
@@ -96,11 +98,17 @@ class DeviceBlock:
         self.out = torch.empty(qs, device="cuda", dtype=dt)
         self.ws = torch.empty(fb.fb_workspace_bytes(self.shape), device="cuda", dtype=torch.uint8)
         self.nsets = nsets
+        self.fused = fused       # refresh steps through fb_refresh_step (one streaming launch + one combine)
 
     def step(self, t, kv_set, R, prof=None):
         """One diffusion step t of a block whose prefix is K/V set kv_set."""
         fb = self.fb
         q, kb, vb = self.steps[t]
+        if t % R == 0 and self.fused:
+            ev = prof if prof is not None else (None, None, None)
+            fb.fb_refresh_step_prof(self.shape, q, self.K[kv_set], self.V[kv_set], kb, vb, self.o, self.m, self.lse,
+                                    self.out, None, self.ws, ev[0], ev[1], ev[2])
+            return
         if t % R == 0:
             if prof is None:
                 fb.fb_external_partial(self.shape, q, self.K[kv_set], self.V[kv_set], self.o, self.m, self.lse, self.ws)
@@ -199,10 +207,12 @@ def read_traffic(workload_name):
     return None
 
 
-def roofline_obj(w, attn_ms, traffic=None):
-    alg = external_algorithmic_bytes(w)
+def roofline_obj(w, attn_ms, traffic=None, fused=False):
+    alg = external_algorithmic_bytes(w, fused)
     ach = alg / (attn_ms * 1e-3) / 1e9
-    return {"bound": "hbm", "kernel": "fb::attn_bf16_kernel<128, 0, 64, 1, 2> (external pass, streaming attention kernel)",
+    kern = ("fb::attn_bf16_kernel<128, 6, 64, 1, 2> (refresh step: prefix splits + the block's own keys, one streaming launch)"
+            if fused else "fb::attn_bf16_kernel<128, 0, 64, 1, 2> (external pass, streaming attention kernel)")
+    return {"bound": "hbm", "kernel": kern,
             "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": traffic,
             "algorithmic_bytes_per_launch": alg, "avg_launch_us": round(attn_ms * 1e3, 2)}
@@ -408,6 +418,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=400)
     ap.add_argument("--workload", default="llm_32k")
     ap.add_argument("--no-graph", action="store_true", help="launch every step eagerly instead of per-block HIP graphs")
+    ap.add_argument("--fused", action="store_true",
+                    help="refresh steps through fb_refresh_step (2 launches) instead of fb_external_partial + "
+                         "fb_internal_merge (3 launches); measured slower at the LLM shapes, where its 8 extra "
+                         "workgroups do not fit beside the 256 that already fill the CUs")
     ap.add_argument("--no-long", action="store_true", help="skip the 128K-context external-pass measurement")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-extras", action="store_true", help="skip the video-shaped (MFMA), sparse and paged measurements")
@@ -468,7 +482,7 @@ def main():
     if args.profile_external > 0:
         # the same loop as the event-timed pass of the benchmark: whole blocks, one refresh step and
         # steps-1 reuse steps each, K/V sets rotated per block
-        d = DeviceBlock(w, max(2, min(4, int(-(-600e6 // w.kv_bytes)))))
+        d = DeviceBlock(w, max(2, min(4, int(-(-600e6 // w.kv_bytes)))), fused=args.fused)
         for b in range(args.profile_external):
             for t in range(w.steps):
                 d.step(t, b % d.nsets, w.refresh)
@@ -477,7 +491,8 @@ def main():
         return
     K, W = args.steps, args.warmup
     nsets = max(2, min(4, int(-(-600e6 // w.kv_bytes))))     # working set well beyond the last-level cache
-    dev = DeviceBlock(w, nsets)
+    fused = args.fused
+    dev = DeviceBlock(w, nsets, fused=fused)
 
     use_graph = not args.no_graph
     sec = time_steps(dev, K, W, w.refresh, use_graph)
@@ -496,8 +511,9 @@ def main():
         "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": describe(w), "kv_buffer_sets_rotated": nsets,
                    "launch": "one HIP graph per block" if use_graph else "eager",
+                   "refresh_step": "fb_refresh_step (2 launches)" if fused else "fb_external_partial + fb_internal_merge (3 launches)",
                    "external_splits": fb.fb_external_splits(dev.shape)},
-        "roofline": roofline_obj(w, prof["attn_ms"], traffic),
+        "roofline": roofline_obj(w, prof["attn_ms"], traffic, fused),
         "steps_detail": {"refresh_step_us": round(prof["refresh_step_ms"] * 1e3, 2),
                          "reuse_step_us": round(prof["reuse_step_ms"] * 1e3, 2),
                          "external_attn_kernel_us": round(prof["attn_ms"] * 1e3, 2),
@@ -511,11 +527,11 @@ def main():
 
     if not args.no_long:
         wl128 = wl.CONFIGS["long_128k"]
-        d2 = DeviceBlock(wl128, 2)
+        d2 = DeviceBlock(wl128, 2, fused=fused)
         for _ in range(3):
             d2.step(0, 0, wl128.refresh)
         p2 = profile_external(d2, 21, wl128.refresh)
-        r2 = roofline_obj(wl128, p2["attn_ms"], read_traffic(wl128.name))
+        r2 = roofline_obj(wl128, p2["attn_ms"], read_traffic(wl128.name), fused)
         r2["workload"] = describe(wl128)
         r2["external_call_us"] = round((p2["attn_ms"] + p2["combine_ms"]) * 1e3, 2)
         r2["refresh_step_us"] = round(p2["refresh_step_ms"] * 1e3, 2)

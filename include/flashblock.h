@@ -219,6 +219,31 @@ fb_status fb_internal_merge(const fb_shape* shape, const void* q, const void* k_
                             const float* lse_part, void* out, float* lse_out, void* hip_stream);
 
 /*
+ * A whole refresh step in two launches: the single-pass formulation of Section 4.4 (one attention
+ * pass over [prefix || block] whose block-external statistics are kept at the block boundary), cut
+ * into splits for a 256-CU part.  One streaming launch covers the prefix splits and, as one more
+ * split, the block's own keys; the combine launch folds the prefix splits into the partial to
+ * cache (o_part, m_part, lse_part: exactly what fb_external_partial returns, up to the order of
+ * floating-point sums) and, in the same pass, merges it with the block-internal statistics by
+ * Eq. 8-9 into out / lse_out (what fb_internal_merge would return for this step).
+ * Arguments as in fb_external_partial and fb_internal_merge; lse_out may be NULL.
+ * workspace: >= fb_workspace_bytes(shape, 0, 0, 0).
+ */
+fb_status fb_refresh_step(const fb_shape* shape, const void* q, const void* k_prefix,
+                          const void* v_prefix, const void* k_block, const void* v_block,
+                          float* o_part, float* m_part, float* lse_part, void* out, float* lse_out,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Profiling aid: fb_refresh_step that also records three caller-created HIP events, as
+ * fb_external_partial_prof does (before the streaming kernel, between it and the combine, after
+ * the combine).  Any of the three may be NULL.  Results are identical to fb_refresh_step. */
+fb_status fb_refresh_step_prof(const fb_shape* shape, const void* q, const void* k_prefix,
+                               const void* v_prefix, const void* k_block, const void* v_block,
+                               float* o_part, float* m_part, float* lse_part, void* out,
+                               float* lse_out, void* workspace, size_t workspace_bytes,
+                               void* ev_begin, void* ev_attn_end, void* ev_end, void* hip_stream);
+
+/*
  * Sparse variant, key-block selection (this library's workload rule; the paper leaves the
  * sparse policy to the sparse-attention method it is combined with, Appendix D).
  * fb_pool_keys: mean over the tokens of every key block of key_block tokens (last block may be

@@ -115,12 +115,12 @@ struct WsLayout {
   size_t o[2], m[2], l[2], mask, ulist, ucnt, order, total;
 };
 
-WsLayout ws_layout(const fb_shape* s, int nsplit, int nsets, int nblk) {
+WsLayout ws_layout(const fb_shape* s, int nsplit, int nsets, int nblk, int nsplit2 = -1) {
   WsLayout w;
   const size_t rows = (size_t)rows_of(s);
   size_t off = 0;
   for (int i = 0; i < 2; ++i) {
-    const size_t n = (i < nsets) ? (size_t)nsplit * rows : 0;
+    const size_t n = (i < nsets) ? (size_t)((i == 1 && nsplit2 >= 0) ? nsplit2 : nsplit) * rows : 0;
     w.o[i] = off; off = align256(off + n * s->head_dim * sizeof(float));
     w.m[i] = off; off = align256(off + n * sizeof(float));
     w.l[i] = off; off = align256(off + n * sizeof(float));
@@ -197,7 +197,7 @@ size_t fb_workspace_bytes(const fb_shape* shape, int32_t key_block, int32_t topk
   if (check_shape(shape) != FB_OK) return 0;
   if (n_splits < 0 || n_splits > FB_MAX_SPLITS) return 0;
   const int ns = n_splits > 0 ? n_splits : auto_splits(shape);
-  size_t t = ws_layout(shape, ns, 1, 0).total;
+  size_t t = ws_layout(shape, ns, 2, 0, 1).total;   // + one block-internal partial for fb_refresh_step
   if (key_block != 0) {
     int nblk = 0;
     if (check_key_block(shape, key_block, topk, &nblk) != FB_OK) return 0;
@@ -350,6 +350,57 @@ fb_status fb_internal_merge(const fb_shape* shape, const void* q, const void* k_
   hipError_t e = launch_attn(shape, p, fb::kPassInternal, (hipStream_t)hip_stream);
   if (e != hipSuccess) return hip_fail(e);
   return FB_OK;
+}
+
+fb_status fb_refresh_step_prof(const fb_shape* shape, const void* q, const void* k_prefix, const void* v_prefix,
+                               const void* k_block, const void* v_block, float* o_part, float* m_part,
+                               float* lse_part, void* out, float* lse_out, void* workspace,
+                               size_t workspace_bytes, void* ev_begin, void* ev_attn_end, void* ev_end,
+                               void* hip_stream) {
+  fb_status st = check_shape(shape);
+  if (st != FB_OK) return st;
+  if (!q || !k_block || !v_block || !o_part || !m_part || !lse_part || !out) return FB_ERR_NULL;
+  if (shape->prefix_len > 0 && (!k_prefix || !v_prefix)) return FB_ERR_NULL;
+  if (!aligned16(q) || !aligned16(k_prefix) || !aligned16(v_prefix) || !aligned16(k_block) ||
+      !aligned16(v_block) || !aligned16(o_part) || !aligned16(m_part) || !aligned16(lse_part) ||
+      !aligned16(out) || !aligned16(lse_out) || !aligned16(workspace))
+    return FB_ERR_ALIGN;
+  const int ns = auto_splits(shape);
+  const WsLayout w = ws_layout(shape, ns, 2, 0, 1);
+  if (!workspace || workspace_bytes < w.total) return FB_ERR_WORKSPACE;
+
+  hipStream_t stream = (hipStream_t)hip_stream;
+  char* ws = (char*)workspace;
+  fb::PassParams p = base_pass(shape, q, k_prefix, v_prefix, shape->prefix_len, ns);
+  p.k2 = k_block; p.v2 = v_block;
+  p.ws_o = (float*)(ws + w.o[0]); p.ws_m = (float*)(ws + w.m[0]); p.ws_l = (float*)(ws + w.l[0]);
+  p.ws_o2 = (float*)(ws + w.o[1]); p.ws_m2 = (float*)(ws + w.m[1]); p.ws_l2 = (float*)(ws + w.l[1]);
+  hipError_t e = hipSuccess;
+  if (ev_begin && (e = hipEventRecord((hipEvent_t)ev_begin, stream)) != hipSuccess) return hip_fail(e);
+  e = launch_attn(shape, p, fb::kPassRefreshFused, stream);
+  if (e != hipSuccess) return hip_fail(e);
+  if (ev_attn_end && (e = hipEventRecord((hipEvent_t)ev_attn_end, stream)) != hipSuccess) return hip_fail(e);
+
+  fb::CombineParams c;
+  memset(&c, 0, sizeof(c));
+  c.rows = (int)rows_of(shape); c.D = shape->head_dim; c.nsplit = ns;
+  c.ws_o = p.ws_o; c.ws_m = p.ws_m; c.ws_l = p.ws_l;
+  c.o = o_part; c.m = m_part; c.lse = lse_part;
+  c.Bq = shape->block_len;
+  c.blk_o = p.ws_o2; c.blk_m = p.ws_m2; c.blk_l = p.ws_l2;
+  c.fin_out = out; c.fin_lse = lse_out; c.fin_bf16 = shape->dtype == FB_BF16;
+  e = fb::launch_combine(c, stream);
+  if (e != hipSuccess) return hip_fail(e);
+  if (ev_end && (e = hipEventRecord((hipEvent_t)ev_end, stream)) != hipSuccess) return hip_fail(e);
+  return FB_OK;
+}
+
+fb_status fb_refresh_step(const fb_shape* shape, const void* q, const void* k_prefix, const void* v_prefix,
+                          const void* k_block, const void* v_block, float* o_part, float* m_part,
+                          float* lse_part, void* out, float* lse_out, void* workspace, size_t workspace_bytes,
+                          void* hip_stream) {
+  return fb_refresh_step_prof(shape, q, k_prefix, v_prefix, k_block, v_block, o_part, m_part, lse_part, out,
+                              lse_out, workspace, workspace_bytes, nullptr, nullptr, nullptr, hip_stream);
 }
 
 fb_status fb_pool_keys(const fb_shape* shape, const void* k_prefix, int32_t key_block, float* k_pooled,

@@ -294,7 +294,8 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
   // instead of the one that two sets in a single wavefront allow.
   constexpr bool kSetSplit = (MODE == kPassSparseRefresh && NG == 2);
   constexpr int TG = kSetSplit ? 1 : NG;          // wavefront groups that own separate tile streams
-  static_assert(NG == 1 || MODE == kPassDense || MODE == kPassDenseHeads || MODE == kPassDensePaged || MODE == kPassSparseReuse || kSetSplit,
+  static_assert(NG == 1 || MODE == kPassDense || MODE == kPassDenseHeads || MODE == kPassDensePaged || MODE == kPassRefreshFused ||
+                    MODE == kPassSparseReuse || kSetSplit,
                 "unsupported group mode");
 
   // wavefront-uniform by construction; in the paged pass, telling the compiler so keeps the block-table
@@ -341,6 +342,11 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
   }
   const int bk = b * p.Hkv + kvh;
   int nkeys = p.nkeys;
+  // fused refresh pass: the workgroups of split index nsplit take the block's own keys
+  const bool own_block = (MODE == kPassRefreshFused) && (split == p.nsplit);
+  if constexpr (MODE == kPassRefreshFused) {
+    if (own_block) nkeys = p.Bq;
+  }
   if constexpr (MODE == kPassDensePaged) nkeys = min(p.nkeys, max(0, p.prefix_lens[b]));   // this sequence's prefix
 
   // WS wavefronts share one 32-row group and split the output columns between them (each repeats
@@ -365,6 +371,12 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
   // contiguous cache: this KV head's [nkeys, D] slab; paged cache: the pool (tiles add their page offset)
   const __bf16* __restrict__ K = (const __bf16*)p.k + ((MODE == kPassDensePaged) ? (size_t)0 : (size_t)bk * nkeys * D);
   const __bf16* __restrict__ V = (const __bf16*)p.v + ((MODE == kPassDensePaged) ? (size_t)0 : (size_t)bk * nkeys * D);
+  if constexpr (MODE == kPassRefreshFused) {
+    if (own_block) {
+      K = (const __bf16*)p.k2 + (size_t)bk * nkeys * D;
+      V = (const __bf16*)p.v2 + (size_t)bk * nkeys * D;
+    }
+  }
 
   // tile list of this workgroup
   int tpb = 1, total;
@@ -374,7 +386,10 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
   } else {
     total = (nkeys + KT - 1) / KT;
   }
-  const TileRange tr = split_range(total, p.nsplit, split);
+  TileRange tr = split_range(total, p.nsplit, split);
+  if constexpr (MODE == kPassRefreshFused) {
+    if (own_block) tr = TileRange{0, total};
+  }
   const uint32_t* __restrict__ bmask = p.blk_mask ? p.blk_mask + (size_t)bk * p.nblk : nullptr;
   const int32_t* __restrict__ ulist = p.union_list ? p.union_list + (size_t)bk * p.nblk : nullptr;
   const uint32_t my_bit = 1u << ((row_ok ? row : 0) / p.Bq);
@@ -618,10 +633,11 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
       }
     }
     const size_t rows_total = (size_t)p.B * p.Hq * p.Bq;
-    const size_t wrow = (size_t)split * rows_total + grow;
-    float* __restrict__ w_o = (kSetSplit && grp == 1) ? p.ws_o2 : p.ws_o;
-    float* __restrict__ w_m = (kSetSplit && grp == 1) ? p.ws_m2 : p.ws_m;
-    float* __restrict__ w_l = (kSetSplit && grp == 1) ? p.ws_l2 : p.ws_l;
+    const size_t wrow = (own_block ? (size_t)0 : (size_t)split * rows_total) + grow;
+    const bool set1 = (kSetSplit && grp == 1) || own_block;
+    float* __restrict__ w_o = set1 ? p.ws_o2 : p.ws_o;
+    float* __restrict__ w_m = set1 ? p.ws_m2 : p.ws_m;
+    float* __restrict__ w_l = set1 ? p.ws_l2 : p.ws_l;
     if (row_ok) {
 #pragma unroll
       for (int db = 0; db < NDBL; ++db)
@@ -671,13 +687,14 @@ hipError_t launch_one(const PassParams& p, hipStream_t s) {
   constexpr int rows_per_wg = kRowsPerWgBf16 / WS;
   const int nrows = p.G * p.Bq;
   const int ntile_rows = (nrows + rows_per_wg - 1) / rows_per_wg;
-  long long nwg = (long long)p.B * p.Hkv * ntile_rows * p.nsplit;
+  const int nunits = p.nsplit + (MODE == kPassRefreshFused ? 1 : 0);   // split indices per (batch, KV head)
+  long long nwg = (long long)p.B * p.Hkv * ntile_rows * nunits;
   if (MODE == kPassDensePaged) nwg = (((long long)p.B * p.Hkv * p.nsplit + 7) / 8) * 8 * ntile_rows;
   if (nwg >= (1ll << 31)) return hipErrorInvalidValue;
   PassParams q = p;
   if (MODE == kPassDensePaged) q.div_page = make_fastdiv((uint32_t)p.page_size);
   q.div_rowtiles = make_fastdiv((uint32_t)ntile_rows);
-  q.div_nsplit = make_fastdiv((uint32_t)p.nsplit);
+  q.div_nsplit = make_fastdiv((uint32_t)nunits);
   q.div_hkv = make_fastdiv((uint32_t)p.Hkv);
   hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(256 * NG), lds, s, q);
   return hipGetLastError();
@@ -725,6 +742,11 @@ hipError_t launch_d(const PassParams& p, PassMode mode, hipStream_t s) {
       const int tiles = (p.nkeys + kKeyTile - 1) / kKeyTile;
       if (p.nsplit > 1 && tiles >= 8 * p.nsplit) return launch_one<D, kPassDenseHeads, kKeyTile, 1, 2>(p, s);
       return launch_one<D, kPassDenseHeads, kKeyTile, 1, 1>(p, s);
+    }
+    case kPassRefreshFused: {
+      const int tiles = (p.nkeys + kKeyTile - 1) / kKeyTile;
+      if (tiles >= 8 * p.nsplit) return launch_one<D, kPassRefreshFused, kKeyTile, 1, 2>(p, s);
+      return launch_one<D, kPassRefreshFused, kKeyTile, 1, 1>(p, s);
     }
     case kPassDensePaged: {
       const int tiles = (p.nkeys + kKeyTile - 1) / kKeyTile;

@@ -86,11 +86,18 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const PassParams p) {
   int nkeys = p.nkeys;
   if constexpr (MODE == kPassDensePaged) nkeys = min(p.nkeys, max(0, p.prefix_lens[b]));   // this sequence's prefix
   const int bk = b * p.Hkv + kvh;
+  // fused refresh pass: the workgroups of split index nsplit take the block's own keys
+  const bool own_block = (MODE == kPassRefreshFused) && (split == p.nsplit);
+  if (own_block) nkeys = p.Bq;
 
   const float* __restrict__ Q = (const float*)p.q + (size_t)(b * p.Hq + h) * p.Bq * D;
   // contiguous cache: this KV head's [nkeys, D] slab; paged cache: the pool (tiles add their page offset)
   const float* __restrict__ K = (const float*)p.k + ((MODE == kPassDensePaged) ? (size_t)0 : (size_t)bk * nkeys * D);
   const float* __restrict__ V = (const float*)p.v + ((MODE == kPassDensePaged) ? (size_t)0 : (size_t)bk * nkeys * D);
+  if (own_block) {
+    K = (const float*)p.k2 + (size_t)bk * nkeys * D;
+    V = (const float*)p.v2 + (size_t)bk * nkeys * D;
+  }
 
   for (int i = tid; i < 4 * D; i += 256) {
     const int r = chunk * 4 + i / D;
@@ -105,7 +112,8 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const PassParams p) {
   } else {
     total = (nkeys + kKeyTile - 1) / kKeyTile;
   }
-  const TileRange tr = split_range(total, p.nsplit, split);
+  TileRange tr = split_range(total, p.nsplit, split);
+  if (own_block) tr = TileRange{0, total};
 
   RowState<NACC> sel, res;   // res only used by the sparse refresh pass
   sel.init();
@@ -212,12 +220,15 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const PassParams p) {
       }
     }
     const size_t rows_total = (size_t)p.B * p.Hq * p.Bq;
-    const size_t wrow = (size_t)split * rows_total + grow;
+    const size_t wrow = (own_block ? (size_t)0 : (size_t)split * rows_total) + grow;
+    float* __restrict__ w_o = own_block ? p.ws_o2 : p.ws_o;
+    float* __restrict__ w_m = own_block ? p.ws_m2 : p.ws_m;
+    float* __restrict__ w_l = own_block ? p.ws_l2 : p.ws_l;
 #pragma unroll
-    for (int i = 0; i < NACC; ++i) p.ws_o[wrow * D + lane + 64 * i] = sel.acc[i];
+    for (int i = 0; i < NACC; ++i) w_o[wrow * D + lane + 64 * i] = sel.acc[i];
     if (lane == 0) {
-      p.ws_m[wrow] = sel.m;
-      p.ws_l[wrow] = sel.l;
+      w_m[wrow] = sel.m;
+      w_l[wrow] = sel.l;
     }
     if constexpr (MODE == kPassSparseRefresh) {
 #pragma unroll
@@ -232,7 +243,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const PassParams p) {
 
 template <int D>
 hipError_t launch_d(const PassParams& p, PassMode mode, hipStream_t s) {
-  const dim3 grid((p.Bq + kRowsPerWgF32 - 1) / kRowsPerWgF32, p.B * p.Hq, p.nsplit);
+  const dim3 grid((p.Bq + kRowsPerWgF32 - 1) / kRowsPerWgF32, p.B * p.Hq, p.nsplit + (mode == kPassRefreshFused ? 1 : 0));
   const dim3 block(256);
   switch (mode) {
     case kPassDense: hipLaunchKernelGGL((attn_f32_kernel<D, kPassDense>), grid, block, 0, s, p); break;
@@ -241,6 +252,7 @@ hipError_t launch_d(const PassParams& p, PassMode mode, hipStream_t s) {
     case kPassSparseReuse: hipLaunchKernelGGL((attn_f32_kernel<D, kPassSparseReuse>), grid, block, 0, s, p); break;
     case kPassDenseHeads: hipLaunchKernelGGL((attn_f32_kernel<D, kPassDenseHeads>), grid, block, 0, s, p); break;
     case kPassDensePaged: hipLaunchKernelGGL((attn_f32_kernel<D, kPassDensePaged>), grid, block, 0, s, p); break;
+    case kPassRefreshFused: hipLaunchKernelGGL((attn_f32_kernel<D, kPassRefreshFused>), grid, block, 0, s, p); break;
   }
   return hipGetLastError();
 }

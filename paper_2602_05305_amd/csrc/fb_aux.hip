@@ -72,6 +72,12 @@ __device__ __forceinline__ void emit(const Folded& f, float* __restrict__ o, flo
   }
 }
 
+// float -> bf16 bits, round to nearest even (inputs are finite)
+__device__ __forceinline__ uint32_t bf16_rne(float x) {
+  const uint32_t u = __float_as_uint(x);
+  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
 __device__ __forceinline__ Folded empty_folded() {
   Folded f;
   f.o = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -95,6 +101,25 @@ __device__ __forceinline__ void finish_row(const CombineParams& p, const Folded&
   if (p.res_out_o != nullptr) emit(res, p.res_out_o, p.res_out_m, p.res_out_lse, row, p.D, c4);
   const Folded total = fold_two(sel, res);
   emit(total, p.o, p.m, p.lse, row, p.D, c4);
+  if (p.fin_out != nullptr) {
+    // fused refresh step: Eq. 8-9 with the block-internal partial, then normalise
+    Folded in;
+    in.m2 = p.blk_m[row];
+    in.l = p.blk_l[row];
+    in.o = *(const float4*)(p.blk_o + row * p.D + c4 * 4);
+    const Folded f = fold_two(total, in);
+    const float inv = f.l > 0.f ? 1.f / f.l : 0.f;
+    const float4 r = make_float4(f.o.x * inv, f.o.y * inv, f.o.z * inv, f.o.w * inv);
+    if (p.fin_bf16) {
+      uint2 pk;
+      pk.x = bf16_rne(r.x) | (bf16_rne(r.y) << 16);
+      pk.y = bf16_rne(r.z) | (bf16_rne(r.w) << 16);
+      *(uint2*)((uint16_t*)p.fin_out + row * p.D + c4 * 4) = pk;
+    } else {
+      *(float4*)((float*)p.fin_out + row * p.D + c4 * 4) = r;
+    }
+    if (p.fin_lse != nullptr && c4 == 0) p.fin_lse[row] = f.l > 0.f ? (f.m2 + log2f(f.l)) * kLn2 : -INFINITY;
+  }
 }
 
 // Few splits: one thread per (row, 4 columns) walks the splits.

@@ -42,7 +42,8 @@ enum PassMode : int {
   kPassSparseRefresh = 2,  // like dense, but every key block is routed to the selected or the residual set
   kPassSparseReuse = 3,    // only key blocks of the per-KV-group union list; selected set only
   kPassDenseHeads = 4,     // dense, but only query heads flagged in head_on take part (others keep their cache)
-  kPassDensePaged = 5      // dense over a paged KV pool with a block table and per-sequence prefix lengths
+  kPassDensePaged = 5,     // dense over a paged KV pool with a block table and per-sequence prefix lengths
+  kPassRefreshFused = 6    // dense over the prefix plus one extra split over the block's own keys (partial set 1)
 };
 
 // One attention pass.  Rows of one KV group are addressed "group-flattened": query head
@@ -72,6 +73,8 @@ struct PassParams {
   const int32_t* prefix_lens; // [B] keys per sequence (<= nkeys)
   int page_size, max_pages, num_pages;
   const int32_t* seq_order;   // [B] sequences by descending prefix length (longest work is dispatched first), or null
+  // fused refresh pass: split index nsplit streams the block's own K/V [B,Hkv,Bq,D] into partial set 1
+  const void* k2; const void* v2;
   // dense / heads / paged pass with nsplit == 1: ws_o / ws_m / ws_l are the caller's final (o, m, lse)
   // arrays and the kernel emits natural-log units itself (no combine pass)
   int direct;
@@ -88,6 +91,10 @@ struct CombineParams {
   float* res_out_o; float* res_out_m; float* res_out_lse;                  // residual out (refresh) or null
   float* o; float* m; float* lse;                                          // total out
   const uint8_t* head_on; int Bq;   // if head_on != null: rows of heads with a zero flag are left untouched
+  // fused refresh step: block-internal partial (one split, log2 domain) merged with the total by Eq. 8-9 into
+  // the normalised output (storage type) and its log-normaliser; null = no final output
+  const float* blk_o; const float* blk_m; const float* blk_l;
+  void* fin_out; float* fin_lse; int fin_bf16;
 };
 
 struct SelectParams {

@@ -55,6 +55,8 @@ _SIGNATURES = {
                                   + [c_int32, c_void_p, c_size_t, c_void_p]),
     "fb_head_similarity": (c_int, [POINTER(fb_shape)] + [c_void_p] * 4),
     "fb_internal_merge": (c_int, [POINTER(fb_shape)] + [c_void_p] * 9),
+    "fb_refresh_step": (c_int, [POINTER(fb_shape)] + [c_void_p] * 11 + [c_size_t, c_void_p]),
+    "fb_refresh_step_prof": (c_int, [POINTER(fb_shape)] + [c_void_p] * 11 + [c_size_t] + [c_void_p] * 4),
     "fb_pool_keys": (c_int, [POINTER(fb_shape), c_void_p, c_int32, c_void_p, c_void_p]),
     "fb_select_topk": (c_int, [POINTER(fb_shape), c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p]),
     "fb_sparse_external_residual": (c_int, [POINTER(fb_shape), c_int32, c_void_p, c_void_p, c_void_p, c_int32,
@@ -181,6 +183,25 @@ def fb_internal_merge(shape, q, k_block, v_block, o_part, m_part, lse_part, out,
     st = load_library().fb_internal_merge(ctypes.byref(shape), _ptr(q), _ptr(k_block), _ptr(v_block), _ptr(o_part),
                                           _ptr(m_part), _ptr(lse_part), _ptr(out), _ptr(lse_out), _stream(stream))
     _check(st, "fb_internal_merge")
+
+
+def fb_refresh_step(shape, q, k_prefix, v_prefix, k_block, v_block, o_part, m_part, lse_part, out, lse_out,
+                    workspace, stream=None):
+    st = load_library().fb_refresh_step(ctypes.byref(shape), _ptr(q), _ptr(k_prefix), _ptr(v_prefix), _ptr(k_block),
+                                        _ptr(v_block), _ptr(o_part), _ptr(m_part), _ptr(lse_part), _ptr(out),
+                                        _ptr(lse_out), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                        _stream(stream))
+    _check(st, "fb_refresh_step")
+
+
+def fb_refresh_step_prof(shape, q, k_prefix, v_prefix, k_block, v_block, o_part, m_part, lse_part, out, lse_out,
+                         workspace, ev_begin, ev_attn_end, ev_end, stream=None):
+    st = load_library().fb_refresh_step_prof(ctypes.byref(shape), _ptr(q), _ptr(k_prefix), _ptr(v_prefix),
+                                             _ptr(k_block), _ptr(v_block), _ptr(o_part), _ptr(m_part),
+                                             _ptr(lse_part), _ptr(out), _ptr(lse_out), _ptr(workspace),
+                                             workspace.numel() * workspace.element_size(),
+                                             ev_begin, ev_attn_end, ev_end, _stream(stream))
+    _check(st, "fb_refresh_step_prof")
 
 
 def fb_pool_keys(shape, k_prefix, key_block, k_pooled, stream=None):

@@ -81,6 +81,7 @@ def test_workspace_and_split_queries():
     assert fb.fb_external_splits(big) == 32      # one 8-wavefront workgroup per CU: 256 CUs / 8 KV heads
 
 
+TOO_SMALL = 256                      # below one split partial of _ok_shape (the general query also covers fb_refresh_step)
 FAKE = ctypes.c_void_p(0x1000)       # aligned, never dereferenced: validation fails first
 ODD = ctypes.c_void_p(0x1004)
 
@@ -96,13 +97,13 @@ def test_external_partial_error_paths():
     assert call(ctypes.byref(s), ODD, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, ws_bytes, None) == fb.FB_ERR_ALIGN
     assert call(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, ODD, FAKE, ws_bytes, None) == fb.FB_ERR_ALIGN
     assert call(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, ws_bytes, None) == fb.FB_ERR_WORKSPACE
-    assert call(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, ws_bytes - 1, None) == fb.FB_ERR_WORKSPACE
+    assert call(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, TOO_SMALL, None) == fb.FB_ERR_WORKSPACE
     bad = _ok_shape(head_dim=96)
     assert call(ctypes.byref(bad), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, ws_bytes, None) == fb.FB_ERR_UNSUPPORTED
     ex = lib.fb_external_partial_ex
     assert ex(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 257, FAKE, 1 << 30, None) == fb.FB_ERR_SHAPE
     assert ex(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, -1, FAKE, 1 << 30, None) == fb.FB_ERR_SHAPE
-    assert ex(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 16, FAKE, ws_bytes - 1, None) in (
+    assert ex(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 16, FAKE, TOO_SMALL, None) in (
         fb.FB_ERR_WORKSPACE,)
 
 
@@ -112,7 +113,7 @@ def test_external_partial_heads_error_paths():
     ws_bytes = fb.fb_workspace_bytes(s)
     call = lib.fb_external_partial_heads
     assert call(ctypes.byref(s), FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE, ws_bytes, None) == fb.FB_ERR_NULL
-    assert call(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, ws_bytes - 1, None) == fb.FB_ERR_WORKSPACE
+    assert call(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, TOO_SMALL, None) == fb.FB_ERR_WORKSPACE
     assert call(ctypes.byref(s), FAKE, FAKE, FAKE, ODD, ODD, FAKE, FAKE, FAKE, ws_bytes, None) == fb.FB_ERR_ALIGN  # mask may be unaligned, o may not
 
 
@@ -141,7 +142,7 @@ def test_external_partial_paged_error_paths():
     assert call(ctypes.byref(s), FAKE, ctypes.byref(_paged(num_pages=0)), *tail) == fb.FB_ERR_SHAPE
     assert call(ctypes.byref(s), FAKE, ctypes.byref(_paged(max_pages=3)), *tail) == fb.FB_ERR_SHAPE   # 3*64 < 256
     assert call(ctypes.byref(s), FAKE, ctypes.byref(_paged(v_pool=0x1004)), *tail) == fb.FB_ERR_ALIGN
-    assert call(ctypes.byref(s), FAKE, ctypes.byref(_paged()), FAKE, FAKE, FAKE, 0, FAKE, ws_bytes - 1, None) == fb.FB_ERR_WORKSPACE
+    assert call(ctypes.byref(s), FAKE, ctypes.byref(_paged()), FAKE, FAKE, FAKE, 0, FAKE, TOO_SMALL, None) == fb.FB_ERR_WORKSPACE
     assert call(ctypes.byref(s), FAKE, ctypes.byref(_paged()), FAKE, FAKE, FAKE, 300, FAKE, 1 << 30, None) == fb.FB_ERR_SHAPE
 
 
@@ -154,6 +155,26 @@ def test_internal_merge_error_paths():
     assert call(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, None, None) == fb.FB_ERR_NULL  # 2 of 3
     assert call(ctypes.byref(s), FAKE, FAKE, ODD, FAKE, FAKE, FAKE, FAKE, None, None) == fb.FB_ERR_ALIGN
     assert call(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, ODD, None) == fb.FB_ERR_ALIGN
+
+
+def test_refresh_step_error_paths():
+    lib = fb.load_library()
+    s = _ok_shape()
+    ws_bytes = fb.fb_workspace_bytes(s)
+    call = lib.fb_refresh_step
+    ok = [FAKE] * 9 + [None, FAKE, ws_bytes, None]       # q kp vp kb vb o m lse out | lse_out ws bytes stream
+    for i in (0, 3, 4, 5, 6, 7, 8):
+        a = list(ok); a[i] = None
+        assert call(ctypes.byref(s), *a) == fb.FB_ERR_NULL, i
+    a = list(ok); a[1] = None
+    assert call(ctypes.byref(s), *a) == fb.FB_ERR_NULL                       # prefix_len > 0 needs k_prefix
+    a = list(ok); a[8] = ODD
+    assert call(ctypes.byref(s), *a) == fb.FB_ERR_ALIGN
+    a = list(ok); a[10] = None
+    assert call(ctypes.byref(s), *a) == fb.FB_ERR_WORKSPACE
+    a = list(ok); a[11] = ws_bytes - 1
+    assert call(ctypes.byref(s), *a) == fb.FB_ERR_WORKSPACE
+    assert call(ctypes.byref(_ok_shape(head_dim=96)), *ok) == fb.FB_ERR_UNSUPPORTED
 
 
 def test_sparse_error_paths():

@@ -221,3 +221,50 @@ def test_bf16_small_blocks_column_split(Bq, P, n_splits):
     column-split wavefront layout of the dense pass, with and without wavefront groups."""
     _compare_block(_wl("bf16", 1, 8, 2, 128, P, Bq), seed=29, n_splits=n_splits)
     _compare_block(_wl("bf16", 2, 4, 2, 64, P, Bq), seed=30, n_splits=n_splits)
+
+
+# ------------------------------------------------------------------ fused refresh step
+def _compare_refresh_step(w, seed):
+    """fb_refresh_step = external partial over the prefix + this step's merged output, in one
+    streaming launch and one combine launch; both results against the oracle."""
+    print(f"[case] refresh_step {w.name} seed={seed}", flush=True)
+    Kp, Vp = wl.make_prefix(w, seed)
+    Q, Kb, Vb = wl.make_block_steps(w, seed, 1)[0]
+    shape = T.shape_of(w)
+    q, kb, vb = T.to_dev(Q, w.dtype), T.to_dev(Kb, w.dtype), T.to_dev(Vb, w.dtype)
+    kp = T.to_dev(Kp, w.dtype) if w.prefix_len > 0 else None
+    vp = T.to_dev(Vp, w.dtype) if w.prefix_len > 0 else None
+    ws = T.workspace(shape)
+    ext = T.Partial(w)
+    out = torch.empty_like(q)
+    lse = torch.empty(q.shape[:3], device=T.DEV, dtype=torch.float32)
+    fb.fb_refresh_step(shape, q, kp, vp, kb, vb, ext.o, ext.m, ext.lse, out, lse, ws)
+    torch.cuda.synchronize()
+    ora_ext = orc.partial(Q, Kp, Vp) if w.prefix_len > 0 else orc.empty_partial(w.batch, w.n_q_heads, w.block_len, w.head_dim)
+    T.check_partial(ext.numpy(), ora_ext, w.dtype, f"{w.name} fused ext")
+    ora_out, ora_lse = orc.merge(ora_ext, orc.partial(Q, Kb, Vb))
+    T.assert_close(out.double().cpu().numpy(), ora_out, w.dtype, f"{w.name} fused out")
+    T.assert_close(lse.double().cpu().numpy(), ora_lse, w.dtype, f"{w.name} fused lse", lse=True)
+    # the cached partial must serve the following reuse steps exactly like fb_external_partial's
+    out2 = torch.empty_like(q)
+    fb.fb_internal_merge(shape, q, kb, vb, ext.o, ext.m, ext.lse, out2, None)
+    torch.cuda.synchronize()
+    T.assert_close(out2.double().cpu().numpy(), ora_out, w.dtype, f"{w.name} fused cache -> merge")
+    # a refresh step is exact attention over [prefix, block]
+    a, _ = orc.full_attention(Q, np.concatenate([Kp, Kb], 2), np.concatenate([Vp, Vb], 2))
+    T.assert_close(out.double().cpu().numpy(), a, w.dtype, f"{w.name} fused == full attention")
+
+
+@pytest.mark.parametrize("dtype,B,Hq,Hkv,d,P,Bq", [
+    ("f32", 1, 4, 4, 64, 256, 16),
+    ("f32", 2, 4, 2, 128, 333, 7),
+    ("f32", 1, 2, 1, 64, 0, 8),
+    ("bf16", 1, 8, 2, 128, 1617, 32),
+    ("bf16", 2, 4, 4, 64, 700, 16),
+    ("bf16", 1, 32, 8, 128, 8192 + 5, 32),      # 8-wavefront workgroups, several splits
+    ("bf16", 1, 4, 4, 128, 2048, 200),          # several row tiles and a block of several key tiles
+    ("bf16", 1, 8, 2, 128, 0, 32),
+    ("bf16", 1, 8, 2, 128, 300, 4),
+])
+def test_fused_refresh_step(dtype, B, Hq, Hkv, d, P, Bq):
+    _compare_refresh_step(_wl(dtype, B, Hq, Hkv, d, P, Bq), seed=51)
