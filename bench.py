@@ -420,8 +420,7 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch every step eagerly instead of per-block HIP graphs")
     ap.add_argument("--fused", action="store_true",
                     help="refresh steps through fb_refresh_step (2 launches) instead of fb_external_partial + "
-                         "fb_internal_merge (3 launches); measured slower at the LLM shapes, where its 8 extra "
-                         "workgroups do not fit beside the 256 that already fill the CUs")
+                         "fb_internal_merge (3 launches); measured within 1-2 % of each other at the LLM shapes")
     ap.add_argument("--no-long", action="store_true", help="skip the 128K-context external-pass measurement")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-extras", action="store_true", help="skip the video-shaped (MFMA), sparse and paged measurements")

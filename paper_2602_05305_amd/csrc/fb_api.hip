@@ -3,6 +3,7 @@
 #include <math.h>
 #include <string.h>
 
+#include <algorithm>
 #include <string>
 
 #include "../../include/flashblock.h"
@@ -373,6 +374,12 @@ fb_status fb_refresh_step_prof(const fb_shape* shape, const void* q, const void*
   char* ws = (char*)workspace;
   fb::PassParams p = base_pass(shape, q, k_prefix, v_prefix, shape->prefix_len, ns);
   p.k2 = k_block; p.v2 = v_block;
+  {
+    // prefix tiles the block phase is worth (its cold load, LDS hand-over and epilogue), capped at half a split
+    const int tiles = (shape->prefix_len + fb::kKeyTile - 1) / fb::kKeyTile;
+    const int btiles = (shape->block_len + fb::kKeyTile - 1) / fb::kKeyTile;
+    p.blk_cost = ns > 1 ? std::min(2 + btiles, tiles / ns / 2) : 0;
+  }
   p.ws_o = (float*)(ws + w.o[0]); p.ws_m = (float*)(ws + w.m[0]); p.ws_l = (float*)(ws + w.l[0]);
   p.ws_o2 = (float*)(ws + w.o[1]); p.ws_m2 = (float*)(ws + w.m[1]); p.ws_l2 = (float*)(ws + w.l[1]);
   hipError_t e = hipSuccess;

@@ -341,13 +341,8 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
     if (p.seq_order != nullptr) b = p.seq_order[b];
   }
   const int bk = b * p.Hkv + kvh;
-  int nkeys = p.nkeys;
-  // fused refresh pass: the workgroups of split index nsplit take the block's own keys
-  const bool own_block = (MODE == kPassRefreshFused) && (split == p.nsplit);
-  if constexpr (MODE == kPassRefreshFused) {
-    if (own_block) nkeys = p.Bq;
-  }
-  if constexpr (MODE == kPassDensePaged) nkeys = min(p.nkeys, max(0, p.prefix_lens[b]));   // this sequence's prefix
+  int nkeys_pass = p.nkeys;
+  if constexpr (MODE == kPassDensePaged) nkeys_pass = min(p.nkeys, max(0, p.prefix_lens[b]));   // this sequence's prefix
 
   // WS wavefronts share one 32-row group and split the output columns between them (each repeats
   // the cheap score / softmax work): used when the pass has too few rows to fill the GPU, where
@@ -367,309 +362,330 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
     if (!__syncthreads_or(head_active ? 1 : 0)) return;
   }
 
-  const __bf16* __restrict__ Q = (const __bf16*)p.q;
-  // contiguous cache: this KV head's [nkeys, D] slab; paged cache: the pool (tiles add their page offset)
-  const __bf16* __restrict__ K = (const __bf16*)p.k + ((MODE == kPassDensePaged) ? (size_t)0 : (size_t)bk * nkeys * D);
-  const __bf16* __restrict__ V = (const __bf16*)p.v + ((MODE == kPassDensePaged) ? (size_t)0 : (size_t)bk * nkeys * D);
-  if constexpr (MODE == kPassRefreshFused) {
-    if (own_block) {
-      K = (const __bf16*)p.k2 + (size_t)bk * nkeys * D;
-      V = (const __bf16*)p.v2 + (size_t)bk * nkeys * D;
-    }
-  }
-
-  // tile list of this workgroup
-  int tpb = 1, total;
-  if constexpr (MODE == kPassSparseReuse) {
-    tpb = p.key_block / KT;
-    total = p.union_cnt[bk] * tpb;
-  } else {
-    total = (nkeys + KT - 1) / KT;
-  }
-  TileRange tr = split_range(total, p.nsplit, split);
-  if constexpr (MODE == kPassRefreshFused) {
-    if (own_block) tr = TileRange{0, total};
-  }
-  const uint32_t* __restrict__ bmask = p.blk_mask ? p.blk_mask + (size_t)bk * p.nblk : nullptr;
-  const int32_t* __restrict__ ulist = p.union_list ? p.union_list + (size_t)bk * p.nblk : nullptr;
-  const uint32_t my_bit = 1u << ((row_ok ? row : 0) / p.Bq);
-
-  auto entry_k0 = [&](int e, uint32_t& mask) -> int {
-    if constexpr (MODE == kPassSparseReuse) {
-      const int blk = ulist[e / tpb];
-      mask = bmask[blk];
-      return blk * p.key_block + KT * (e % tpb);
-    } else if constexpr (MODE == kPassSparseRefresh) {
-      mask = bmask[(e * KT) / p.key_block];
-      return e * KT;
-    } else if constexpr (MODE == kPassDensePaged) {
-      // descriptor word = page id, clamped into the pool
-      const uint32_t slot = fastdiv((uint32_t)(e * KT), p.div_page);
-      mask = (uint32_t)min(max(p.block_table[(size_t)b * p.max_pages + slot], 0), p.num_pages - 1);
-      return e * KT;
-    } else {
-      mask = 0xffffffffu;
-      return e * KT;
-    }
-  };
-
-  // The first tile's loads go out before anything else touches memory: the start of the kernel
-  // is a chain of cold latencies (instruction fetch, TLB, HBM), so the longest one starts first.
-  // Tiles are visited in a rotated order (start offset differs per workgroup): workgroups that
-  // run in lockstep would otherwise all read the same offset of their 2^k-strided chunks, i.e.
-  // the same HBM channels, at the same time.  The statistics do not depend on the tile order.
-  const int ntiles = tr.end - tr.begin;
-  const int rot = ntiles > 0 ? (int)((blockIdx.x * 13u + (blockIdx.x >> 5) * 7u) % (unsigned)ntiles) : 0;
-  auto tile_entry = [&](int i) -> int {   // i-th tile of this wavefront group
-    int j = TG * i + (kSetSplit ? 0 : grp) + rot;
-    if (j >= ntiles) j -= ntiles;
-    return tr.begin + j;
-  };
-  const int common = ntiles / TG;                 // tiles every group has
-  const bool extra = !kSetSplit && (ntiles % TG) > grp;   // this group has one more
-  TileRegs regs;
-  // Tile descriptors (first key, selection mask) are looked up two tiles ahead: in the list-driven
-  // sparse reuse pass they come from dependent scalar loads, whose latency would otherwise sit
-  // in front of every tile's global loads.
-  const int mine = common + (extra ? 1 : 0);
-  auto load_tile = [&](int k0, uint32_t aux) {
-    if constexpr (MODE == kPassDensePaged) {
-      // page `aux` holds keys [j * page_size, (j+1) * page_size) of this sequence; rebase so that key
-      // index k0 + r addresses row (k0 % page_size) + r of this KV head's slab of the page
-      const int in_page = k0 - (int)(fastdiv((uint32_t)k0, p.div_page) * p.div_page.d);
-      const long long off = (((long long)aux * p.Hkv + kvh) * p.page_size + in_page - k0) * D;
-      tile_load<D, KT, kSetSplit>(regs, K + off, V + off, k0, nkeys, tid, grp);
-    } else {
-      tile_load<D, KT, kSetSplit>(regs, K, V, k0, nkeys, tid, grp);
-    }
-  };
-  uint32_t mask_cur = 0, mask_next = 0, mask_nn = 0;
-  int k0_cur = 0, k0_next = 0, k0_nn = 0;
-  if (mine > 0) {
-    k0_cur = entry_k0(tile_entry(0), mask_cur);
-    load_tile(k0_cur, mask_cur);
-    if (mine > 1) k0_next = entry_k0(tile_entry(1), mask_next);
-  }
-
-  bf16x8 qreg[C::NKS];
-#pragma unroll
-  for (int ks = 0; ks < C::NKS; ++ks) {
-    // rows past the end load the group's last row instead (branch-free, in bounds); whatever
-    // they compute is never stored
-    const u32x4 u = gload128(Q + (row_ok ? grow : grow_last) * D + ks * 16 + 8 * h);
-    qreg[ks] = __builtin_bit_cast(bf16x8, u);
-  }
-
-  // Internal pass: the cached external partial is independent of everything computed here.  In
-  // the small (column-split) pass, which is a chain of memory latencies, its loads are issued up
-  // front and complete under the attention work; in the large pass, where registers decide how
-  // many wavefronts fit a SIMD, they are issued only in front of the epilogue.
-  constexpr int NEO = (MODE == kPassInternal) ? NDBL * 4 : 1;
-  constexpr bool kExtEarly = (WS > 1);
-  f32x4 eo[NEO];
-  float ext_m_v = -INFINITY, ext_lse_v = -INFINITY;
-  auto load_ext = [&]() {
-    typedef const __attribute__((address_space(1))) f32x4* gptr_f4;
-    typedef const __attribute__((address_space(1))) float* gptr_f;
-    const bool have = (p.ext_o != nullptr) && row_ok;
-#pragma unroll
-    for (int i = 0; i < NEO; ++i) eo[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-    if (have) {
-      ext_m_v = *((gptr_f)p.ext_m + grow);
-      ext_lse_v = *((gptr_f)p.ext_lse + grow);
-#pragma unroll
-      for (int db = 0; db < NDBL; ++db)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4)
-          eo[db * 4 + q4] = *(gptr_f4)(p.ext_o + grow * D + 32 * (db_base + db) + 8 * q4 + 4 * h);
-    }
-  };
-  if constexpr (MODE == kPassInternal && kExtEarly) load_ext();
-  WaveState<NDBL> sel;
-  sel.init();
-  WaveState<(MODE == kPassSparseRefresh && !kSetSplit) ? NDBL : 1> res;
-  res.init();
-
-  // Steady state per iteration: issue the global loads of tile i+1 (they stay in flight in
-  // registers), compute tile i from LDS, park tile i+1 in the other LDS stage, one barrier.
-  auto run_tile = [&](auto& st, const unsigned char* stage, bool on, int nvalid) {
-    tile_compute<D, KT, WS>(st, qreg, stage, p.scale_log2, on, nvalid, l32, h, db_base);
-  };
-  auto compute = [&](const unsigned char* stage, int k0, uint32_t mask) {
-    const int nvalid = min(C::KT, nkeys - k0);      // <= 0 only for a reuse-list tile past the end
-    if constexpr (MODE == kPassSparseReuse) {
-      if (nvalid <= 0) return;
-    }
-    if constexpr (kSetSplit) {
-      const bool on = row_ok && (((mask & my_bit) != 0u) == (grp == 0));
-      if (__any(on)) run_tile(sel, stage, on, nvalid);
-    } else if constexpr (MODE == kPassSparseRefresh) {
-      const bool on = row_ok && (mask & my_bit);
-      if (__any(on)) run_tile(sel, stage, on, nvalid);
-      const bool off = row_ok && !(mask & my_bit);
-      if (__any(off)) run_tile(res, stage, off, nvalid);
-    } else if constexpr (MODE == kPassSparseReuse) {
-      const bool on = row_ok && (mask & my_bit);
-      if (__any(on)) run_tile(sel, stage, on, nvalid);
-    } else if constexpr (MODE == kPassDenseHeads) {
-      if (__any(head_active)) run_tile(sel, stage, head_active, nvalid);
-    } else {
-      run_tile(sel, stage, true, nvalid);
-    }
-  };
-
-  if (ntiles > 0) {
-    if (common > 0 || extra) tile_store<D, KT, kSetSplit>(regs, smem, tid, grp);
-    __syncthreads();
-    for (int i = 0; i < common - 1; ++i) {       // steady state: one barrier per tile
-      if (i + 2 < mine) k0_nn = entry_k0(tile_entry(i + 2), mask_nn);
-      load_tile(k0_next, mask_next);
-      compute(smem + (i & 1) * C::STAGE, k0_cur, mask_cur);
-      tile_store<D, KT, kSetSplit>(regs, smem + ((i + 1) & 1) * C::STAGE, tid, grp);
-      __syncthreads();
-      k0_cur = k0_next;
-      mask_cur = mask_next;
-      k0_next = k0_nn;
-      mask_next = mask_nn;
-    }
-    if (common > 0) {
-      const int i = common - 1;
-      if (extra) load_tile(k0_next, mask_next);
-      compute(smem + (i & 1) * C::STAGE, k0_cur, mask_cur);
-      if (TG > 1 && (ntiles % TG) != 0) {         // some group has one more tile (workgroup-uniform)
-        if (extra) tile_store<D, KT, kSetSplit>(regs, smem + ((i + 1) & 1) * C::STAGE, tid, grp);
-        __syncthreads();
-        if (extra) compute(smem + ((i + 1) & 1) * C::STAGE, k0_next, mask_next);
+  // One pass over a key range with fresh statistics, from the first tile load to the result's store.
+  // Every mode runs it once, except the fused refresh pass, where the workgroup of the last prefix
+  // split runs it a second time over the block's own keys (partial set 1).
+  constexpr bool kFused = (MODE == kPassRefreshFused);
+  auto run_pass = [&](const bool own_block) __attribute__((always_inline)) {
+    const int nkeys = own_block ? p.Bq : nkeys_pass;
+    const __bf16* __restrict__ Q = (const __bf16*)p.q;
+    // contiguous cache: this KV head's [nkeys, D] slab; paged cache: the pool (tiles add their page offset)
+    const __bf16* __restrict__ K = (const __bf16*)p.k + ((MODE == kPassDensePaged) ? (size_t)0 : (size_t)bk * nkeys * D);
+    const __bf16* __restrict__ V = (const __bf16*)p.v + ((MODE == kPassDensePaged) ? (size_t)0 : (size_t)bk * nkeys * D);
+    if constexpr (kFused) {
+      if (own_block) {
+        K = (const __bf16*)p.k2 + (size_t)bk * nkeys * D;
+        V = (const __bf16*)p.v2 + (size_t)bk * nkeys * D;
       }
-    } else if (extra) {
-      compute(smem, k0_cur, mask_cur);
     }
-  }
-  if constexpr (TG > 1) {
-    // hand group 1's statistics to group 0: [wave][register][lane] floats in the (now idle) LDS
-    constexpr int REC = NDBL * 16 + 2;
-    float* mbuf = (float*)smem_all + (size_t)wave * REC * 64 + lane;
-    __syncthreads();
-    if (grp == 1) {
-#pragma unroll
-      for (int db = 0; db < NDBL; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) mbuf[(db * 16 + r) * 64] = sel.o[db][r];
-      mbuf[(NDBL * 16) * 64] = sel.m;
-      mbuf[(NDBL * 16 + 1) * 64] = sel.l;
+
+    // tile list of this workgroup
+    int tpb = 1, total;
+    if constexpr (MODE == kPassSparseReuse) {
+      tpb = p.key_block / KT;
+      total = p.union_cnt[bk] * tpb;
+    } else {
+      total = (nkeys + KT - 1) / KT;
     }
-    __syncthreads();
-    if (grp == 1) return;
-    const float m1 = mbuf[(NDBL * 16) * 64], l1 = mbuf[(NDBL * 16 + 1) * 64];
-    const float M = fmaxf(sel.m, m1);
-    const float Mu = (M == -INFINITY) ? 0.f : M;
-    const float w0 = __builtin_amdgcn_exp2f(sel.m - Mu), w1 = __builtin_amdgcn_exp2f(m1 - Mu);
-#pragma unroll
-    for (int db = 0; db < NDBL; ++db)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) sel.o[db][r] = sel.o[db][r] * w0 + mbuf[(db * 16 + r) * 64] * w1;
-    sel.l = sel.l * w0 + l1 * w1;
-    sel.m = M;
-  }
-  // ---------------------------------------------------------------- epilogue
-  const float l_sel = sel.l + __shfl_xor(sel.l, 32, 64);
-  if constexpr (MODE == kPassInternal) {
-    if constexpr (!kExtEarly) load_ext();
-    if (!row_ok) return;
-    float me2 = -INFINITY, le = 0.f;
-    if (ext_lse_v != -INFINITY) {
-      me2 = ext_m_v * kLog2e;
-      le = exp2f((ext_lse_v - ext_m_v) * kLog2e);
-    }
-    // Eq. 8-9 with the cached pair expressed through (o, m, lse): A_out e^{L_out-M} = o e^{m-M}
-    const float M2 = fmaxf(me2, sel.m);
-    const float Mu = (M2 == -INFINITY) ? 0.f : M2;
-    const float we = exp2f(me2 - Mu), wi = exp2f(sel.m - Mu);
-    const float den = le * we + l_sel * wi;
-    const float inv = den > 0.f ? 1.f / den : 0.f;
-    __bf16* out = (__bf16*)p.out + grow * D;
-#pragma unroll
-    for (int db = 0; db < NDBL; ++db)
-#pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        const int d0 = 32 * (db_base + db) + 8 * q4 + 4 * h;
-        const f32x4 e = eo[(MODE == kPassInternal) ? db * 4 + q4 : 0];   // o of an empty partial is 0 by contract
-        float r[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) r[i] = (sel.o[db][4 * q4 + i] * wi + e[i] * we) * inv;
-        u32x2 pk;
-        pk.x = pack_bf16x2(r[0], r[1]);
-        pk.y = pack_bf16x2(r[2], r[3]);
-        *(u32x2*)(out + d0) = pk;
+    TileRange tr = split_range(total, p.nsplit, split);
+    if constexpr (kFused) {
+      if (own_block) {
+        tr = TileRange{0, total};
+      } else {
+        // the last split's workgroup also runs the block phase: it gets blk_cost tiles fewer
+        tr = split_range(total + p.blk_cost, p.nsplit, split);
+        tr.begin = min(tr.begin, total);
+        tr.end = min(tr.end, total);
       }
-    if (p.lse_out != nullptr && h == 0 && db_base == 0) p.lse_out[grow] = den > 0.f ? (M2 + log2f(den)) * kLn2 : -INFINITY;
-  } else {
-    if constexpr (MODE == kPassDense || MODE == kPassDenseHeads || MODE == kPassDensePaged) {
-      if (p.direct) {
-        // single split: this is the final partial.  Same conversion as the split combine: m is
-        // rounded when converted to natural-log units, o is rescaled to the reference consumers
-        // recover from it.
-        if (!(row_ok && head_active)) return;
-        float m_nat = -INFINITY, L = -INFINITY, adj = 0.f;
-        if (l_sel > 0.f) {
-          m_nat = sel.m * kLn2;
-          adj = exp2f(sel.m - m_nat * kLog2e);
-          L = (sel.m + log2f(l_sel)) * kLn2;
-        }
+    }
+    const uint32_t* __restrict__ bmask = p.blk_mask ? p.blk_mask + (size_t)bk * p.nblk : nullptr;
+    const int32_t* __restrict__ ulist = p.union_list ? p.union_list + (size_t)bk * p.nblk : nullptr;
+    const uint32_t my_bit = 1u << ((row_ok ? row : 0) / p.Bq);
+
+    auto entry_k0 = [&](int e, uint32_t& mask) -> int {
+      if constexpr (MODE == kPassSparseReuse) {
+        const int blk = ulist[e / tpb];
+        mask = bmask[blk];
+        return blk * p.key_block + KT * (e % tpb);
+      } else if constexpr (MODE == kPassSparseRefresh) {
+        mask = bmask[(e * KT) / p.key_block];
+        return e * KT;
+      } else if constexpr (MODE == kPassDensePaged) {
+        // descriptor word = page id, clamped into the pool
+        const uint32_t slot = fastdiv((uint32_t)(e * KT), p.div_page);
+        mask = (uint32_t)min(max(p.block_table[(size_t)b * p.max_pages + slot], 0), p.num_pages - 1);
+        return e * KT;
+      } else {
+        mask = 0xffffffffu;
+        return e * KT;
+      }
+    };
+
+    // The first tile's loads go out before anything else touches memory: the start of the kernel
+    // is a chain of cold latencies (instruction fetch, TLB, HBM), so the longest one starts first.
+    // Tiles are visited in a rotated order (start offset differs per workgroup): workgroups that
+    // run in lockstep would otherwise all read the same offset of their 2^k-strided chunks, i.e.
+    // the same HBM channels, at the same time.  The statistics do not depend on the tile order.
+    const int ntiles = tr.end - tr.begin;
+    const int rot = ntiles > 0 ? (int)((blockIdx.x * 13u + (blockIdx.x >> 5) * 7u) % (unsigned)ntiles) : 0;
+    auto tile_entry = [&](int i) -> int {   // i-th tile of this wavefront group
+      int j = TG * i + (kSetSplit ? 0 : grp) + rot;
+      if (j >= ntiles) j -= ntiles;
+      return tr.begin + j;
+    };
+    const int common = ntiles / TG;                 // tiles every group has
+    const bool extra = !kSetSplit && (ntiles % TG) > grp;   // this group has one more
+    TileRegs regs;
+    // Tile descriptors (first key, selection mask) are looked up two tiles ahead: in the list-driven
+    // sparse reuse pass they come from dependent scalar loads, whose latency would otherwise sit
+    // in front of every tile's global loads.
+    const int mine = common + (extra ? 1 : 0);
+    auto load_tile = [&](int k0, uint32_t aux) {
+      if constexpr (MODE == kPassDensePaged) {
+        // page `aux` holds keys [j * page_size, (j+1) * page_size) of this sequence; rebase so that key
+        // index k0 + r addresses row (k0 % page_size) + r of this KV head's slab of the page
+        const int in_page = k0 - (int)(fastdiv((uint32_t)k0, p.div_page) * p.div_page.d);
+        const long long off = (((long long)aux * p.Hkv + kvh) * p.page_size + in_page - k0) * D;
+        tile_load<D, KT, kSetSplit>(regs, K + off, V + off, k0, nkeys, tid, grp);
+      } else {
+        tile_load<D, KT, kSetSplit>(regs, K, V, k0, nkeys, tid, grp);
+      }
+    };
+    uint32_t mask_cur = 0, mask_next = 0, mask_nn = 0;
+    int k0_cur = 0, k0_next = 0, k0_nn = 0;
+    if (mine > 0) {
+      k0_cur = entry_k0(tile_entry(0), mask_cur);
+      load_tile(k0_cur, mask_cur);
+      if (mine > 1) k0_next = entry_k0(tile_entry(1), mask_next);
+    }
+
+    bf16x8 qreg[C::NKS];
+#pragma unroll
+    for (int ks = 0; ks < C::NKS; ++ks) {
+      // rows past the end load the group's last row instead (branch-free, in bounds); whatever
+      // they compute is never stored
+      const u32x4 u = gload128(Q + (row_ok ? grow : grow_last) * D + ks * 16 + 8 * h);
+      qreg[ks] = __builtin_bit_cast(bf16x8, u);
+    }
+
+    // Internal pass: the cached external partial is independent of everything computed here.  In
+    // the small (column-split) pass, which is a chain of memory latencies, its loads are issued up
+    // front and complete under the attention work; in the large pass, where registers decide how
+    // many wavefronts fit a SIMD, they are issued only in front of the epilogue.
+    constexpr int NEO = (MODE == kPassInternal) ? NDBL * 4 : 1;
+    constexpr bool kExtEarly = (WS > 1);
+    f32x4 eo[NEO];
+    float ext_m_v = -INFINITY, ext_lse_v = -INFINITY;
+    auto load_ext = [&]() {
+      typedef const __attribute__((address_space(1))) f32x4* gptr_f4;
+      typedef const __attribute__((address_space(1))) float* gptr_f;
+      const bool have = (p.ext_o != nullptr) && row_ok;
+#pragma unroll
+      for (int i = 0; i < NEO; ++i) eo[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (have) {
+        ext_m_v = *((gptr_f)p.ext_m + grow);
+        ext_lse_v = *((gptr_f)p.ext_lse + grow);
 #pragma unroll
         for (int db = 0; db < NDBL; ++db)
 #pragma unroll
-          for (int q4 = 0; q4 < 4; ++q4) {
-            const int d0 = 32 * (db_base + db) + 8 * q4 + 4 * h;
-            f32x4 o4 = {sel.o[db][4 * q4] * adj, sel.o[db][4 * q4 + 1] * adj, sel.o[db][4 * q4 + 2] * adj,
-                        sel.o[db][4 * q4 + 3] * adj};
-            *(f32x4*)(p.ws_o + grow * D + d0) = o4;
-          }
-        if (h == 0 && db_base == 0) {
-          p.ws_m[grow] = m_nat;
-          p.ws_l[grow] = L;
+          for (int q4 = 0; q4 < 4; ++q4)
+            eo[db * 4 + q4] = *(gptr_f4)(p.ext_o + grow * D + 32 * (db_base + db) + 8 * q4 + 4 * h);
+      }
+    };
+    if constexpr (MODE == kPassInternal && kExtEarly) load_ext();
+    WaveState<NDBL> sel;
+    sel.init();
+    WaveState<(MODE == kPassSparseRefresh && !kSetSplit) ? NDBL : 1> res;
+    res.init();
+
+    // Steady state per iteration: issue the global loads of tile i+1 (they stay in flight in
+    // registers), compute tile i from LDS, park tile i+1 in the other LDS stage, one barrier.
+    auto run_tile = [&](auto& st, const unsigned char* stage, bool on, int nvalid) {
+      tile_compute<D, KT, WS>(st, qreg, stage, p.scale_log2, on, nvalid, l32, h, db_base);
+    };
+    auto compute = [&](const unsigned char* stage, int k0, uint32_t mask) {
+      const int nvalid = min(C::KT, nkeys - k0);      // <= 0 only for a reuse-list tile past the end
+      if constexpr (MODE == kPassSparseReuse) {
+        if (nvalid <= 0) return;
+      }
+      if constexpr (kSetSplit) {
+        const bool on = row_ok && (((mask & my_bit) != 0u) == (grp == 0));
+        if (__any(on)) run_tile(sel, stage, on, nvalid);
+      } else if constexpr (MODE == kPassSparseRefresh) {
+        const bool on = row_ok && (mask & my_bit);
+        if (__any(on)) run_tile(sel, stage, on, nvalid);
+        const bool off = row_ok && !(mask & my_bit);
+        if (__any(off)) run_tile(res, stage, off, nvalid);
+      } else if constexpr (MODE == kPassSparseReuse) {
+        const bool on = row_ok && (mask & my_bit);
+        if (__any(on)) run_tile(sel, stage, on, nvalid);
+      } else if constexpr (MODE == kPassDenseHeads) {
+        if (__any(head_active)) run_tile(sel, stage, head_active, nvalid);
+      } else {
+        run_tile(sel, stage, true, nvalid);
+      }
+    };
+
+    if (ntiles > 0) {
+      if (common > 0 || extra) tile_store<D, KT, kSetSplit>(regs, smem, tid, grp);
+      __syncthreads();
+      for (int i = 0; i < common - 1; ++i) {       // steady state: one barrier per tile
+        if (i + 2 < mine) k0_nn = entry_k0(tile_entry(i + 2), mask_nn);
+        load_tile(k0_next, mask_next);
+        compute(smem + (i & 1) * C::STAGE, k0_cur, mask_cur);
+        tile_store<D, KT, kSetSplit>(regs, smem + ((i + 1) & 1) * C::STAGE, tid, grp);
+        __syncthreads();
+        k0_cur = k0_next;
+        mask_cur = mask_next;
+        k0_next = k0_nn;
+        mask_next = mask_nn;
+      }
+      if (common > 0) {
+        const int i = common - 1;
+        if (extra) load_tile(k0_next, mask_next);
+        compute(smem + (i & 1) * C::STAGE, k0_cur, mask_cur);
+        if (TG > 1 && (ntiles % TG) != 0) {         // some group has one more tile (workgroup-uniform)
+          if (extra) tile_store<D, KT, kSetSplit>(regs, smem + ((i + 1) & 1) * C::STAGE, tid, grp);
+          __syncthreads();
+          if (extra) compute(smem + ((i + 1) & 1) * C::STAGE, k0_next, mask_next);
         }
-        return;
+      } else if (extra) {
+        compute(smem, k0_cur, mask_cur);
       }
     }
-    const size_t rows_total = (size_t)p.B * p.Hq * p.Bq;
-    const size_t wrow = (own_block ? (size_t)0 : (size_t)split * rows_total) + grow;
-    const bool set1 = (kSetSplit && grp == 1) || own_block;
-    float* __restrict__ w_o = set1 ? p.ws_o2 : p.ws_o;
-    float* __restrict__ w_m = set1 ? p.ws_m2 : p.ws_m;
-    float* __restrict__ w_l = set1 ? p.ws_l2 : p.ws_l;
-    if (row_ok) {
+    if constexpr (TG > 1) {
+      // hand group 1's statistics to group 0: [wave][register][lane] floats in the (now idle) LDS
+      constexpr int REC = NDBL * 16 + 2;
+      float* mbuf = (float*)smem_all + (size_t)wave * REC * 64 + lane;
+      __syncthreads();
+      if (grp == 1) {
+#pragma unroll
+        for (int db = 0; db < NDBL; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) mbuf[(db * 16 + r) * 64] = sel.o[db][r];
+        mbuf[(NDBL * 16) * 64] = sel.m;
+        mbuf[(NDBL * 16 + 1) * 64] = sel.l;
+      }
+      __syncthreads();
+      if (grp == 1) return;
+      const float m1 = mbuf[(NDBL * 16) * 64], l1 = mbuf[(NDBL * 16 + 1) * 64];
+      const float M = fmaxf(sel.m, m1);
+      const float Mu = (M == -INFINITY) ? 0.f : M;
+      const float w0 = __builtin_amdgcn_exp2f(sel.m - Mu), w1 = __builtin_amdgcn_exp2f(m1 - Mu);
+#pragma unroll
+      for (int db = 0; db < NDBL; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sel.o[db][r] = sel.o[db][r] * w0 + mbuf[(db * 16 + r) * 64] * w1;
+      sel.l = sel.l * w0 + l1 * w1;
+      sel.m = M;
+    }
+    // ---------------------------------------------------------------- epilogue
+    const float l_sel = sel.l + __shfl_xor(sel.l, 32, 64);
+    if constexpr (MODE == kPassInternal) {
+      if constexpr (!kExtEarly) load_ext();
+      if (!row_ok) return;
+      float me2 = -INFINITY, le = 0.f;
+      if (ext_lse_v != -INFINITY) {
+        me2 = ext_m_v * kLog2e;
+        le = exp2f((ext_lse_v - ext_m_v) * kLog2e);
+      }
+      // Eq. 8-9 with the cached pair expressed through (o, m, lse): A_out e^{L_out-M} = o e^{m-M}
+      const float M2 = fmaxf(me2, sel.m);
+      const float Mu = (M2 == -INFINITY) ? 0.f : M2;
+      const float we = exp2f(me2 - Mu), wi = exp2f(sel.m - Mu);
+      const float den = le * we + l_sel * wi;
+      const float inv = den > 0.f ? 1.f / den : 0.f;
+      __bf16* out = (__bf16*)p.out + grow * D;
 #pragma unroll
       for (int db = 0; db < NDBL; ++db)
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
           const int d0 = 32 * (db_base + db) + 8 * q4 + 4 * h;
-          f32x4 o4 = {sel.o[db][4 * q4], sel.o[db][4 * q4 + 1], sel.o[db][4 * q4 + 2], sel.o[db][4 * q4 + 3]};
-          // streaming store: the partials are read next by another kernel, never again by this
-          // one; written through, they do not pile up as dirty L2 lines to flush at kernel end
-          __builtin_nontemporal_store(o4, (f32x4*)(w_o + wrow * D + d0));
+          const f32x4 e = eo[(MODE == kPassInternal) ? db * 4 + q4 : 0];   // o of an empty partial is 0 by contract
+          float r[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) r[i] = (sel.o[db][4 * q4 + i] * wi + e[i] * we) * inv;
+          u32x2 pk;
+          pk.x = pack_bf16x2(r[0], r[1]);
+          pk.y = pack_bf16x2(r[2], r[3]);
+          *(u32x2*)(out + d0) = pk;
         }
-      if (h == 0 && db_base == 0) {
-        w_m[wrow] = sel.m;
-        w_l[wrow] = l_sel;
+      if (p.lse_out != nullptr && h == 0 && db_base == 0) p.lse_out[grow] = den > 0.f ? (M2 + log2f(den)) * kLn2 : -INFINITY;
+    } else {
+      if constexpr (MODE == kPassDense || MODE == kPassDenseHeads || MODE == kPassDensePaged) {
+        if (p.direct) {
+          // single split: this is the final partial.  Same conversion as the split combine: m is
+          // rounded when converted to natural-log units, o is rescaled to the reference consumers
+          // recover from it.
+          if (!(row_ok && head_active)) return;
+          float m_nat = -INFINITY, L = -INFINITY, adj = 0.f;
+          if (l_sel > 0.f) {
+            m_nat = sel.m * kLn2;
+            adj = exp2f(sel.m - m_nat * kLog2e);
+            L = (sel.m + log2f(l_sel)) * kLn2;
+          }
+#pragma unroll
+          for (int db = 0; db < NDBL; ++db)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+              const int d0 = 32 * (db_base + db) + 8 * q4 + 4 * h;
+              f32x4 o4 = {sel.o[db][4 * q4] * adj, sel.o[db][4 * q4 + 1] * adj, sel.o[db][4 * q4 + 2] * adj,
+                          sel.o[db][4 * q4 + 3] * adj};
+              *(f32x4*)(p.ws_o + grow * D + d0) = o4;
+            }
+          if (h == 0 && db_base == 0) {
+            p.ws_m[grow] = m_nat;
+            p.ws_l[grow] = L;
+          }
+          return;
+        }
       }
-    }
-    if constexpr (MODE == kPassSparseRefresh && !kSetSplit) {
-      const float l_res = res.l + __shfl_xor(res.l, 32, 64);
+      const size_t rows_total = (size_t)p.B * p.Hq * p.Bq;
+      const size_t wrow = (own_block ? (size_t)0 : (size_t)split * rows_total) + grow;
+      const bool set1 = (kSetSplit && grp == 1) || own_block;
+      float* __restrict__ w_o = set1 ? p.ws_o2 : p.ws_o;
+      float* __restrict__ w_m = set1 ? p.ws_m2 : p.ws_m;
+      float* __restrict__ w_l = set1 ? p.ws_l2 : p.ws_l;
       if (row_ok) {
 #pragma unroll
         for (int db = 0; db < NDBL; ++db)
 #pragma unroll
           for (int q4 = 0; q4 < 4; ++q4) {
             const int d0 = 32 * (db_base + db) + 8 * q4 + 4 * h;
-            f32x4 o4 = {res.o[db][4 * q4], res.o[db][4 * q4 + 1], res.o[db][4 * q4 + 2], res.o[db][4 * q4 + 3]};
-            *(f32x4*)(p.ws_o2 + wrow * D + d0) = o4;
+            f32x4 o4 = {sel.o[db][4 * q4], sel.o[db][4 * q4 + 1], sel.o[db][4 * q4 + 2], sel.o[db][4 * q4 + 3]};
+            // streaming store: the partials are read next by another kernel, never again by this
+            // one; written through, they do not pile up as dirty L2 lines to flush at kernel end
+            __builtin_nontemporal_store(o4, (f32x4*)(w_o + wrow * D + d0));
           }
         if (h == 0 && db_base == 0) {
-          p.ws_m2[wrow] = res.m;
-          p.ws_l2[wrow] = l_res;
+          w_m[wrow] = sel.m;
+          w_l[wrow] = l_sel;
         }
       }
+      if constexpr (MODE == kPassSparseRefresh && !kSetSplit) {
+        const float l_res = res.l + __shfl_xor(res.l, 32, 64);
+        if (row_ok) {
+#pragma unroll
+          for (int db = 0; db < NDBL; ++db)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+              const int d0 = 32 * (db_base + db) + 8 * q4 + 4 * h;
+              f32x4 o4 = {res.o[db][4 * q4], res.o[db][4 * q4 + 1], res.o[db][4 * q4 + 2], res.o[db][4 * q4 + 3]};
+              *(f32x4*)(p.ws_o2 + wrow * D + d0) = o4;
+            }
+          if (h == 0 && db_base == 0) {
+            p.ws_m2[wrow] = res.m;
+            p.ws_l2[wrow] = l_res;
+          }
+        }
+      }
+    }
+  };
+  run_pass(false);
+  if constexpr (kFused) {
+    if (split == p.nsplit - 1) {   // workgroup-uniform
+      __syncthreads();             // group 0 has read group 1's statistics out of LDS
+      run_pass(true);
     }
   }
 }
@@ -687,14 +703,13 @@ hipError_t launch_one(const PassParams& p, hipStream_t s) {
   constexpr int rows_per_wg = kRowsPerWgBf16 / WS;
   const int nrows = p.G * p.Bq;
   const int ntile_rows = (nrows + rows_per_wg - 1) / rows_per_wg;
-  const int nunits = p.nsplit + (MODE == kPassRefreshFused ? 1 : 0);   // split indices per (batch, KV head)
-  long long nwg = (long long)p.B * p.Hkv * ntile_rows * nunits;
+  long long nwg = (long long)p.B * p.Hkv * ntile_rows * p.nsplit;
   if (MODE == kPassDensePaged) nwg = (((long long)p.B * p.Hkv * p.nsplit + 7) / 8) * 8 * ntile_rows;
   if (nwg >= (1ll << 31)) return hipErrorInvalidValue;
   PassParams q = p;
   if (MODE == kPassDensePaged) q.div_page = make_fastdiv((uint32_t)p.page_size);
   q.div_rowtiles = make_fastdiv((uint32_t)ntile_rows);
-  q.div_nsplit = make_fastdiv((uint32_t)nunits);
+  q.div_nsplit = make_fastdiv((uint32_t)p.nsplit);
   q.div_hkv = make_fastdiv((uint32_t)p.Hkv);
   hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(256 * NG), lds, s, q);
   return hipGetLastError();

@@ -73,8 +73,9 @@ struct PassParams {
   const int32_t* prefix_lens; // [B] keys per sequence (<= nkeys)
   int page_size, max_pages, num_pages;
   const int32_t* seq_order;   // [B] sequences by descending prefix length (longest work is dispatched first), or null
-  // fused refresh pass: split index nsplit streams the block's own K/V [B,Hkv,Bq,D] into partial set 1
-  const void* k2; const void* v2;
+  // fused refresh pass: the block's own K/V [B,Hkv,Bq,D] go into partial set 1 (bf16: second phase of the last
+  // split's workgroup, which gets blk_cost prefix tiles fewer; fp32: one extra split index)
+  const void* k2; const void* v2; int blk_cost;
   // dense / heads / paged pass with nsplit == 1: ws_o / ws_m / ws_l are the caller's final (o, m, lse)
   // arrays and the kernel emits natural-log units itself (no combine pass)
   int direct;
