@@ -258,6 +258,38 @@ def select_topk(Q, K, key_block, topk):
     return idx
 
 
+def block_mass(Q, K, key_block, scale=None):
+    """Attention mass per key block at a step that computes full attention over the prefix (the
+    step the sparse mask is derived from, Appendix "Adapting SparseD to Block dLLM"): with
+    p_ij = softmax_j(s_ij) over all prefix keys (Eq. 1-2 restricted to J_out), the mass of block c
+    for query head h is the mean over the block's query rows i of sum_{j in c} p_ij.
+    [B,Hq,nblk]; every (b, h) row sums to 1."""
+    S = scores(Q, K, scale)                                   # [B,Hq,Bq,P]
+    P = S.shape[-1]
+    nblk = -(-P // key_block)
+    mx = S.max(axis=-1, keepdims=True)
+    e = np.exp(S - mx)
+    prob = e / e.sum(axis=-1, keepdims=True)
+    mass = np.zeros(S.shape[:2] + (nblk,))
+    for c in range(nblk):
+        mass[:, :, c] = prob[..., c * key_block:min(P, (c + 1) * key_block)].sum(axis=-1).mean(axis=-1)
+    return mass
+
+
+def select_topk_scores(sc, topk):
+    """Top-k key blocks per (batch, query head) of given block scores [B,Hq,nblk]: ascending
+    indices, ties to the lower block index, topk clamped to nblk.  int32 [B,Hq,min(topk,nblk)]."""
+    sc = np.asarray(sc, dtype=np.float64)
+    B, Hq, nblk = sc.shape
+    k = min(int(topk), nblk)
+    idx = np.empty((B, Hq, k), dtype=np.int32)
+    for b in range(B):
+        for h in range(Hq):
+            order = sorted(range(nblk), key=lambda c: (-sc[b, h, c], c))
+            idx[b, h] = np.array(sorted(order[:k]), dtype=np.int32)
+    return idx
+
+
 def selection_key_mask(idx, P, key_block):
     """bool [B,Hq,P]: True for prefix keys inside a selected key block."""
     B, Hq, k = idx.shape

@@ -108,11 +108,38 @@ def _selection_mask_off_by_one(idx, P, key_block):               # selected bloc
     return np.roll(m, 1, axis=-1)
 
 
+def _block_mass_unnormalised(Q, K, key_block, scale=None):       # weights against the row maximum, not the row sum
+    S = orc.scores(Q, K, scale)
+    e = np.exp(S - S.max(axis=-1, keepdims=True))
+    nblk = -(-S.shape[-1] // key_block)
+    return np.stack([e[..., c * key_block:(c + 1) * key_block].sum(-1).mean(-1) for c in range(nblk)], axis=-1)
+
+
+def _block_mass_wrong_kv_head(Q, K, key_block, scale=None):      # head h reads KV head h % Hkv
+    Q, K = np.asarray(Q), np.asarray(K)
+    Hq, Hkv = Q.shape[1], K.shape[1]
+    out = [_ORIG["block_mass"](Q[:, h:h + 1], K[:, (h % Hkv):(h % Hkv) + 1], key_block, scale) for h in range(Hq)]
+    return np.concatenate(out, axis=1)
+
+
+def _select_topk_scores_ties_high(sc, topk):                     # ties go to the higher index
+    sc = np.asarray(sc, dtype=np.float64)
+    B, Hq, nblk = sc.shape
+    k = min(int(topk), nblk)
+    idx = np.empty((B, Hq, k), dtype=np.int32)
+    for b in range(B):
+        for h in range(Hq):
+            order = sorted(range(nblk), key=lambda c: (-sc[b, h, c], -c))
+            idx[b, h] = np.array(sorted(order[:k]), dtype=np.int32)
+    return idx
+
+
 def _cache_bytes_fp32_a(n_layers, n_heads, block_rows, head_dim, batch=1, a_bytes=4, l_bytes=4):
     return _ORIG["cache_bytes_paper_layout"](n_layers, n_heads, block_rows, head_dim, batch, a_bytes, l_bytes)
 
 
-_ORIG = {n: getattr(orc, n) for n in ("partial", "run_block_dense", "selection_key_mask", "cache_bytes_paper_layout")}
+_ORIG = {n: getattr(orc, n) for n in ("partial", "run_block_dense", "selection_key_mask", "cache_bytes_paper_layout",
+                                      "block_mass")}
 
 MUTATIONS = [
     ("default_scale", _wrong_scale, pins.test_hand_case_scale_and_weights),
@@ -129,6 +156,10 @@ MUTATIONS = [
     ("selection_key_mask", _selection_mask_off_by_one, pins.test_selection_key_mask_hand_example),
     ("selection_key_mask", _selection_mask_off_by_one, pins.test_sparse_reuse_equals_augmented_sdpa),
     ("cache_bytes_paper_layout", _cache_bytes_fp32_a, pins.test_cache_bytes_match_table5),
+    ("block_mass", _block_mass_unnormalised, pins.test_block_mass_closed_forms),
+    ("block_mass", _block_mass_wrong_kv_head, pins.test_block_mass_closed_forms),
+    ("block_mass", _block_mass_wrong_kv_head, pins.test_block_mass_matches_library_softmax_and_sums_to_one),
+    ("select_topk_scores", _select_topk_scores_ties_high, pins.test_select_topk_scores_hand_and_bruteforce),
 ]
 
 

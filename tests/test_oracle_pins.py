@@ -288,6 +288,49 @@ def test_topk_ties_go_to_lower_index_and_bruteforce():
             assert idx[b, h].tolist() == sorted(np.argsort(-np.array(sc), kind="stable")[:5].tolist())
 
 
+def test_block_mass_closed_forms():
+    """Attention mass per key block.  (1) All-zero keys: uniform weights, mass = block size / P,
+    short last block included.  (2) d = 1 hand case: q = ln 2, keys (0, 1 | 1, 2): weights
+    proportional to 1, 2, 2, 4, so the two blocks of two hold 3/9 and 6/9 (scale 1).  (3) One key far
+    above the rest takes (almost) all the mass of its block, for every head that reads it (GQA)."""
+    Q = np.random.default_rng(1).standard_normal((2, 4, 3, 8))
+    m = orc.block_mass(Q, np.zeros((2, 2, 7, 8)), 3)
+    assert m.shape == (2, 4, 3) and np.allclose(m, np.array([3, 3, 1]) / 7.0)
+    q = np.full((1, 1, 2, 1), np.log(2.0))
+    K = np.array([0.0, 1.0, 1.0, 2.0]).reshape(1, 1, 4, 1)
+    assert np.allclose(orc.block_mass(q, K, 2, scale=1.0)[0, 0], [3.0 / 9.0, 6.0 / 9.0])
+    K = np.zeros((1, 2, 8, 4)); K[0, 1, 5] = 50.0
+    m = orc.block_mass(np.ones((1, 4, 2, 4)), K, 4, scale=1.0)
+    assert np.allclose(m[0, :2], 0.5) and np.allclose(m[0, 2:], [0.0, 1.0], atol=1e-12)
+
+
+def test_block_mass_matches_library_softmax_and_sums_to_one():
+    """Against scipy's softmax on scores written out here with einsum (GQA: head h reads KV head
+    h // G), summed per block by reduceat; each (batch, head) row of masses sums to 1."""
+    from scipy.special import softmax
+    rng = np.random.default_rng(8)
+    Q, K = rng.standard_normal((2, 6, 5, 16)), rng.standard_normal((2, 3, 45, 16))
+    m = orc.block_mass(Q, K, 8)
+    Kh = np.repeat(K, 2, axis=1)                               # KV head of each query head
+    pr = softmax(np.einsum("bhid,bhjd->bhij", Q, Kh) / 4.0, axis=-1)
+    want = np.add.reduceat(pr, np.arange(0, 45, 8), axis=-1).mean(axis=2)
+    assert np.allclose(m, want, atol=1e-13)
+    assert np.allclose(m.sum(-1), 1.0)
+
+
+def test_select_topk_scores_hand_and_bruteforce():
+    sc = np.array([[[0.1, 0.4, 0.4, 0.05, 0.05]]])
+    assert orc.select_topk_scores(sc, 1)[0, 0].tolist() == [1]               # tie -> lower index
+    assert orc.select_topk_scores(sc, 2)[0, 0].tolist() == [1, 2]
+    assert orc.select_topk_scores(sc, 4)[0, 0].tolist() == [0, 1, 2, 3]      # tie among the last again
+    assert orc.select_topk_scores(sc, 9)[0, 0].tolist() == [0, 1, 2, 3, 4]   # clamped
+    r = np.random.default_rng(3).standard_normal((2, 3, 17))
+    idx = orc.select_topk_scores(r, 6)
+    for b in range(2):
+        for h in range(3):
+            assert idx[b, h].tolist() == sorted(np.argsort(-r[b, h], kind="stable")[:6].tolist())
+
+
 def test_selection_key_mask_hand_example():
     """Block c covers tokens [c*kb, min(P, (c+1)*kb)): 7 tokens in blocks of 3, last block short."""
     idx = np.array([[[1], [2]]], dtype=np.int32)
