@@ -259,6 +259,25 @@ fb_status fb_select_topk(const fb_shape* shape, const void* q, const float* k_po
                          int32_t key_block, int32_t topk, int32_t* sel_idx, void* hip_stream);
 
 /*
+ * Key-block selection by attention mass (appendix on adapting the sparse method to block
+ * diffusion: the sparse mask of a block is derived from full attention at the block's first
+ * diffusion step and frozen for the block).  With p_ij = exp(s_ij - lse_i) the softmax weights of
+ * full attention over the prefix (lse_part = the log-normaliser a refresh step's external partial
+ * carries for the same q), the score of key block c for query head h is the mean over the block's
+ * query rows of sum_{j in c} p_ij; sel_idx gets the topk highest-scoring blocks per head, in the
+ * format fb_select_topk writes (ascending, ties to the lower index, -1 padding).
+ *   in : q [B,Hq,Bq,d], k_prefix [B,Hkv,P,d], lse_part [B,Hq,Bq] float
+ *   out: sel_idx int32 [B,Hq,topk]; mass_out float [B,Hq,nblk] (the scores; may be NULL)
+ *   workspace: >= fb_select_mass_workspace_bytes(shape, key_block) bytes (per-row masses).
+ * Reads K once (no V).  topk = 0 or prefix_len = 0: nothing is launched.
+ */
+size_t fb_select_mass_workspace_bytes(const fb_shape* shape, int32_t key_block);
+fb_status fb_select_topk_mass(const fb_shape* shape, const void* q, const void* k_prefix,
+                              const float* lse_part, int32_t key_block, int32_t topk,
+                              int32_t* sel_idx, float* mass_out, void* workspace,
+                              size_t workspace_bytes, void* hip_stream);
+
+/*
  * Sparse external pass with residual reuse (Section 4.2 sparse paragraph, Appendix D).
  * J_sel(h) = prefix keys inside the key blocks listed in sel_idx[b,h,:]; J_res(h) = the rest.
  *   mode FB_SPARSE_REFRESH: one pass over the whole prefix with the current q; keys of J_res

@@ -439,11 +439,67 @@ fb_status fb_select_topk(const fb_shape* shape, const void* q, const float* k_po
   if (!q || !sel_idx || (nblk > 0 && !k_pooled)) return FB_ERR_NULL;
   if (!aligned16(q) || !aligned16(k_pooled) || !aligned16(sel_idx)) return FB_ERR_ALIGN;
   fb::SelectParams p;
+  memset(&p, 0, sizeof(p));
   p.q = q; p.k_pooled = k_pooled; p.sel_idx = sel_idx;
   p.B = shape->batch; p.Hq = shape->n_q_heads; p.Hkv = shape->n_kv_heads;
   p.G = shape->n_q_heads / shape->n_kv_heads; p.Bq = shape->block_len; p.D = shape->head_dim;
   p.nblk = nblk; p.topk = topk; p.is_bf16 = shape->dtype == FB_BF16;
   hipError_t e = fb::launch_select_topk(p, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return hip_fail(e);
+  return FB_OK;
+}
+
+size_t fb_select_mass_workspace_bytes(const fb_shape* shape, int32_t key_block) {
+  if (check_shape(shape) != FB_OK) return 0;
+  int nblk = 0;
+  if (check_key_block(shape, key_block, 0, &nblk) != FB_OK) return 0;
+  return align256((size_t)rows_of(shape) * nblk * sizeof(float)) + 256;
+}
+
+fb_status fb_select_topk_mass(const fb_shape* shape, const void* q, const void* k_prefix, const float* lse_part,
+                              int32_t key_block, int32_t topk, int32_t* sel_idx, float* mass_out,
+                              void* workspace, size_t workspace_bytes, void* hip_stream) {
+  fb_status st = check_shape(shape);
+  if (st != FB_OK) return st;
+  int nblk = 0;
+  st = check_key_block(shape, key_block, topk, &nblk);
+  if (st != FB_OK) return st;
+  if (topk == 0 || nblk == 0) return FB_OK;
+  if (!q || !k_prefix || !lse_part || !sel_idx) return FB_ERR_NULL;
+  if (!aligned16(q) || !aligned16(k_prefix) || !aligned16(lse_part) || !aligned16(sel_idx) ||
+      !aligned16(mass_out) || !aligned16(workspace))
+    return FB_ERR_ALIGN;
+  if (!workspace || workspace_bytes < fb_select_mass_workspace_bytes(shape, key_block)) return FB_ERR_WORKSPACE;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  const bool bf16 = shape->dtype == FB_BF16;
+
+  fb::MassParams m;
+  memset(&m, 0, sizeof(m));
+  m.q = q; m.k = k_prefix; m.lse = lse_part; m.rowmass = (float*)workspace;
+  m.B = shape->batch; m.Hq = shape->n_q_heads; m.Hkv = shape->n_kv_heads;
+  m.G = shape->n_q_heads / shape->n_kv_heads; m.Bq = shape->block_len;
+  m.nkeys = shape->prefix_len; m.key_block = key_block; m.nblk = nblk;
+  m.scale_log2 = eff_scale(shape) * kLog2e;
+  {
+    // key-block ranges per row tile: enough workgroups for ~2 per CU, never more than key blocks
+    const long long groups = bf16
+        ? (long long)m.B * m.Hkv * ((m.G * m.Bq + fb::kRowsPerWgBf16 - 1) / fb::kRowsPerWgBf16)
+        : (long long)m.B * m.Hq * ((m.Bq + fb::kRowsPerWgF32 - 1) / fb::kRowsPerWgF32);
+    long long ns = ((bf16 ? 512 : 1024) + groups - 1) / groups;
+    if (ns > nblk) ns = nblk;
+    if (ns > 65535) ns = 65535;
+    m.nsplit = (int)ns;
+  }
+  hipError_t e = bf16 ? fb::launch_block_mass_bf16(m, shape->head_dim, stream)
+                      : fb::launch_block_mass_f32(m, shape->head_dim, stream);
+  if (e != hipSuccess) return hip_fail(e);
+
+  fb::SelectParams p;
+  memset(&p, 0, sizeof(p));
+  p.sel_idx = sel_idx; p.rowmass = m.rowmass; p.score_out = mass_out;
+  p.B = m.B; p.Hq = m.Hq; p.Hkv = m.Hkv; p.G = m.G; p.Bq = m.Bq; p.D = shape->head_dim;
+  p.nblk = nblk; p.topk = topk; p.is_bf16 = bf16;
+  e = fb::launch_select_topk(p, stream);
   if (e != hipSuccess) return hip_fail(e);
   return FB_OK;
 }

@@ -690,6 +690,79 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
   }
 }
 
+// Attention mass per (query row, key block) at a step that has the log-normaliser of full attention
+// over the prefix: p_ij = exp(s_ij - lse_i), summed over the keys of each block.  Reads K only.
+// Workgroup = 128 group-flattened rows of one KV head x a range of key blocks; scores as in the
+// attention pass (S^T = K Q^T on the MFMA units, K tiles double-buffered in LDS).
+template <int D>
+__global__ __launch_bounds__(256) void block_mass_bf16_kernel(const MassParams p) {
+  using C = Cfg<D, kKeyTile>;
+  __shared__ __align__(16) unsigned char stages[2 * C::KBYTES];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, h = lane >> 5;
+  const int rt = blockIdx.x, split = blockIdx.y, bk = blockIdx.z;
+  const int b = bk / p.Hkv, kvh = bk % p.Hkv;
+  const int nrows = p.G * p.Bq, nkeys = p.nkeys;
+  const int row = rt * kRowsPerWgBf16 + wave * 32 + l32;
+  const bool row_ok = row < nrows;
+  const size_t hrow = (size_t)kvh * nrows + (row_ok ? row : nrows - 1);   // head * Bq + i within the batch element
+  const size_t grow = (size_t)b * p.Hq * p.Bq + hrow;
+  const __bf16* __restrict__ Q = (const __bf16*)p.q;
+  const __bf16* __restrict__ K = (const __bf16*)p.k + (size_t)bk * nkeys * D;
+
+  const int tpb = p.key_block / kKeyTile;
+  const TileRange br = split_range(p.nblk, p.nsplit, split);            // key blocks of this workgroup
+  const int t0 = br.begin * tpb, t1 = min(br.end * tpb, (nkeys + kKeyTile - 1) / kKeyTile);
+  if (t0 >= t1) return;                                                 // workgroup-uniform
+
+  u32x4 kr[4];
+  load_k<D, kKeyTile>(kr, K, t0 * kKeyTile, nkeys, tid);
+  bf16x8 qreg[C::NKS];
+#pragma unroll
+  for (int ks = 0; ks < C::NKS; ++ks) qreg[ks] = __builtin_bit_cast(bf16x8, gload128(Q + grow * D + ks * 16 + 8 * h));
+  const float lse = p.lse[grow];
+  const bool live = lse != -INFINITY;
+  const float lse2 = live ? lse * kLog2e : 0.f;
+  store_k<D, kKeyTile>(kr, stages, tid);
+  __syncthreads();
+
+  float acc = 0.f;
+  for (int t = t0; t < t1; ++t) {
+    const int cur = (t - t0) & 1;
+    const bool more = t + 1 < t1;                                       // workgroup-uniform
+    if (more) load_k<D, kKeyTile>(kr, K, (t + 1) * kKeyTile, nkeys, tid);
+    const unsigned char* Ks = stages + cur * C::KBYTES;
+    f32x16 s[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < C::NKS; ++ks)
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        const bf16x8 a = *(const bf16x8*)(Ks + (kb * 32 + l32) * C::KSTR + (ks * 16 + 8 * h) * 2);
+        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], s[kb], 0, 0, 0);
+      }
+    const int nvalid = min(kKeyTile, nkeys - t * kKeyTile);
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int key = kb * 32 + 8 * (r / 4) + 4 * h + (r % 4);          // key of this accumulator register
+        const float pf = __builtin_amdgcn_exp2f(fmaf(s[kb][r], p.scale_log2, -lse2));
+        acc += (key < nvalid) ? pf : 0.f;
+      }
+    if (more) store_k<D, kKeyTile>(kr, stages + (cur ^ 1) * C::KBYTES, tid);
+    __syncthreads();
+    if ((t + 1) % tpb == 0 || !more) {                                  // the key block is complete
+      const float tot = acc + __shfl_xor(acc, 32, 64);
+      if (h == 0 && row_ok)
+        p.rowmass[((size_t)b * p.nblk + t / tpb) * ((size_t)p.Hq * p.Bq) + hrow] = live ? tot : 0.f;
+      acc = 0.f;
+    }
+  }
+}
+
 template <int D, int MODE, int KT, int WS, int NG>
 hipError_t launch_one(const PassParams& p, hipStream_t s) {
   static bool attr_set = false;   // raising the dynamic-LDS limit is idempotent; the flag only saves calls
@@ -777,6 +850,14 @@ hipError_t launch_d(const PassParams& p, PassMode mode, hipStream_t s) {
 }
 
 }  // namespace
+
+hipError_t launch_block_mass_bf16(const MassParams& p, int D, hipStream_t s) {
+  const int rowtiles = (p.G * p.Bq + kRowsPerWgBf16 - 1) / kRowsPerWgBf16;
+  const dim3 grid(rowtiles, p.nsplit, p.B * p.Hkv);
+  if (D == 64) hipLaunchKernelGGL(block_mass_bf16_kernel<64>, grid, dim3(256), 0, s, p);
+  else hipLaunchKernelGGL(block_mass_bf16_kernel<128>, grid, dim3(256), 0, s, p);
+  return hipGetLastError();
+}
 
 hipError_t launch_attn_bf16(const PassParams& p, int D, PassMode mode, hipStream_t s) {
   if (D == 64) return launch_d<64>(p, mode, s);

@@ -241,6 +241,63 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const PassParams p) {
   }
 }
 
+// Attention mass per (query row, key block): sum over the block's keys of exp(s - lse), fp32 storage.
+// Same work decomposition as the attention pass (one wavefront per query row, lane j scores key j).
+template <int D>
+__global__ __launch_bounds__(256) void block_mass_f32_kernel(const MassParams p) {
+  constexpr int KSTR = D + 4;
+  constexpr float kLog2e = 1.4426950408889634f;
+  __shared__ __align__(16) float Ks[kKeyTile * KSTR];
+  __shared__ __align__(16) float Qs[4 * D];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int chunk = blockIdx.x, bh = blockIdx.y, split = blockIdx.z;
+  const int b = bh / p.Hq, h = bh % p.Hq, kvh = h / p.G;
+  const int row = chunk * 4 + wave, nkeys = p.nkeys;
+  const bool valid = row < p.Bq;
+  const float* __restrict__ Q = (const float*)p.q + (size_t)bh * p.Bq * D;
+  const float* __restrict__ K = (const float*)p.k + (size_t)(b * p.Hkv + kvh) * nkeys * D;
+  for (int i = tid; i < 4 * D; i += 256) {
+    const int r = chunk * 4 + i / D;
+    Qs[i] = (r < p.Bq) ? Q[(size_t)r * D + (i % D)] : 0.f;
+  }
+  const float lse = valid ? p.lse[(size_t)bh * p.Bq + row] : 0.f;
+  const bool live = lse != -INFINITY;
+  const float lse2 = live ? lse * kLog2e : 0.f;
+  const int tpb = p.key_block / kKeyTile;
+  const TileRange br = split_range(p.nblk, p.nsplit, split);
+  const int t0 = br.begin * tpb, t1 = min(br.end * tpb, (nkeys + kKeyTile - 1) / kKeyTile);
+  float acc = 0.f;
+  for (int t = t0; t < t1; ++t) {
+    const int k0 = t * kKeyTile;
+    __syncthreads();
+    for (int c = tid; c < kKeyTile * (D / 4); c += 256) {
+      const int r = c / (D / 4), c4 = c % (D / 4);
+      float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (k0 + r < nkeys) val = *(const float4*)(K + (size_t)(k0 + r) * D + c4 * 4);
+      *(float4*)(Ks + r * KSTR + c4 * 4) = val;
+    }
+    __syncthreads();
+    const float4* kr = (const float4*)(Ks + lane * KSTR);
+    const float4* qr = (const float4*)(Qs + wave * D);
+    float s = 0.f;
+#pragma unroll 8
+    for (int i = 0; i < D / 4; ++i) {
+      const float4 a = kr[i], c = qr[i];
+      s = fmaf(a.x, c.x, s);
+      s = fmaf(a.y, c.y, s);
+      s = fmaf(a.z, c.z, s);
+      s = fmaf(a.w, c.w, s);
+    }
+    acc += (k0 + lane < nkeys) ? exp2f(s * p.scale_log2 - lse2) : 0.f;
+    if ((t + 1) % tpb == 0 || t + 1 == t1) {
+      const float tot = wave_sum(acc);
+      if (valid && lane == 0)
+        p.rowmass[((size_t)b * p.nblk + t / tpb) * ((size_t)p.Hq * p.Bq) + (size_t)h * p.Bq + row] = live ? tot : 0.f;
+      acc = 0.f;
+    }
+  }
+}
+
 template <int D>
 hipError_t launch_d(const PassParams& p, PassMode mode, hipStream_t s) {
   const dim3 grid((p.Bq + kRowsPerWgF32 - 1) / kRowsPerWgF32, p.B * p.Hq, p.nsplit + (mode == kPassRefreshFused ? 1 : 0));
@@ -258,6 +315,13 @@ hipError_t launch_d(const PassParams& p, PassMode mode, hipStream_t s) {
 }
 
 }  // namespace
+
+hipError_t launch_block_mass_f32(const MassParams& p, int D, hipStream_t s) {
+  const dim3 grid((p.Bq + kRowsPerWgF32 - 1) / kRowsPerWgF32, p.B * p.Hq, p.nsplit);
+  if (D == 64) hipLaunchKernelGGL(block_mass_f32_kernel<64>, grid, dim3(256), 0, s, p);
+  else hipLaunchKernelGGL(block_mass_f32_kernel<128>, grid, dim3(256), 0, s, p);
+  return hipGetLastError();
+}
 
 hipError_t launch_attn_f32(const PassParams& p, int D, PassMode mode, hipStream_t s) {
   if (D == 64) return launch_d<64>(p, mode, s);

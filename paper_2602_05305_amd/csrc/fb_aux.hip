@@ -301,6 +301,18 @@ __global__ __launch_bounds__(256) void select_topk_kernel(const SelectParams p) 
   const int D = p.D, tid = threadIdx.x, nblk = p.nblk;
   const int k = min(p.topk, nblk);
 
+  if (p.rowmass != nullptr) {
+    // score = attention mass of the block: mean over the head's rows of the per-row masses (fixed order)
+    const float* rm = p.rowmass + (size_t)b * nblk * ((size_t)p.Hq * p.Bq) + (size_t)h * p.Bq;
+    for (int c = tid; c < nblk; c += 256) {
+      const float* r = rm + (size_t)c * ((size_t)p.Hq * p.Bq);
+      float s = 0.f;
+      for (int i = 0; i < p.Bq; ++i) s += r[i];
+      s /= (float)p.Bq;
+      key[c] = order_key(s);
+      if (p.score_out != nullptr) p.score_out[(size_t)bh * nblk + c] = s;
+    }
+  } else {
   {  // mean over the block's query rows
     const int d = tid % D, tl = tid / D, ntl = 256 / D;
     float s = 0.f;
@@ -325,6 +337,7 @@ __global__ __launch_bounds__(256) void select_topk_kernel(const SelectParams p) 
       s = fmaf(a.w, qbar[4 * i + 3], s);
     }
     key[c] = order_key(s);
+  }
   }
   __syncthreads();
 

@@ -101,6 +101,16 @@ struct CombineParams {
 struct SelectParams {
   const void* q; const float* k_pooled; int32_t* sel_idx;
   int B, Hq, Hkv, G, Bq, D, nblk, topk, is_bf16;
+  // score source "attention mass": per-row masses [B][nblk][Hq*Bq] (then q / k_pooled are unused), and an
+  // optional copy of the block scores [B,Hq,nblk]
+  const float* rowmass; float* score_out;
+};
+
+// Attention mass of every (query row, key block): sum over the block's keys of exp(s - lse).
+struct MassParams {
+  const void* q; const void* k; const float* lse; float* rowmass;   // rowmass [B][nblk][Hq*Bq]
+  int B, Hq, Hkv, G, Bq, nkeys, key_block, nblk, nsplit;            // nsplit: key-block ranges per row tile
+  float scale_log2;
 };
 
 struct PoolParams {
@@ -120,6 +130,8 @@ hipError_t launch_combine(const CombineParams& p, hipStream_t s);
 hipError_t launch_pool_keys(const PoolParams& p, hipStream_t s);
 hipError_t launch_select_topk(const SelectParams& p, hipStream_t s);
 hipError_t launch_build_masks(const MaskParams& p, hipStream_t s);
+hipError_t launch_block_mass_f32(const MassParams& p, int D, hipStream_t s);
+hipError_t launch_block_mass_bf16(const MassParams& p, int D, hipStream_t s);
 hipError_t launch_seq_order(const int32_t* prefix_lens, int32_t* seq_order, int B, hipStream_t s);
 hipError_t launch_head_similarity(const float* o_a, const float* o_b, float* sim, int BH, int Bq, int D, hipStream_t s);
 

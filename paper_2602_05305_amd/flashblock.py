@@ -59,6 +59,9 @@ _SIGNATURES = {
     "fb_refresh_step_prof": (c_int, [POINTER(fb_shape)] + [c_void_p] * 11 + [c_size_t] + [c_void_p] * 4),
     "fb_pool_keys": (c_int, [POINTER(fb_shape), c_void_p, c_int32, c_void_p, c_void_p]),
     "fb_select_topk": (c_int, [POINTER(fb_shape), c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p]),
+    "fb_select_mass_workspace_bytes": (c_size_t, [POINTER(fb_shape), c_int32]),
+    "fb_select_topk_mass": (c_int, [POINTER(fb_shape), c_void_p, c_void_p, c_void_p, c_int32, c_int32, c_void_p,
+                                    c_void_p, c_void_p, c_size_t, c_void_p]),
     "fb_sparse_external_residual": (c_int, [POINTER(fb_shape), c_int32, c_void_p, c_void_p, c_void_p, c_int32,
                                             c_int32] + [c_void_p] * 8 + [c_size_t, c_void_p]),
 }
@@ -213,6 +216,17 @@ def fb_select_topk(shape, q, k_pooled, key_block, topk, sel_idx, stream=None):
     st = load_library().fb_select_topk(ctypes.byref(shape), _ptr(q), _ptr(k_pooled), key_block, topk, _ptr(sel_idx),
                                        _stream(stream))
     _check(st, "fb_select_topk")
+
+
+def fb_select_mass_workspace_bytes(shape, key_block) -> int:
+    return int(load_library().fb_select_mass_workspace_bytes(ctypes.byref(shape), key_block))
+
+
+def fb_select_topk_mass(shape, q, k_prefix, lse_part, key_block, topk, sel_idx, mass_out, workspace, stream=None):
+    st = load_library().fb_select_topk_mass(ctypes.byref(shape), _ptr(q), _ptr(k_prefix), _ptr(lse_part), key_block,
+                                            topk, _ptr(sel_idx), _ptr(mass_out), _ptr(workspace),
+                                            workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(st, "fb_select_topk_mass")
 
 
 def fb_sparse_external_residual(shape, mode, q, k_prefix, v_prefix, key_block, topk, sel_idx, res_o, res_m, res_lse,

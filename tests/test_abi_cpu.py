@@ -206,6 +206,33 @@ def test_sparse_error_paths():
     assert lib.fb_pool_keys(ctypes.byref(huge), FAKE, 64, FAKE, None) == fb.FB_ERR_UNSUPPORTED
 
 
+def test_select_topk_mass_error_paths():
+    lib = fb.load_library()
+    s = _ok_shape()
+    n = fb.fb_select_mass_workspace_bytes(s, 64)
+    assert n >= 64 * 4 * 4                           # 64 rows x 4 key blocks, floats
+    assert fb.fb_select_mass_workspace_bytes(s, 48) == 0
+    assert fb.fb_select_mass_workspace_bytes(_ok_shape(batch=0), 64) == 0
+    call = lib.fb_select_topk_mass
+    ok = [FAKE, FAKE, FAKE, 64, 2, FAKE, None, FAKE, n, None]     # q k lse key_block topk idx mass ws bytes stream
+    for i in (0, 1, 2, 5):
+        a = list(ok); a[i] = None
+        assert call(ctypes.byref(s), *a) == fb.FB_ERR_NULL, i
+    a = list(ok); a[3] = 48
+    assert call(ctypes.byref(s), *a) == fb.FB_ERR_UNSUPPORTED
+    a = list(ok); a[4] = -1
+    assert call(ctypes.byref(s), *a) == fb.FB_ERR_SHAPE
+    a = list(ok); a[4] = 0
+    assert call(ctypes.byref(s), *a) == fb.FB_OK                  # nothing to select, nothing launched
+    a = list(ok); a[6] = ODD
+    assert call(ctypes.byref(s), *a) == fb.FB_ERR_ALIGN
+    a = list(ok); a[7] = None
+    assert call(ctypes.byref(s), *a) == fb.FB_ERR_WORKSPACE
+    a = list(ok); a[8] = n - 1
+    assert call(ctypes.byref(s), *a) == fb.FB_ERR_WORKSPACE
+    assert call(ctypes.byref(_ok_shape(prefix_len=0)), *ok) == fb.FB_OK
+
+
 def test_status_strings():
     lib = fb.load_library()
     seen = {lib.fb_status_string(i).decode() for i in range(8)}

@@ -149,3 +149,74 @@ def test_sparse_gpu_selection_end_to_end():
         sel = orc.partial(Q, Kp, Vp, key_mask=kmask)
         out, _ = orc.merge(orc.merge_partials(sel, res), orc.partial(Q, Kb, Vb))
         T.assert_close(gpu[t]["out"], out, "bf16", f"gpu-selected step {t}")
+
+
+# ------------------------------------------------------------------ selection by attention mass
+@pytest.mark.parametrize("dtype,B,Hq,Hkv,d,P,Bq,kb,topk", [
+    ("f32", 1, 4, 2, 64, 700, 7, 64, 3),
+    ("f32", 2, 4, 4, 128, 256, 16, 128, 1),
+    ("bf16", 1, 8, 2, 128, 2048 + 37, 32, 64, 8),
+    ("bf16", 2, 4, 4, 64, 1000, 16, 128, 5),
+    ("bf16", 1, 32, 8, 128, 8192, 32, 256, 8),
+    ("bf16", 1, 4, 4, 128, 1024, 200, 64, 20),       # several row tiles; topk > number of key blocks
+])
+def test_select_topk_mass_matches_oracle(dtype, B, Hq, Hkv, d, P, Bq, kb, topk):
+    """fb_select_topk_mass: the block scores (attention mass) against the oracle within the
+    storage tolerance (relative: masses are of order 1/nblk), rows summing to 1, and the selection
+    = the oracle's top-k of the oracle's masses except for near-ties at the k-th score."""
+    w = _wl(dtype, B, Hq, Hkv, d, P, Bq, kb, topk)
+    print(f"[case] mass {w.name}", flush=True)
+    Kp, Vp = wl.make_prefix(w, 61)
+    Q = wl.make_block_steps(w, 61, steps=1)[0][0]
+    shape = T.shape_of(w)
+    q, kp, vp = T.to_dev(Q, dtype), T.to_dev(Kp, dtype), T.to_dev(Vp, dtype)
+    ext = T.Partial(w)
+    fb.fb_external_partial(shape, q, kp, vp, ext.o, ext.m, ext.lse, T.workspace(shape))
+    nblk = -(-P // kb)
+    idx = torch.full((B, Hq, topk), -7, device=T.DEV, dtype=torch.int32)
+    mass = torch.full((B, Hq, nblk), -1.0, device=T.DEV, dtype=torch.float32)
+    ws = torch.empty(fb.fb_select_mass_workspace_bytes(shape, kb), device=T.DEV, dtype=torch.uint8)
+    fb.fb_select_topk_mass(shape, q, kp, ext.lse, kb, topk, idx, mass, ws)
+    torch.cuda.synchronize()
+    want_mass = orc.block_mass(Q, Kp, kb)
+    got_mass = mass.double().cpu().numpy()
+    rel = 2e-5 if dtype == "f32" else 1e-2
+    assert np.abs(got_mass - want_mass).max() <= rel * want_mass.max() + 1e-7, np.abs(got_mass - want_mass).max()
+    assert np.abs(got_mass.sum(-1) - 1.0).max() <= (1e-4 if dtype == "f32" else 1e-2)
+    want = orc.select_topk_scores(want_mass, topk)
+    got = idx.cpu().numpy()
+    k = min(topk, nblk)
+    assert (got[:, :, k:] == -1).all()
+    for b in range(B):
+        for h in range(Hq):
+            g = got[b, h, :k]
+            assert (np.diff(g) > 0).all() and g.min() >= 0 and g.max() < nblk
+            diff = set(g.tolist()) ^ set(want[b, h].tolist())
+            if diff:
+                kth = np.sort(want_mass[b, h])[::-1][k - 1]
+                assert all(abs(want_mass[b, h, c] - kth) <= rel * want_mass[b, h].max() for c in diff), (b, h, diff)
+    # the kernel's own scores and its own selection are consistent: exact top-k of mass_out, ties low
+    own = orc.select_topk_scores(got_mass, topk)
+    assert np.array_equal(own, got[:, :, :k])
+
+
+def test_mass_selection_feeds_the_sparse_path():
+    """Mass-selected blocks go through fb_sparse_external_residual like any other selection; the
+    refresh step stays exact attention."""
+    w = _wl("bf16", 1, 8, 2, 128, 4096, 32, 64, 16)
+    Kp, Vp = wl.make_prefix(w, 63)
+    Q, Kb, Vb = wl.make_block_steps(w, 63, steps=1)[0]
+    shape = T.shape_of(w)
+    q, kp, vp = T.to_dev(Q, "bf16"), T.to_dev(Kp, "bf16"), T.to_dev(Vp, "bf16")
+    ext, res, tot = T.Partial(w), T.Partial(w), T.Partial(w)
+    ws = T.workspace(shape, w.key_block, w.topk)
+    fb.fb_external_partial(shape, q, kp, vp, ext.o, ext.m, ext.lse, ws)
+    idx = torch.empty((1, 8, 16), device=T.DEV, dtype=torch.int32)
+    wsm = torch.empty(fb.fb_select_mass_workspace_bytes(shape, 64), device=T.DEV, dtype=torch.uint8)
+    fb.fb_select_topk_mass(shape, q, kp, ext.lse, 64, 16, idx, None, wsm)
+    fb.fb_sparse_external_residual(shape, fb.FB_SPARSE_REFRESH, q, kp, vp, 64, 16, idx, res.o, res.m, res.lse,
+                                   tot.o, tot.m, tot.lse, ws)
+    torch.cuda.synchronize()
+    T.check_partial(tot.numpy(), orc.partial(Q, Kp, Vp), "bf16", "mass-selected refresh total")
+    kmask = orc.selection_key_mask(idx.cpu().numpy(), w.prefix_len, w.key_block)
+    T.check_partial(res.numpy(), orc.partial(Q, Kp, Vp, key_mask=~kmask), "bf16", "mass-selected residual")
