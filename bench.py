@@ -293,10 +293,15 @@ def sparse_extra(torch, fb, wl):
     ro = torch.empty(rows + (w.head_dim,), device="cuda")
     rm, rl = torch.empty(rows, device="cuda"), torch.empty(rows, device="cuda")
     q = d.steps[0][0]
+    i = [0]
     t_pool = _ev_median_us(torch, lambda: fb.fb_pool_keys(d.shape, d.K[0], w.key_block, pooled[0]))
     fb.fb_pool_keys(d.shape, d.K[1], w.key_block, pooled[1])
     t_sel = _ev_median_us(torch, lambda: fb.fb_select_topk(d.shape, q, pooled[0], w.key_block, w.topk, idx))
-    i = [0]
+    wsm = torch.empty(fb.fb_select_mass_workspace_bytes(d.shape, w.key_block), device="cuda", dtype=torch.uint8)
+    fb.fb_external_partial(d.shape, q, d.K[0], d.V[0], d.o, d.m, d.lse, ws)
+    idx_m = torch.empty_like(idx)
+    t_mass = _ev_median_us(torch, lambda: fb.fb_select_topk_mass(d.shape, q, d.K[i[0] % 2], d.lse, w.key_block, w.topk,
+                                                                   idx_m, None, wsm))
 
     def call(mode):
         s = i[0] % 2
@@ -312,6 +317,7 @@ def sparse_extra(torch, fb, wl):
     union_bytes = union * w.key_block * w.head_dim * 2 * 2
     return {"workload": describe(w) + f", key_block {w.key_block}, topk {w.topk}",
             "pool_keys_us": round(t_pool, 1), "select_topk_us": round(t_sel, 1),
+            "select_topk_mass_us": round(t_mass, 1),
             "sparse_refresh_call_us": round(t_refresh, 1), "sparse_reuse_call_us": round(t_reuse, 1),
             "dense_external_call_us": round(t_dense, 1),
             "union_fraction_of_prefix": round(union / (nblk * w.n_kv_heads), 3),
@@ -382,28 +388,36 @@ def sparse_accuracy(torch, fb, wl, prefix_len=32768):
                  torch.full(shp, float("-inf"), device="cuda"))
         fb.fb_pool_keys(d.shape, d.K[0], w.key_block, pooled)
         out_a, out_b, out_f = torch.empty_like(d.out), torch.empty_like(d.out), torch.empty_like(d.out)
-        l1_res, l1_only = [], []
-        for t, (q, kb, vb) in enumerate(d.steps):
-            if t == 0:
-                fb.fb_select_topk(d.shape, q, pooled, w.key_block, w.topk, idx)
-                fb.fb_sparse_external_residual(d.shape, fb.FB_SPARSE_REFRESH, q, d.K[0], d.V[0], w.key_block, w.topk,
-                                               idx, *res, *ext, ws)
-                continue
-            fb.fb_sparse_external_residual(d.shape, fb.FB_SPARSE_REUSE, q, d.K[0], d.V[0], w.key_block, w.topk, idx,
-                                           *res, *ext, ws)
-            fb.fb_internal_merge(d.shape, q, kb, vb, *ext, out_a, None)
-            fb.fb_sparse_external_residual(d.shape, fb.FB_SPARSE_REUSE, q, d.K[0], d.V[0], w.key_block, w.topk, idx,
-                                           *empty, *ext, ws)
-            fb.fb_internal_merge(d.shape, q, kb, vb, *ext, out_b, None)
-            fb.fb_external_partial(d.shape, q, d.K[0], d.V[0], *full, ws)
-            fb.fb_internal_merge(d.shape, q, kb, vb, *full, out_f, None)
-            l1_res.append((out_a.float() - out_f.float()).abs().mean().item())
-            l1_only.append((out_b.float() - out_f.float()).abs().mean().item())
-        rows.append({"density": density, "l1_sparse_only": sum(l1_only) / len(l1_only),
-                     "l1_sparse_plus_cached_residual": sum(l1_res) / len(l1_res)})
+        wsm = torch.empty(fb.fb_select_mass_workspace_bytes(d.shape, w.key_block), device="cuda", dtype=torch.uint8)
+        row = {"density": density}
+        for rule in ("mean_pooled_keys", "attention_mass"):
+            l1_res, l1_only = [], []
+            for t, (q, kb, vb) in enumerate(d.steps):
+                if t == 0:
+                    if rule == "mean_pooled_keys":
+                        fb.fb_select_topk(d.shape, q, pooled, w.key_block, w.topk, idx)
+                    else:       # mask from full attention at the block's first step
+                        fb.fb_external_partial(d.shape, q, d.K[0], d.V[0], *full, ws)
+                        fb.fb_select_topk_mass(d.shape, q, d.K[0], full[2], w.key_block, w.topk, idx, None, wsm)
+                    fb.fb_sparse_external_residual(d.shape, fb.FB_SPARSE_REFRESH, q, d.K[0], d.V[0], w.key_block, w.topk,
+                                                   idx, *res, *ext, ws)
+                    continue
+                fb.fb_sparse_external_residual(d.shape, fb.FB_SPARSE_REUSE, q, d.K[0], d.V[0], w.key_block, w.topk, idx,
+                                               *res, *ext, ws)
+                fb.fb_internal_merge(d.shape, q, kb, vb, *ext, out_a, None)
+                fb.fb_sparse_external_residual(d.shape, fb.FB_SPARSE_REUSE, q, d.K[0], d.V[0], w.key_block, w.topk, idx,
+                                               *empty, *ext, ws)
+                fb.fb_internal_merge(d.shape, q, kb, vb, *ext, out_b, None)
+                fb.fb_external_partial(d.shape, q, d.K[0], d.V[0], *full, ws)
+                fb.fb_internal_merge(d.shape, q, kb, vb, *full, out_f, None)
+                l1_res.append((out_a.float() - out_f.float()).abs().mean().item())
+                l1_only.append((out_b.float() - out_f.float()).abs().mean().item())
+            row[rule] = {"l1_sparse_only": sum(l1_only) / len(l1_only),
+                         "l1_sparse_plus_cached_residual": sum(l1_res) / len(l1_res)}
+        rows.append(row)
         del d
         torch.cuda.empty_cache()
-    return {"workload": describe(base) + ", densities swept", "mean_abs_output": None, "rows": rows}
+    return {"workload": describe(base) + ", densities swept, two selection rules", "rows": rows}
 
 
 def describe(w):
