@@ -267,7 +267,13 @@ def video_extra(torch, fb, wl):
     t_int = _ev_median_us(torch, lambda: fb.fb_internal_merge(d.shape, q, kb, vb, d.o, d.m, d.lse, d.out, None), 7, 2)
     hm = torch.zeros((w.batch, w.n_q_heads), device="cuda", dtype=torch.uint8)
     hm[:, ::2] = 1                       # head-wise selective refresh: every other head recomputed
-    t_half = _ev_median_us(torch, lambda: fb.fb_external_partial_heads(d.shape, q, d.K[0], d.V[0], hm, d.o, d.m, d.lse, d.ws), 7, 2)
+    ws_h = torch.empty(fb.fb_workspace_bytes(d.shape, 0, 0, 8), device="cuda", dtype=torch.uint8)
+    t_half = _ev_median_us(torch, lambda: fb.fb_external_partial_heads(d.shape, q, d.K[0], d.V[0], hm, d.o, d.m, d.lse,
+                                                                       ws_h, w.n_q_heads // 2), 7, 2)
+    hm1 = torch.zeros((w.batch, w.n_q_heads), device="cuda", dtype=torch.uint8)
+    hm1[:, 3] = 1                        # a single unstable head
+    t_one = _ev_median_us(torch, lambda: fb.fb_external_partial_heads(d.shape, q, d.K[0], d.V[0], hm1, d.o, d.m, d.lse,
+                                                                      ws_h, 1), 7, 2)
     f_ext = 4.0 * w.batch * w.n_q_heads * w.block_len * w.prefix_len * w.head_dim
     f_int = 4.0 * w.batch * w.n_q_heads * w.block_len * w.block_len * w.head_dim
     peak = 2500.0
@@ -275,7 +281,7 @@ def video_extra(torch, fb, wl):
     return {"workload": describe(w), "bound": "mfma", "peak": peak, "unit": "TFLOP/s",
             "external_us": round(t_ext, 1), "external_tflops": round(f_ext / t_ext / 1e6, 1),
             "external_frac": round(f_ext / t_ext / 1e6 / peak, 4),
-            "external_half_of_heads_us": round(t_half, 1),
+            "external_half_of_heads_us": round(t_half, 1), "external_one_head_us": round(t_one, 1),
             "internal_us": round(t_int, 1), "internal_tflops": round(f_int / t_int / 1e6, 1),
             "internal_frac": round(f_int / t_int / 1e6 / peak, 4),
             "block_speedup_cached_vs_full": round(S * (t_ext + t_int) / (-(-S // R) * t_ext + S * t_int), 3)}
@@ -325,10 +331,10 @@ def sparse_extra(torch, fb, wl):
             "refresh_GBps_vs_kv_bytes": round(w.kv_bytes / t_refresh / 1e3, 1)}
 
 
-def paged_extra(torch, fb, wl):
+def paged_setup(torch, fb, wl):
     """Paged prefix cache with ragged per-sequence lengths (the serving shape): batch 32, prefix
-    lengths uniform in [512, 8192], 256-token pages handed out in random order.  Bandwidth is priced
-    against the K/V bytes of the tokens that exist, not of the padded maximum."""
+    lengths uniform in [512, 8192], 256-token pages handed out in random order.  Returns the
+    call closure and a description."""
     import numpy as np
     base = wl.CONFIGS["llm_32k"]
     B, pmax, page = 32, 8192, 256
@@ -359,13 +365,22 @@ def paged_extra(torch, fb, wl):
     def call():
         fb.fb_external_partial_paged(shape, q, kvs[i[0] % 2], o, m, l, ws)
         i[0] += 1
-    t = _ev_median_us(torch, call)
     kv_bytes = int(lens.sum()) * base.n_kv_heads * base.head_dim * 2 * 2
-    return {"workload": f"paged external pass: batch {B}, prefix lengths uniform 512..{pmax} ({int(lens.sum())} tokens), "
+    info = {"workload": f"paged external pass: batch {B}, prefix lengths uniform 512..{pmax} ({int(lens.sum())} tokens), "
                         f"{page}-token pages in random order, {base.n_q_heads} q / {base.n_kv_heads} kv heads, "
                         f"head_dim {base.head_dim}, block {base.block_len}, bf16",
-            "splits": ns, "external_call_us": round(t, 1), "kv_bytes": kv_bytes,
-            "GBps_vs_kv_bytes": round(kv_bytes / t / 1e3, 1), "frac_of_8TBps": round(kv_bytes / t / 1e3 / 8000.0, 4)}
+            "splits": ns, "kv_bytes": kv_bytes}
+    return call, info
+
+
+def paged_extra(torch, fb, wl):
+    """Bandwidth of the paged external pass, priced against the K/V bytes of the tokens that exist
+    (not of the padded maximum)."""
+    call, info = paged_setup(torch, fb, wl)
+    t = _ev_median_us(torch, call)
+    info.update({"external_call_us": round(t, 1), "GBps_vs_kv_bytes": round(info["kv_bytes"] / t / 1e3, 1),
+                 "frac_of_8TBps": round(info["kv_bytes"] / t / 1e3 / 8000.0, 4)})
+    return info
 
 
 def sparse_accuracy(torch, fb, wl, prefix_len=32768):
@@ -444,6 +459,8 @@ def main():
                     help="only print the sparse-vs-full L1 table (synthetic analogue of the paper's Table 3)")
     ap.add_argument("--profile-sparse", type=int, default=0, metavar="N",
                     help="only run N sparse refresh + reuse call pairs of the sparse_64k workload (for rocprofv3)")
+    ap.add_argument("--profile-paged", type=int, default=0, metavar="N",
+                    help="only run N paged external passes of the batch-32 serving shape (for rocprofv3)")
     ap.add_argument("--profile-copy", type=int, default=0, metavar="N",
                     help="only run N plain device copies of 256 MiB (calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -468,6 +485,13 @@ def main():
             y.copy_(x)
         torch.cuda.synchronize()
         print(f"ran {args.profile_copy} device copies of {x.numel()} bytes (read {x.numel()} + write {x.numel()} per copy)")
+        return
+    if args.profile_paged > 0:
+        call, info = paged_setup(torch, fb, wl)
+        for _ in range(args.profile_paged):
+            call()
+        torch.cuda.synchronize()
+        print(f"ran {args.profile_paged} calls of {info['workload']} ({info['kv_bytes']} K/V bytes per call)")
         return
     if args.sparse_accuracy:
         print(json.dumps(sparse_accuracy(torch, fb, wl)))

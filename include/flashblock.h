@@ -144,11 +144,18 @@ fb_status fb_external_partial_prof(const fb_shape* shape, const void* q, const v
  * the other heads are left exactly as they are (their cached partial stays in force).  Which
  * heads to refresh is the caller's policy.  head_mask: device, uint8 [B,Hq], required.
  * KV groups none of whose query heads is flagged are not streamed at all.
+ * n_active_heads: host-side hint, the largest number of flagged heads in any batch element
+ * (0 = unknown, sized as if all were flagged).  The mask lives in device memory, so this is the
+ * only way the library can tell that few workgroups will do real work and cut the prefix into
+ * more splits to keep the GPU full; a wrong hint costs speed, never correctness.
+ * workspace: >= fb_workspace_bytes(shape, 0, 0, fb_external_heads_splits(shape, n_active_heads)).
  */
+int32_t fb_external_heads_splits(const fb_shape* shape, int32_t n_active_heads);
 fb_status fb_external_partial_heads(const fb_shape* shape, const void* q, const void* k_prefix,
-                                    const void* v_prefix, const uint8_t* head_mask, float* o_part,
-                                    float* m_part, float* lse_part, void* workspace,
-                                    size_t workspace_bytes, void* hip_stream);
+                                    const void* v_prefix, const uint8_t* head_mask,
+                                    int32_t n_active_heads, float* o_part, float* m_part,
+                                    float* lse_part, void* workspace, size_t workspace_bytes,
+                                    void* hip_stream);
 
 /*
  * Paged prefix cache with per-sequence prefix lengths: the deployment shape of the language-model

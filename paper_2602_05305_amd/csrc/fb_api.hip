@@ -44,8 +44,26 @@ float eff_scale(const fb_shape* s) { return s->scale > 0.f ? s->scale : 1.0f / s
 
 long long rows_of(const fb_shape* s) { return (long long)s->batch * s->n_q_heads * s->block_len; }
 
-int auto_splits(const fb_shape* s) {
+int auto_splits(const fb_shape* s, int active_heads = 0) {
   const int tiles = (s->prefix_len + fb::kKeyTile - 1) / fb::kKeyTile;
+  if (s->dtype == FB_BF16 && active_heads > 0 && active_heads < s->n_q_heads) {
+    // Per-head refresh with a hint: only the KV groups of flagged heads do work (at most
+    // min(Hkv, active) of them per batch element).  8-wavefront workgroups, one per CU; among the two
+    // split counts around 256 / groups take the one with the shorter critical path
+    // (rounds of 256 workgroups x tiles per split), never fewer than 8 tiles per split.
+    const int G = s->n_q_heads / s->n_kv_heads;
+    const long long kvg = active_heads < s->n_kv_heads ? active_heads : s->n_kv_heads;
+    const long long groups = (long long)s->batch * kvg * ((G * s->block_len + fb::kRowsPerWgBf16 - 1) / fb::kRowsPerWgBf16);
+    long long best = 1, best_cost = -1;
+    const long long lo = 256 / groups > 1 ? 256 / groups : 1;
+    for (long long ns = lo; ns <= lo + 1; ++ns) {
+      if (ns > 1 && tiles < 8 * ns) continue;
+      if (ns > FB_MAX_SPLITS) continue;
+      const long long cost = ((groups * ns + 255) / 256) * ((tiles + ns - 1) / ns);
+      if (best_cost < 0 || cost < best_cost) { best = ns; best_cost = cost; }
+    }
+    return (int)best;
+  }
   if (s->dtype == FB_BF16) {
     // Every split costs a 128-row fp32 partial written and read back, so splits are as few as
     // still fill the GPU.
@@ -214,7 +232,7 @@ namespace {
 
 fb_status external_partial_impl(const fb_shape* shape, const void* q, const void* k_prefix,
                                 const void* v_prefix, const fb_paged_kv* paged, const uint8_t* head_mask,
-                                bool use_head_mask, float* o_part, float* m_part, float* lse_part,
+                                bool use_head_mask, int n_active_heads, float* o_part, float* m_part, float* lse_part,
                                 int32_t n_splits, void* workspace, size_t workspace_bytes,
                                 void* ev_begin, void* ev_attn_end, void* ev_end, void* hip_stream) {
   fb_status st = check_shape(shape);
@@ -235,7 +253,8 @@ fb_status external_partial_impl(const fb_shape* shape, const void* q, const void
   if (!aligned16(q) || !aligned16(k_prefix) || !aligned16(v_prefix) || !aligned16(o_part) ||
       !aligned16(m_part) || !aligned16(lse_part) || !aligned16(workspace))
     return FB_ERR_ALIGN;
-  const int ns = n_splits > 0 ? n_splits : (paged ? paged_splits(shape) : auto_splits(shape));
+  if (n_active_heads < 0) return FB_ERR_SHAPE;
+  const int ns = n_splits > 0 ? n_splits : (paged ? paged_splits(shape) : auto_splits(shape, n_active_heads));
   const WsLayout w = ws_layout(shape, ns, 1, 0);
   if (!workspace || workspace_bytes < w.total) return FB_ERR_WORKSPACE;
 
@@ -287,15 +306,20 @@ fb_status fb_external_partial_prof(const fb_shape* shape, const void* q, const v
                                    const void* v_prefix, float* o_part, float* m_part, float* lse_part,
                                    int32_t n_splits, void* workspace, size_t workspace_bytes,
                                    void* ev_begin, void* ev_attn_end, void* ev_end, void* hip_stream) {
-  return external_partial_impl(shape, q, k_prefix, v_prefix, nullptr, nullptr, false, o_part, m_part, lse_part, n_splits,
+  return external_partial_impl(shape, q, k_prefix, v_prefix, nullptr, nullptr, false, 0, o_part, m_part, lse_part, n_splits,
                                workspace, workspace_bytes, ev_begin, ev_attn_end, ev_end, hip_stream);
 }
 
+int32_t fb_external_heads_splits(const fb_shape* shape, int32_t n_active_heads) {
+  if (check_shape(shape) != FB_OK || n_active_heads < 0) return 0;
+  return auto_splits(shape, n_active_heads);
+}
+
 fb_status fb_external_partial_heads(const fb_shape* shape, const void* q, const void* k_prefix,
-                                    const void* v_prefix, const uint8_t* head_mask, float* o_part,
-                                    float* m_part, float* lse_part, void* workspace, size_t workspace_bytes,
-                                    void* hip_stream) {
-  return external_partial_impl(shape, q, k_prefix, v_prefix, nullptr, head_mask, true, o_part, m_part, lse_part, 0,
+                                    const void* v_prefix, const uint8_t* head_mask, int32_t n_active_heads,
+                                    float* o_part, float* m_part, float* lse_part, void* workspace,
+                                    size_t workspace_bytes, void* hip_stream) {
+  return external_partial_impl(shape, q, k_prefix, v_prefix, nullptr, head_mask, true, n_active_heads, o_part, m_part, lse_part, 0,
                                workspace, workspace_bytes, nullptr, nullptr, nullptr, hip_stream);
 }
 
@@ -303,7 +327,7 @@ fb_status fb_external_partial_paged(const fb_shape* shape, const void* q, const 
                                     float* m_part, float* lse_part, int32_t n_splits, void* workspace,
                                     size_t workspace_bytes, void* hip_stream) {
   if (!kv) return FB_ERR_NULL;
-  return external_partial_impl(shape, q, nullptr, nullptr, kv, nullptr, false, o_part, m_part, lse_part, n_splits,
+  return external_partial_impl(shape, q, nullptr, nullptr, kv, nullptr, false, 0, o_part, m_part, lse_part, n_splits,
                                workspace, workspace_bytes, nullptr, nullptr, nullptr, hip_stream);
 }
 

@@ -325,10 +325,17 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
   } else {
     const int bid = blockIdx.x, q8 = nwg / 8, r8 = nwg % 8;
     const int xcd = bid % 8, j = bid / 8;
-    const int w = (xcd < r8 ? xcd * (q8 + 1) : r8 * (q8 + 1) + (xcd - r8) * q8) + j;
+    int w = (xcd < r8 ? xcd * (q8 + 1) : r8 * (q8 + 1) + (xcd - r8) * q8) + j;
+    if constexpr (MODE == kPassDenseHeads) {
+      // Per-head refresh over many row tiles: whole heads drop out, so a head's row tiles are dealt
+      // round-robin over the XCDs (each XCD's L2 then holds that head's K/V stream once) instead of
+      // filling one XCD, which would leave the XCDs of unflagged heads idle.
+      if (p.div_rowtiles.d > 1) w = bid;
+    }
     rest = fastdiv((uint32_t)w, p.div_rowtiles);
     rt = w - (int)(rest * p.div_rowtiles.d);
   }
+  const uint32_t unit = rest;   // (batch, KV head, split) index: the same for all row tiles that share K/V
   int split = 0;
   if constexpr (MODE != kPassInternal) {
     const uint32_t r2 = fastdiv(rest, p.div_nsplit);
@@ -425,9 +432,12 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
     // is a chain of cold latencies (instruction fetch, TLB, HBM), so the longest one starts first.
     // Tiles are visited in a rotated order (start offset differs per workgroup): workgroups that
     // run in lockstep would otherwise all read the same offset of their 2^k-strided chunks, i.e.
-    // the same HBM channels, at the same time.  The statistics do not depend on the tile order.
+    // the same HBM channels, at the same time.  Row tiles of one unit share the offset: they run side
+    // by side on one XCD, and walking the same K/V tiles at the same time is what lets its L2 serve
+    // all but the first of them.  The statistics do not depend on the tile order.
     const int ntiles = tr.end - tr.begin;
-    const int rot = ntiles > 0 ? (int)((blockIdx.x * 13u + (blockIdx.x >> 5) * 7u) % (unsigned)ntiles) : 0;
+    const uint32_t rsrc = (p.div_rowtiles.d == 1) ? blockIdx.x : unit;
+    const int rot = ntiles > 0 ? (int)((rsrc * 13u + (rsrc >> 5) * 7u) % (unsigned)ntiles) : 0;
     auto tile_entry = [&](int i) -> int {   // i-th tile of this wavefront group
       int j = TG * i + (kSetSplit ? 0 : grp) + rot;
       if (j >= ntiles) j -= ntiles;
@@ -828,7 +838,9 @@ hipError_t launch_d(const PassParams& p, PassMode mode, hipStream_t s) {
       return launch_one<D, kPassSparseRefresh, kKeyTile, 1, 2>(p, s);
     case kPassDenseHeads: {
       const int tiles = (p.nkeys + kKeyTile - 1) / kKeyTile;
-      if (p.nsplit > 1 && tiles >= 8 * p.nsplit) return launch_one<D, kPassDenseHeads, kKeyTile, 1, 2>(p, s);
+      // 8-wavefront workgroups also without splits: workgroups of unflagged heads leave at once, and the
+      // remaining ones should each be able to use a whole CU
+      if (tiles >= 8 * p.nsplit) return launch_one<D, kPassDenseHeads, kKeyTile, 1, 2>(p, s);
       return launch_one<D, kPassDenseHeads, kKeyTile, 1, 1>(p, s);
     }
     case kPassRefreshFused: {

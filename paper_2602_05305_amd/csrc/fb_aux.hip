@@ -449,17 +449,25 @@ __global__ __launch_bounds__(256) void head_similarity_kernel(const float* __res
 }  // namespace
 
 // order[r] = index of the sequence with the r-th longest prefix (ties: lower index first).  Rank by
-// counting: B is a batch size, so the B^2 comparisons are a few microseconds at most.
+// counting: B is a batch size, so B^2 comparisons are cheap; the lengths are staged through LDS in
+// chunks of 256 so that the kernel is one memory round trip per chunk, not one per comparison.
 __global__ __launch_bounds__(256) void seq_order_kernel(const int32_t* __restrict__ lens, int32_t* __restrict__ order, int B) {
+  __shared__ int chunk[256];
   const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= B) return;
-  const int li = lens[i];
+  const int li = (i < B) ? lens[i] : 0;
   int rank = 0;
-  for (int j = 0; j < B; ++j) {
-    const int lj = lens[j];
-    rank += (lj > li || (lj == li && j < i)) ? 1 : 0;
+  for (int j0 = 0; j0 < B; j0 += 256) {
+    const int j = j0 + threadIdx.x;
+    __syncthreads();
+    chunk[threadIdx.x] = (j < B) ? lens[j] : 0;
+    __syncthreads();
+    const int n = min(256, B - j0);
+    for (int t = 0; t < n; ++t) {
+      const int lj = chunk[t];
+      rank += (lj > li || (lj == li && j0 + t < i)) ? 1 : 0;
+    }
   }
-  order[rank] = i;
+  if (i < B) order[rank] = i;
 }
 
 hipError_t launch_seq_order(const int32_t* prefix_lens, int32_t* seq_order, int B, hipStream_t s) {

@@ -49,7 +49,9 @@ _SIGNATURES = {
     "fb_external_partial": (c_int, [POINTER(fb_shape)] + [c_void_p] * 7 + [c_size_t, c_void_p]),
     "fb_external_partial_ex": (c_int, [POINTER(fb_shape)] + [c_void_p] * 6 + [c_int32, c_void_p, c_size_t, c_void_p]),
     "fb_external_partial_prof": (c_int, [POINTER(fb_shape)] + [c_void_p] * 6 + [c_int32, c_void_p, c_size_t] + [c_void_p] * 4),
-    "fb_external_partial_heads": (c_int, [POINTER(fb_shape)] + [c_void_p] * 8 + [c_size_t, c_void_p]),
+    "fb_external_heads_splits": (c_int32, [POINTER(fb_shape), c_int32]),
+    "fb_external_partial_heads": (c_int, [POINTER(fb_shape)] + [c_void_p] * 4 + [c_int32] + [c_void_p] * 4
+                                  + [c_size_t, c_void_p]),
     "fb_paged_splits": (c_int32, [POINTER(fb_shape)]),
     "fb_external_partial_paged": (c_int, [POINTER(fb_shape), c_void_p, POINTER(fb_paged_kv)] + [c_void_p] * 3
                                   + [c_int32, c_void_p, c_size_t, c_void_p]),
@@ -152,9 +154,15 @@ def fb_external_partial_prof(shape, q, k_prefix, v_prefix, o_part, m_part, lse_p
     _check(st, "fb_external_partial_prof")
 
 
-def fb_external_partial_heads(shape, q, k_prefix, v_prefix, head_mask, o_part, m_part, lse_part, workspace, stream=None):
+def fb_external_heads_splits(shape, n_active_heads) -> int:
+    return int(load_library().fb_external_heads_splits(ctypes.byref(shape), n_active_heads))
+
+
+def fb_external_partial_heads(shape, q, k_prefix, v_prefix, head_mask, o_part, m_part, lse_part, workspace,
+                              n_active_heads=0, stream=None):
     st = load_library().fb_external_partial_heads(ctypes.byref(shape), _ptr(q), _ptr(k_prefix), _ptr(v_prefix),
-                                                  _ptr(head_mask), _ptr(o_part), _ptr(m_part), _ptr(lse_part),
+                                                  _ptr(head_mask), n_active_heads, _ptr(o_part), _ptr(m_part),
+                                                  _ptr(lse_part),
                                                   _ptr(workspace), workspace.numel() * workspace.element_size(),
                                                   _stream(stream))
     _check(st, "fb_external_partial_heads")

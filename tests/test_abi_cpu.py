@@ -112,9 +112,18 @@ def test_external_partial_heads_error_paths():
     s = _ok_shape()
     ws_bytes = fb.fb_workspace_bytes(s)
     call = lib.fb_external_partial_heads
-    assert call(ctypes.byref(s), FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE, ws_bytes, None) == fb.FB_ERR_NULL
-    assert call(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, TOO_SMALL, None) == fb.FB_ERR_WORKSPACE
-    assert call(ctypes.byref(s), FAKE, FAKE, FAKE, ODD, ODD, FAKE, FAKE, FAKE, ws_bytes, None) == fb.FB_ERR_ALIGN  # mask may be unaligned, o may not
+    assert call(ctypes.byref(s), FAKE, FAKE, FAKE, None, 0, FAKE, FAKE, FAKE, FAKE, ws_bytes, None) == fb.FB_ERR_NULL
+    assert call(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, 0, FAKE, FAKE, FAKE, FAKE, TOO_SMALL, None) == fb.FB_ERR_WORKSPACE
+    assert call(ctypes.byref(s), FAKE, FAKE, FAKE, ODD, 0, ODD, FAKE, FAKE, FAKE, ws_bytes, None) == fb.FB_ERR_ALIGN  # mask may be unaligned, o may not
+    assert call(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, -1, FAKE, FAKE, FAKE, FAKE, ws_bytes, None) == fb.FB_ERR_SHAPE
+    # the hint only ever raises the split count, and only where few heads leave the GPU underfilled
+    video = _ok_shape(dtype="bf16", head_dim=128, n_q_heads=12, n_kv_heads=12, block_len=4680, prefix_len=37440)
+    assert fb.fb_external_heads_splits(video, 0) == fb.fb_external_splits(video) == 1
+    assert fb.fb_external_heads_splits(video, 12) == 1
+    assert fb.fb_external_heads_splits(video, 6) == 1            # 222 workgroups: one round either way
+    assert fb.fb_external_heads_splits(video, 3) == 2
+    assert fb.fb_external_heads_splits(video, 1) == 6            # 37 row tiles x 6 = 222 workgroups, one round
+    assert fb.fb_external_heads_splits(video, -1) == 0
 
 
 def _paged(**kw):

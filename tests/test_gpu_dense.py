@@ -148,14 +148,19 @@ def test_bf16_bitwise_reproducible():
 
 
 # ------------------------------------------------------------------ head-wise selective refresh
-@pytest.mark.parametrize("dtype,B,Hq,Hkv,d,P,Bq,mask", [
-    ("bf16", 1, 6, 6, 128, 700, 48, [1, 0, 0, 1, 1, 0]),                 # MHA (video-like): 3 of 6 heads refreshed
-    ("bf16", 1, 8, 2, 128, 2000, 32, [0, 0, 0, 0, 1, 0, 0, 1]),          # GQA: one KV group entirely off
-    ("bf16", 2, 4, 2, 128, 5000, 32, [1, 0, 0, 0, 0, 0, 1, 1]),          # batch 2, split-KV with wavefront groups
-    ("bf16", 1, 4, 4, 64, 300, 16, [0, 0, 0, 0]),                        # nothing refreshed: cache untouched
-    ("f32", 1, 4, 2, 64, 300, 6, [0, 1, 1, 0]),
+@pytest.mark.parametrize("dtype,B,Hq,Hkv,d,P,Bq,mask,hint", [
+    ("bf16", 1, 6, 6, 128, 700, 48, [1, 0, 0, 1, 1, 0], 0),              # MHA (video-like): 3 of 6 heads refreshed
+    ("bf16", 1, 6, 6, 128, 700, 48, [1, 0, 0, 1, 1, 0], 3),              # the same with the hint (more splits)
+    ("bf16", 1, 6, 6, 128, 2100, 300, [0, 0, 0, 0, 1, 0], 1),            # several row tiles, one head, hint
+    ("bf16", 1, 6, 6, 128, 2100, 300, [1, 1, 0, 0, 1, 0], 1),            # hint too low: slower, still right
+    ("bf16", 1, 8, 2, 128, 2000, 32, [0, 0, 0, 0, 1, 0, 0, 1], 0),       # GQA: one KV group entirely off
+    ("bf16", 1, 8, 2, 128, 2000, 32, [0, 0, 0, 0, 1, 0, 0, 1], 2),
+    ("bf16", 2, 4, 2, 128, 5000, 32, [1, 0, 0, 0, 0, 0, 1, 1], 0),       # batch 2, split-KV with wavefront groups
+    ("bf16", 1, 4, 4, 64, 300, 16, [0, 0, 0, 0], 0),                     # nothing refreshed: cache untouched
+    ("f32", 1, 4, 2, 64, 300, 6, [0, 1, 1, 0], 0),
+    ("f32", 1, 4, 2, 64, 300, 6, [0, 1, 1, 0], 2),
 ])
-def test_head_wise_selective_refresh(dtype, B, Hq, Hkv, d, P, Bq, mask):
+def test_head_wise_selective_refresh(dtype, B, Hq, Hkv, d, P, Bq, mask, hint):
     """fb_external_partial_heads: flagged heads get the fresh partial of the new query, the others
     keep the cached one bit for bit; the merged step output follows."""
     w = _wl(dtype, B, Hq, Hkv, d, P, Bq, S=2, R=2)
@@ -163,7 +168,7 @@ def test_head_wise_selective_refresh(dtype, B, Hq, Hkv, d, P, Bq, mask):
     Kp, Vp = wl.make_prefix(w, 61)
     (Q0, _, _), (Q1, Kb1, Vb1) = wl.make_block_steps(w, 61)
     shape = T.shape_of(w)
-    ws = T.workspace(shape)
+    ws = T.workspace(shape, n_splits=max(fb.fb_external_splits(shape), fb.fb_external_heads_splits(shape, hint)))
     kp, vp = T.to_dev(Kp, dtype), T.to_dev(Vp, dtype)
     part = T.Partial(w)
     fb.fb_external_partial(shape, T.to_dev(Q0, dtype), kp, vp, part.o, part.m, part.lse, ws)
@@ -171,7 +176,7 @@ def test_head_wise_selective_refresh(dtype, B, Hq, Hkv, d, P, Bq, mask):
     before = {k: v.clone() for k, v in (("o", part.o), ("m", part.m), ("lse", part.lse))}
     hm = torch.tensor(mask, dtype=torch.uint8, device=T.DEV).reshape(B, Hq)
     q1 = T.to_dev(Q1, dtype)
-    fb.fb_external_partial_heads(shape, q1, kp, vp, hm, part.o, part.m, part.lse, ws)
+    fb.fb_external_partial_heads(shape, q1, kp, vp, hm, part.o, part.m, part.lse, ws, hint)
     out = torch.empty_like(q1)
     fb.fb_internal_merge(shape, q1, T.to_dev(Kb1, dtype), T.to_dev(Vb1, dtype), part.o, part.m, part.lse, out, None)
     torch.cuda.synchronize()
