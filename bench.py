@@ -245,8 +245,15 @@ def cpu_baseline(w, budget_s=12.0):
 
 
 def _ev_median_us(torch, fn, reps=15, warm=3):
-    for _ in range(warm):
+    """Median event-timed duration of fn.  Clocks take a while to settle on a freshly idle GPU (the
+    first ~10 ms of a compute-bound kernel run measurably slower), so warm up for at least 20 ms."""
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    n = 0
+    while n < warm or time.perf_counter() - t0 < 0.02:
         fn()
+        torch.cuda.synchronize()
+        n += 1
     torch.cuda.synchronize()
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
     for a, b in evs:

@@ -116,7 +116,7 @@ def test_external_partial_heads_error_paths():
     assert call(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, 0, FAKE, FAKE, FAKE, FAKE, TOO_SMALL, None) == fb.FB_ERR_WORKSPACE
     assert call(ctypes.byref(s), FAKE, FAKE, FAKE, ODD, 0, ODD, FAKE, FAKE, FAKE, ws_bytes, None) == fb.FB_ERR_ALIGN  # mask may be unaligned, o may not
     assert call(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, -1, FAKE, FAKE, FAKE, FAKE, ws_bytes, None) == fb.FB_ERR_SHAPE
-    # the hint only ever raises the split count, and only where few heads leave the GPU underfilled
+    # the hint changes the split count where few heads leave the GPU underfilled
     video = _ok_shape(dtype="bf16", head_dim=128, n_q_heads=12, n_kv_heads=12, block_len=4680, prefix_len=37440)
     assert fb.fb_external_heads_splits(video, 0) == fb.fb_external_splits(video) == 1
     assert fb.fb_external_heads_splits(video, 12) == 1
