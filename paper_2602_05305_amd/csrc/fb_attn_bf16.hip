@@ -122,10 +122,11 @@ __device__ __forceinline__ void store_v(const u32x4 (&r)[4], unsigned char* __re
     for (int w = 0; w < 4; ++w) {
       const uint32_t a = r[0][w], b = r[1][w], c = r[2][w], d = r[3][w];
       u32x2 lo, hi;   // column 2w (low halves) and 2w+1 (high halves) of the 4 keys
-      lo.x = (a & 0xffffu) | (b << 16);
-      lo.y = (c & 0xffffu) | (d << 16);
-      hi.x = (a >> 16) | (b & 0xffff0000u);
-      hi.y = (c >> 16) | (d & 0xffff0000u);
+      // one byte-permute each: {first.lo16, second.lo16} and {first.hi16, second.hi16}
+      lo.x = __builtin_amdgcn_perm(b, a, 0x05040100u);
+      lo.y = __builtin_amdgcn_perm(d, c, 0x05040100u);
+      hi.x = __builtin_amdgcn_perm(b, a, 0x07060302u);
+      hi.y = __builtin_amdgcn_perm(d, c, 0x07060302u);
       const int dcol = doct * 8 + 2 * w;
       *(u32x2*)(Vt + dcol * C::VSTR + slot * 2) = lo;
       *(u32x2*)(Vt + (dcol + 1) * C::VSTR + slot * 2) = hi;
