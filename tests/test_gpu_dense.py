@@ -270,6 +270,13 @@ def _compare_refresh_step(w, seed):
     ("bf16", 1, 4, 4, 128, 2048, 200),          # several row tiles and a block of several key tiles
     ("bf16", 1, 8, 2, 128, 0, 32),
     ("bf16", 1, 8, 2, 128, 300, 4),
+    # small blocks with many prefix splits, both storage types
+    ("f32", 1, 4, 2, 64, 1024, 16),
+    ("f32", 1, 2, 2, 128, 2048 + 9, 5),
+    ("bf16", 2, 4, 4, 64, 4096, 16),
+    ("bf16", 1, 32, 8, 128, 4096 + 33, 64),
+    ("bf16", 1, 32, 8, 128, 4096, 65),          # block of two key tiles, the second ragged
+    ("bf16", 1, 8, 8, 128, 8192, 1),
 ])
 def test_fused_refresh_step(dtype, B, Hq, Hkv, d, P, Bq):
     _compare_refresh_step(_wl(dtype, B, Hq, Hkv, d, P, Bq), seed=51)
