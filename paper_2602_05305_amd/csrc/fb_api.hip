@@ -268,7 +268,9 @@ fb_status external_partial_impl(const fb_shape* shape, const void* q, const void
     mode = fb::kPassDensePaged;
     p.block_table = paged->block_table; p.prefix_lens = paged->prefix_lens;
     p.page_size = paged->page_size; p.max_pages = paged->max_pages; p.num_pages = paged->num_pages;
-    if (shape->batch > 1) {
+    if (shape->batch > 1 && shape->batch <= 128 && shape->dtype == FB_BF16) {
+      p.order_inline = 1;       // the bf16 kernel ranks up to 128 sequences in its prologue
+    } else if (shape->batch > 1) {
       p.seq_order = (int32_t*)(ws + w.order);
       hipError_t eo = fb::launch_seq_order(paged->prefix_lens, (int32_t*)(ws + w.order), shape->batch, stream);
       if (eo != hipSuccess) return hip_fail(eo);

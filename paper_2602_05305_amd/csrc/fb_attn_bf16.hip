@@ -346,7 +346,29 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
   int b = (int)fastdiv(rest, p.div_hkv);
   const int kvh = (int)(rest - (uint32_t)b * p.div_hkv.d);
   if constexpr (MODE == kPassDensePaged) {
-    if (p.seq_order != nullptr) b = p.seq_order[b];
+    if (p.seq_order != nullptr) {
+      b = p.seq_order[b];
+    } else if (p.order_inline) {
+      // Small batch: this workgroup finds the sequence with the b-th longest prefix itself (ties: lower
+      // index first) instead of waiting for a separate ordering kernel: lengths to LDS, one rank per
+      // thread, the thread whose sequence has rank b publishes it.  The LDS is not yet in use.
+      int* lens_s = (int*)smem_all;
+      __shared__ int chosen;
+      const int nthr = 256 * NG;
+      for (int i = threadIdx.x; i < p.B; i += nthr) lens_s[i] = p.prefix_lens[i];
+      __syncthreads();
+      for (int i = threadIdx.x; i < p.B; i += nthr) {
+        const int li = lens_s[i];
+        int rank = 0;
+        for (int j = 0; j < p.B; ++j) {
+          const int lj = lens_s[j];
+          rank += (lj > li || (lj == li && j < i)) ? 1 : 0;
+        }
+        if (rank == b) chosen = i;
+      }
+      __syncthreads();
+      b = chosen;
+    }
   }
   const int bk = b * p.Hkv + kvh;
   int nkeys_pass = p.nkeys;

@@ -73,6 +73,7 @@ struct PassParams {
   const int32_t* prefix_lens; // [B] keys per sequence (<= nkeys)
   int page_size, max_pages, num_pages;
   const int32_t* seq_order;   // [B] sequences by descending prefix length (longest work is dispatched first), or null
+  int order_inline;           // seq_order == null and 1: each workgroup ranks the (few) sequences itself
   // fused refresh pass: the block's own K/V [B,Hkv,Bq,D] go into partial set 1 (bf16: second phase of the last
   // split's workgroup, which gets blk_cost prefix tiles fewer; fp32: one extra split index)
   const void* k2; const void* v2; int blk_cost;

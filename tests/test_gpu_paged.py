@@ -62,6 +62,14 @@ def test_paged_external_matches_oracle(dtype, B, Hq, Hkv, d, P, Bq, page, lens):
     _run_paged(_wl(dtype, B, Hq, Hkv, d, P, Bq), seed=41, page_size=page, lens=lens)
 
 
+def test_paged_large_batch_uses_the_ordering_kernel():
+    """More than 128 sequences: the longest-first order comes from the separate ranking kernel
+    (smaller batches rank inside the attention kernel).  Lengths with many ties."""
+    rng = np.random.default_rng(9)
+    lens = rng.integers(0, 5, size=130) * 64 + rng.integers(0, 2, size=130) * 17
+    _run_paged(_wl("bf16", 130, 2, 1, 64, 320, 8), seed=44, page_size=64, lens=np.minimum(lens, 320))
+
+
 @pytest.mark.parametrize("n_splits", [1, 3, 16])
 def test_paged_split_counts(n_splits):
     """Every sequence's own tile list is cut into n_splits ranges; short sequences leave some empty."""
