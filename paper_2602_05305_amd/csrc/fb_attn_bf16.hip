@@ -10,6 +10,12 @@
 //   byte is fetched once per pass); wavefront w owns rows [32w, 32w+32).
 //   grid = batch * Hkv * row_tiles * nsplit workgroups, remapped so that workgroups that share
 //   K/V (row tiles of one KV head) land on the same XCD / L2.
+//   Variants of the one kernel template <D, MODE, KT, WS, NG> (picked on the host, launch_d):
+//   NG = 2: 8 wavefronts, two groups stream interleaved tiles and merge through LDS (or, in the
+//   sparse refresh pass, own one accumulator set each); WS = 2/4: wavefronts share 32 rows and
+//   split the output columns (few rows per KV group); KT = 32: internal pass over <= 32 keys.
+//   MODE: dense external, internal + merge epilogue, sparse refresh, sparse reuse, per-head
+//   refresh, paged external, fused refresh step (PassMode in fb_kernels.h).
 // Per 64-key tile
 //   K tile  -> LDS row-major [key][D] (row stride D*2+16 bytes: conflict-free ds_read_b128)
 //   V tile  -> LDS transposed [d][key slot] (stride 64*2+16 bytes); the transpose happens in
