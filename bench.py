@@ -322,7 +322,9 @@ def sparse_extra(torch, fb, wl):
         fb.fb_sparse_external_residual(d.shape, mode, q, d.K[s], d.V[s], w.key_block, w.topk, idx, ro, rm, rl,
                                        d.o, d.m, d.lse, ws)
     t_refresh = _ev_median_us(torch, lambda: call(fb.FB_SPARSE_REFRESH))
-    t_reuse = _ev_median_us(torch, lambda: call(fb.FB_SPARSE_REUSE))
+    t_reuse_rebuild = _ev_median_us(torch, lambda: call(fb.FB_SPARSE_REUSE))
+    # reuse steps of a block keep the refresh step's selection: no mask rebuild
+    t_reuse = _ev_median_us(torch, lambda: call(fb.FB_SPARSE_REUSE_SAME_SELECTION))
     t_dense = _ev_median_us(torch, lambda: fb.fb_external_partial(d.shape, q, d.K[i[0] % 2], d.V[i[0] % 2], d.o, d.m, d.lse, ws))
     sel = idx.cpu().numpy()
     G = w.n_q_heads // w.n_kv_heads
@@ -332,6 +334,7 @@ def sparse_extra(torch, fb, wl):
             "pool_keys_us": round(t_pool, 1), "select_topk_us": round(t_sel, 1),
             "select_topk_mass_us": round(t_mass, 1),
             "sparse_refresh_call_us": round(t_refresh, 1), "sparse_reuse_call_us": round(t_reuse, 1),
+            "sparse_reuse_call_rebuilding_masks_us": round(t_reuse_rebuild, 1),
             "dense_external_call_us": round(t_dense, 1),
             "union_fraction_of_prefix": round(union / (nblk * w.n_kv_heads), 3),
             "reuse_union_bytes": union_bytes, "reuse_GBps_vs_union_bytes": round(union_bytes / t_reuse / 1e3, 1),

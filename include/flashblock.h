@@ -71,7 +71,8 @@ typedef enum fb_dtype { FB_F32 = 0, FB_BF16 = 1 } fb_dtype;
 
 typedef enum fb_sparse_mode {
   FB_SPARSE_REFRESH = 0,  /* stream the whole prefix: write the residual AND selected(+)residual */
-  FB_SPARSE_REUSE = 1     /* stream selected key blocks only, fold in the cached residual */
+  FB_SPARSE_REUSE = 1,    /* stream selected key blocks only, fold in the cached residual */
+  FB_SPARSE_REUSE_SAME_SELECTION = 2   /* FB_SPARSE_REUSE with the selection of the previous call (see below) */
 } fb_sparse_mode;
 
 /* Problem shape.  Plain data, host memory, caller-owned.  struct_size = sizeof(fb_shape). */
@@ -294,6 +295,12 @@ fb_status fb_select_topk_mass(const fb_shape* shape, const void* q, const void* 
  *   mode FB_SPARSE_REUSE: only key blocks selected by at least one query head of a KV group
  *     are read; the selected partial is recomputed with the current q and folded with the
  *     cached residual (res_*: read-only) into (o_part, m_part, lse_part).
+ *   mode FB_SPARSE_REUSE_SAME_SELECTION: FB_SPARSE_REUSE without rebuilding the per-KV-group
+ *     selection masks: the selection is frozen between refresh steps, and the masks that the
+ *     preceding FB_SPARSE_REFRESH / FB_SPARSE_REUSE call (same shape, key_block, topk, same
+ *     workspace, earlier on the same stream) left in the workspace are used again.  sel_idx is
+ *     ignored.  The caller guarantees that nothing else wrote the workspace in between; this is
+ *     the one case in which workspace contents carry over from call to call.
  * The result is external-shaped and feeds fb_internal_merge unchanged.
  *   sel_idx [B,Hq,topk] int32, entries in [0, n_blocks) or negative (ignored); duplicates
  *   are allowed and count once.  topk = 0 (then sel_idx may be NULL) selects nothing.

@@ -537,13 +537,16 @@ fb_status fb_sparse_external_residual(const fb_shape* shape, int32_t mode, const
                                       void* workspace, size_t workspace_bytes, void* hip_stream) {
   fb_status st = check_shape(shape);
   if (st != FB_OK) return st;
-  if (mode != FB_SPARSE_REFRESH && mode != FB_SPARSE_REUSE) return FB_ERR_SHAPE;
+  if (mode != FB_SPARSE_REFRESH && mode != FB_SPARSE_REUSE && mode != FB_SPARSE_REUSE_SAME_SELECTION)
+    return FB_ERR_SHAPE;
+  const bool keep_masks = mode == FB_SPARSE_REUSE_SAME_SELECTION;
+  if (keep_masks) mode = FB_SPARSE_REUSE;
   int nblk = 0;
   st = check_key_block(shape, key_block, topk, &nblk);
   if (st != FB_OK) return st;
   if (!q || !res_o || !res_m || !res_lse || !o_part || !m_part || !lse_part) return FB_ERR_NULL;
   if (shape->prefix_len > 0 && (!k_prefix || !v_prefix)) return FB_ERR_NULL;
-  if (topk > 0 && !sel_idx) return FB_ERR_NULL;
+  if (topk > 0 && !sel_idx && !keep_masks) return FB_ERR_NULL;
   if (!aligned16(q) || !aligned16(k_prefix) || !aligned16(v_prefix) || !aligned16(sel_idx) ||
       !aligned16(res_o) || !aligned16(res_m) || !aligned16(res_lse) || !aligned16(o_part) ||
       !aligned16(m_part) || !aligned16(lse_part) || !aligned16(workspace))
@@ -563,7 +566,7 @@ fb_status fb_sparse_external_residual(const fb_shape* shape, int32_t mode, const
   mp.B = shape->batch; mp.Hq = shape->n_q_heads; mp.Hkv = shape->n_kv_heads;
   mp.G = shape->n_q_heads / shape->n_kv_heads; mp.topk = topk; mp.nblk = nblk;
   hipError_t e = hipSuccess;
-  if (nblk > 0) {
+  if (nblk > 0 && !keep_masks) {
     e = fb::launch_build_masks(mp, stream);
     if (e != hipSuccess) return hip_fail(e);
   }

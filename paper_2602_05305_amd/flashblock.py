@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libflashblock.so")
 
 FB_OK, FB_ERR_NULL, FB_ERR_SHAPE, FB_ERR_DTYPE, FB_ERR_ALIGN, FB_ERR_WORKSPACE, FB_ERR_UNSUPPORTED, FB_ERR_HIP = range(8)
 FB_F32, FB_BF16 = 0, 1
-FB_SPARSE_REFRESH, FB_SPARSE_REUSE = 0, 1
+FB_SPARSE_REFRESH, FB_SPARSE_REUSE, FB_SPARSE_REUSE_SAME_SELECTION = 0, 1, 2
 FB_MAX_SPLITS = 256
 
 

@@ -105,7 +105,7 @@ def run_dense_block_gpu(w: wl.Workload, Kp, Vp, steps, R=None, n_splits=0, scale
     return res
 
 
-def run_sparse_block_gpu(w: wl.Workload, Kp, Vp, steps, idx_per_refresh=None, R=None, scale=0.0):
+def run_sparse_block_gpu(w: wl.Workload, Kp, Vp, steps, idx_per_refresh=None, R=None, scale=0.0, same_selection=False):
     """Sparse path.  idx_per_refresh: dict refresh-step -> int32 [B,Hq,k] (the oracle's selection);
     None = select on the GPU with fb_pool_keys + fb_select_topk."""
     R = w.refresh if R is None else R
@@ -128,8 +128,13 @@ def run_sparse_block_gpu(w: wl.Workload, Kp, Vp, steps, idx_per_refresh=None, R=
                 idx = torch.empty((w.batch, w.n_q_heads, max(w.topk, 1)), device=DEV, dtype=torch.int32)
                 fb.fb_select_topk(shape, q, pooled, w.key_block, w.topk, idx)
         k_arg = idx.shape[2] if (idx_per_refresh is not None) else w.topk
-        fb.fb_sparse_external_residual(shape, fb.FB_SPARSE_REFRESH if refresh else fb.FB_SPARSE_REUSE, q, kp, vp,
-                                       w.key_block, k_arg, idx if k_arg > 0 else None, resid.o, resid.m, resid.lse,
+        if refresh:
+            mode = fb.FB_SPARSE_REFRESH
+        else:       # same_selection: the masks the refresh call left in the workspace serve every reuse step
+            mode = fb.FB_SPARSE_REUSE_SAME_SELECTION if same_selection else fb.FB_SPARSE_REUSE
+        keep = mode == fb.FB_SPARSE_REUSE_SAME_SELECTION
+        fb.fb_sparse_external_residual(shape, mode, q, kp, vp, w.key_block, k_arg,
+                                       idx if (k_arg > 0 and not keep) else None, resid.o, resid.m, resid.lse,
                                        ext.o, ext.m, ext.lse, ws)
         out = torch.empty_like(q)
         lse = torch.empty(q.shape[:3], device=DEV, dtype=torch.float32)

@@ -192,7 +192,9 @@ def test_sparse_error_paths():
     ws_bytes = fb.fb_workspace_bytes(s, 64, 2)
     call = lib.fb_sparse_external_residual
     args = [FAKE] * 3 + [64, 2, FAKE] + [FAKE] * 6 + [FAKE, ws_bytes, None]
-    assert call(ctypes.byref(s), 2, *args) == fb.FB_ERR_SHAPE                       # bad mode
+    assert call(ctypes.byref(s), 3, *args) == fb.FB_ERR_SHAPE                       # bad mode
+    a = list(args); a[5] = None; a[13] = TOO_SMALL
+    assert call(ctypes.byref(s), 2, *a) == fb.FB_ERR_WORKSPACE                      # same-selection reuse takes no sel_idx
     a = list(args); a[3] = 48
     assert call(ctypes.byref(s), 0, *a) == fb.FB_ERR_UNSUPPORTED                    # key_block % 64
     a = list(args); a[3] = 0

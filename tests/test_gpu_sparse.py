@@ -220,3 +220,19 @@ def test_mass_selection_feeds_the_sparse_path():
     T.check_partial(tot.numpy(), orc.partial(Q, Kp, Vp), "bf16", "mass-selected refresh total")
     kmask = orc.selection_key_mask(idx.cpu().numpy(), w.prefix_len, w.key_block)
     T.check_partial(res.numpy(), orc.partial(Q, Kp, Vp, key_mask=~kmask), "bf16", "mass-selected residual")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_sparse_reuse_with_the_previous_calls_selection(dtype):
+    """FB_SPARSE_REUSE_SAME_SELECTION: reuse steps that take the selection masks the refresh call left
+    in the workspace give bit-identical results to reuse steps that rebuild them from sel_idx."""
+    w = _wl(dtype, 2, 8, 2, 128 if dtype == "bf16" else 64, 1500, 16, 64, 5, S=4, R=4)
+    Kp, Vp = wl.make_prefix(w, 67)
+    steps = wl.make_block_steps(w, 67)
+    idx = {0: orc.select_topk(steps[0][0], Kp, w.key_block, w.topk)}
+    a = T.run_sparse_block_gpu(w, Kp, Vp, steps, idx_per_refresh=idx)
+    b = T.run_sparse_block_gpu(w, Kp, Vp, steps, idx_per_refresh=idx, same_selection=True)
+    ora = orc.run_block_sparse(Kp, Vp, steps, w.refresh, w.key_block, w.topk)
+    for t in range(w.steps):
+        assert np.array_equal(a[t]["out"], b[t]["out"]) and np.array_equal(a[t]["lse"], b[t]["lse"]), t
+        T.assert_close(b[t]["out"], ora[t]["out"], dtype, f"same-selection step {t}")
