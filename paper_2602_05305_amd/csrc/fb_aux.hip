@@ -268,34 +268,35 @@ __device__ __forceinline__ uint32_t order_key(float x) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-// Workgroup-wide count of a predicate over key[0..nblk): per element one wavefront ballot and a
-// scalar popcount (no cross-lane data movement), then the four wavefront counts meet in LDS.
-template <typename Pred>
-__device__ __forceinline__ int block_count(const uint32_t* key, int nblk, int* sh4, int tid, Pred pred) {
-  int cnt = 0;
-  for (int c0 = 0; c0 < nblk; c0 += 256) {
-    const int c = c0 + tid;
-    const bool hit = (c < nblk) && pred(key[c < nblk ? c : 0]);
-    cnt += __popcll(__ballot(hit));
+// Exclusive prefix sum of one int per thread over a 256-thread workgroup: shuffles inside each
+// wavefront, wavefront totals through wtot[4] (two barriers; wtot may be reused afterwards).
+__device__ __forceinline__ int block_exclusive_prefix(int v, int* wtot, int tid) {
+  int inc = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int dn = __shfl_up(inc, o, 64);
+    if ((tid & 63) >= o) inc += dn;
   }
-  __syncthreads();                 // previous readers of sh4 are done
-  if ((tid & 63) == 0) sh4[tid >> 6] = cnt;
+  __syncthreads();                      // earlier readers of wtot are done
+  if ((tid & 63) == 63) wtot[tid >> 6] = inc;
   __syncthreads();
-  return sh4[0] + sh4[1] + sh4[2] + sh4[3];
+  int base = 0;
+  for (int wv = 0; wv < (tid >> 6); ++wv) base += wtot[wv];
+  return base + inc - v;
 }
 
 // grid (B*Hq), 256 threads, dynamic LDS: qbar[D] | red[256] | key[nblk] | flag[nblk]
 // Selection = the k largest scores, ties to the lower block index: the k-th largest key T is
-// found by bisection over its 32 bits (count(key >= candidate) per step), then blocks with
-// key > T are taken plus the first k - count(key > T) blocks with key == T in index order.
+// found by a 4-pass radix select over its bytes (256-bin LDS histogram of the keys that match the
+// digits fixed so far), then blocks with key > T are taken plus the first k - count(key > T)
+// blocks with key == T in index order.
 __global__ __launch_bounds__(256) void select_topk_kernel(const SelectParams p) {
   extern __shared__ __align__(16) float lds[];
   float* qbar = lds;
   float* red = qbar + p.D;
   uint32_t* key = (uint32_t*)(red + 256);
   int* flag = (int*)(key + p.nblk);
-  __shared__ int chunk_cnt[256];
-  __shared__ int sh4[4];
+  __shared__ int sel_digit, sel_rest, wtot[4];
 
   const int bh = blockIdx.x, b = bh / p.Hq, h = bh % p.Hq, kvh = h / p.G;
   const int D = p.D, tid = threadIdx.x, nblk = p.nblk;
@@ -313,52 +314,92 @@ __global__ __launch_bounds__(256) void select_topk_kernel(const SelectParams p) 
       if (p.score_out != nullptr) p.score_out[(size_t)bh * nblk + c] = s;
     }
   } else {
-  {  // mean over the block's query rows
-    const int d = tid % D, tl = tid / D, ntl = 256 / D;
-    float s = 0.f;
-    for (int r = tl; r < p.Bq; r += ntl) s += load_elem(p.q, ((size_t)bh * p.Bq + r) * D + d, p.is_bf16);
-    red[tid] = s;
-    __syncthreads();
-    if (tl == 0) {
-      for (int j = 1; j < ntl; ++j) s += red[j * D + d];
-      qbar[d] = s / (float)p.Bq;
+    {  // mean over the block's query rows
+      const int d = tid % D, tl = tid / D, ntl = 256 / D;
+      float s = 0.f;
+      for (int r = tl; r < p.Bq; r += ntl) s += load_elem(p.q, ((size_t)bh * p.Bq + r) * D + d, p.is_bf16);
+      red[tid] = s;
+      __syncthreads();
+      if (tl == 0) {
+        for (int j = 1; j < ntl; ++j) s += red[j * D + d];
+        qbar[d] = s / (float)p.Bq;
+      }
+      __syncthreads();
     }
-    __syncthreads();
-  }
-  const float* kp = p.k_pooled + (size_t)(b * p.Hkv + kvh) * nblk * D;
-  for (int c = tid; c < nblk; c += 256) {
-    const float4* kr = (const float4*)(kp + (size_t)c * D);
-    float s = 0.f;
-    for (int i = 0; i < D / 4; ++i) {
-      const float4 a = kr[i];
-      s = fmaf(a.x, qbar[4 * i], s);
-      s = fmaf(a.y, qbar[4 * i + 1], s);
-      s = fmaf(a.z, qbar[4 * i + 2], s);
-      s = fmaf(a.w, qbar[4 * i + 3], s);
+    // score = qbar . pooled key of the block.  A wavefront reads 64 consecutive 16-byte chunks per
+    // instruction (2 rows at D = 128, 4 at D = 64); a row's partial sums meet by xor-shuffles inside
+    // its lane group; 8 such loads are in flight per wavefront.
+    const float* kp = p.k_pooled + (size_t)(b * p.Hkv + kvh) * nblk * D;
+    const int cpr = D / 4, rpw = 64 / cpr;            // chunks per row, rows per wavefront instruction
+    const int lane = tid & 63, wave = tid >> 6;
+    const int c = lane % cpr, rsub = lane / cpr;
+    const float4 q4 = *(const float4*)(qbar + 4 * c);
+    constexpr int U = 8;
+    for (int r0 = wave * rpw; r0 < nblk; r0 += 4 * rpw * U) {
+      float part[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int r = min(r0 + u * 4 * rpw + rsub, nblk - 1);       // clamped: in bounds, result discarded
+        const float4 a = *(const float4*)(kp + (size_t)r * D + 4 * c);
+        part[u] = fmaf(a.w, q4.w, fmaf(a.z, q4.z, fmaf(a.y, q4.y, a.x * q4.x)));
+      }
+      for (int o = cpr / 2; o > 0; o >>= 1)
+#pragma unroll
+        for (int u = 0; u < U; ++u) part[u] += __shfl_xor(part[u], o, 64);
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int r = r0 + u * 4 * rpw + rsub;
+        if (c == 0 && r < nblk) key[r] = order_key(part[u]);
+      }
     }
-    key[c] = order_key(s);
-  }
   }
   __syncthreads();
 
+  // radix select of the k-th largest key, most significant byte first
   uint32_t T = 0u;
-  for (int bit = 31; bit >= 0; --bit) {
-    const uint32_t cand = T | (1u << bit);
-    if (block_count(key, nblk, sh4, tid, [cand](uint32_t kc) { return kc >= cand; }) >= k) T = cand;
+  int rest = k;                                   // how many keys with the fixed prefix are still to take
+  int* hist = (int*)red;
+  for (int pass = 0; pass < 4; ++pass) {
+    const int shift = 24 - 8 * pass;
+    const uint32_t himask = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
+    hist[tid] = 0;
+    __syncthreads();
+    for (int cidx = tid; cidx < nblk; cidx += 256) {
+      const uint32_t kc = key[cidx];
+      if ((kc & himask) == (T & himask)) atomicAdd(&hist[(kc >> shift) & 0xffu], 1);
+    }
+    __syncthreads();
+    // thread t: keys (with the prefix) whose digit is >= t, and > t: suffix sums over the 256 bins,
+    // by shuffles inside each wavefront plus the totals of the wavefronts above
+    const int mine_h = hist[tid];
+    int ge = mine_h;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int up = __shfl_down(ge, o, 64);
+      if ((tid & 63) + o < 64) ge += up;
+    }
+    if ((tid & 63) == 0) wtot[tid >> 6] = ge;
+    __syncthreads();
+    for (int wv = (tid >> 6) + 1; wv < 4; ++wv) ge += wtot[wv];
+    const int gt = ge - mine_h;
+    if (ge >= rest && gt < rest) {               // exactly one digit qualifies (rest >= 1)
+      sel_digit = tid;
+      sel_rest = rest - gt;
+    }
+    __syncthreads();
+    T |= (uint32_t)sel_digit << shift;
+    rest = sel_rest;
+    __syncthreads();
   }
   // ties with the k-th key to take, lowest index first
-  const int need_eq = k - block_count(key, nblk, sh4, tid, [T](uint32_t kc) { return kc > T; });
+  const int need_eq = rest;
 
   // ascending passes over contiguous chunks: thread t owns blocks [t*per, (t+1)*per)
   const int per = (nblk + 255) / 256;
   const int c0 = min(nblk, tid * per), c1 = min(nblk, c0 + per);
   int mine = 0;
   for (int c = c0; c < c1; ++c) mine += key[c] == T;
-  chunk_cnt[tid] = mine;
-  __syncthreads();
-  int eq_before = 0;
-  for (int t = 0; t < tid; ++t) eq_before += chunk_cnt[t];
-  __syncthreads();
+  int eq_before = block_exclusive_prefix(mine, wtot, tid);
   mine = 0;
   for (int c = c0; c < c1; ++c) {
     const uint32_t kc = key[c];
@@ -367,10 +408,7 @@ __global__ __launch_bounds__(256) void select_topk_kernel(const SelectParams p) 
     flag[c] = f;
     mine += f;
   }
-  chunk_cnt[tid] = mine;
-  __syncthreads();
-  int pos = 0;
-  for (int t = 0; t < tid; ++t) pos += chunk_cnt[t];
+  int pos = block_exclusive_prefix(mine, wtot, tid);
   int32_t* out = p.sel_idx + (size_t)bh * p.topk;
   for (int c = c0; c < c1; ++c)
     if (flag[c]) out[pos++] = c;
@@ -381,7 +419,7 @@ __global__ __launch_bounds__(256) void select_topk_kernel(const SelectParams p) 
 // grid (B*Hkv), 256 threads, dynamic LDS: mask[nblk]
 __global__ __launch_bounds__(256) void build_masks_kernel(const MaskParams p) {
   extern __shared__ __align__(16) uint32_t lmask[];
-  __shared__ int chunk_cnt[256];
+  __shared__ int wtot[4];
   const int bk = blockIdx.x, b = bk / p.Hkv, kvh = bk % p.Hkv;
   const int tid = threadIdx.x, nblk = p.nblk;
   for (int c = tid; c < nblk; c += 256) lmask[c] = 0u;
@@ -403,10 +441,7 @@ __global__ __launch_bounds__(256) void build_masks_kernel(const MaskParams p) {
     p.blk_mask[(size_t)bk * nblk + c] = m;
     mine += (m != 0u);
   }
-  chunk_cnt[tid] = mine;
-  __syncthreads();
-  int pos = 0;
-  for (int t = 0; t < tid; ++t) pos += chunk_cnt[t];
+  int pos = block_exclusive_prefix(mine, wtot, tid);
   int32_t* list = p.union_list + (size_t)bk * nblk;
   for (int c = c0; c < c1; ++c)
     if (lmask[c] != 0u) list[pos++] = c;
