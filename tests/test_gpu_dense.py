@@ -280,3 +280,14 @@ def _compare_refresh_step(w, seed):
 ])
 def test_fused_refresh_step(dtype, B, Hq, Hkv, d, P, Bq):
     _compare_refresh_step(_wl(dtype, B, Hq, Hkv, d, P, Bq), seed=51)
+
+
+# ------------------------------------------------------------------ extreme head groupings / head_dim 64
+@pytest.mark.parametrize("B,Hq,Hkv,d,P,Bq", [
+    (1, 32, 1, 128, 1200, 4),        # G = 32 (the ABI's maximum): one KV head serves every query head
+    (1, 32, 1, 64, 900, 8),
+    (2, 16, 1, 128, 600, 40),        # G = 16, several row tiles per KV group, rows of two heads in one wavefront
+])
+def test_bf16_maximum_head_grouping(B, Hq, Hkv, d, P, Bq):
+    _compare_block(_wl("bf16", B, Hq, Hkv, d, P, Bq), seed=81)
+    _compare_refresh_step(_wl("bf16", B, Hq, Hkv, d, P, Bq), seed=82)

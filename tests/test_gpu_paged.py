@@ -133,3 +133,9 @@ def test_paged_serving_shape_batch32_full_tensors():
     lens = rng.integers(512, 8193, size=32)
     lens[0], lens[5] = 8192, 37
     _run_paged(w, seed=4100, page_size=256, lens=lens)
+
+
+def test_paged_head_dim_64_and_wide_grouping():
+    """head_dim 64 (other tile geometry) and G = 8 with a block that spans two row tiles."""
+    _run_paged(_wl("bf16", 3, 8, 1, 64, 1536, 40), seed=45, page_size=128, lens=[1536, 700, 64])
+    _run_paged(_wl("f32", 2, 8, 1, 128, 384, 3), seed=46, page_size=64, lens=[384, 65])
