@@ -408,9 +408,13 @@ fb_status fb_refresh_step_prof(const fb_shape* shape, const void* q, const void*
   }
   p.ws_o = (float*)(ws + w.o[0]); p.ws_m = (float*)(ws + w.m[0]); p.ws_l = (float*)(ws + w.l[0]);
   p.ws_o2 = (float*)(ws + w.o[1]); p.ws_m2 = (float*)(ws + w.m[1]); p.ws_l2 = (float*)(ws + w.l[1]);
+  // Small block and many splits (the LLM shapes): the prefix splits already fill every CU, so the
+  // block's own keys are not streamed by the attention kernel at all; one fold kernel (4 rows per
+  // workgroup) folds the splits, computes the rows' block-internal attention and merges.
+  const bool small_block = shape->block_len <= fb::kMaxInlineBlock && shape->block_len % fb::kFoldRows == 0 && ns >= 8;
   hipError_t e = hipSuccess;
   if (ev_begin && (e = hipEventRecord((hipEvent_t)ev_begin, stream)) != hipSuccess) return hip_fail(e);
-  e = launch_attn(shape, p, fb::kPassRefreshFused, stream);
+  e = launch_attn(shape, p, small_block ? fb::kPassDense : fb::kPassRefreshFused, stream);
   if (e != hipSuccess) return hip_fail(e);
   if (ev_attn_end && (e = hipEventRecord((hipEvent_t)ev_attn_end, stream)) != hipSuccess) return hip_fail(e);
 
@@ -420,9 +424,16 @@ fb_status fb_refresh_step_prof(const fb_shape* shape, const void* q, const void*
   c.ws_o = p.ws_o; c.ws_m = p.ws_m; c.ws_l = p.ws_l;
   c.o = o_part; c.m = m_part; c.lse = lse_part;
   c.Bq = shape->block_len;
-  c.blk_o = p.ws_o2; c.blk_m = p.ws_m2; c.blk_l = p.ws_l2;
   c.fin_out = out; c.fin_lse = lse_out; c.fin_bf16 = shape->dtype == FB_BF16;
-  e = fb::launch_combine(c, stream);
+  if (small_block) {
+    c.blk_q = q; c.blk_k = k_block; c.blk_v = v_block;
+    c.Hq = shape->n_q_heads; c.Hkv = shape->n_kv_heads; c.G = shape->n_q_heads / shape->n_kv_heads;
+    c.scale_log2 = p.scale_log2;
+    e = fb::launch_refresh_fold(c, stream);
+  } else {
+    c.blk_o = p.ws_o2; c.blk_m = p.ws_m2; c.blk_l = p.ws_l2;
+    e = fb::launch_combine(c, stream);
+  }
   if (e != hipSuccess) return hip_fail(e);
   if (ev_end && (e = hipEventRecord((hipEvent_t)ev_end, stream)) != hipSuccess) return hip_fail(e);
   return FB_OK;

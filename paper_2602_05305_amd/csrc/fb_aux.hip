@@ -204,6 +204,164 @@ __global__ __launch_bounds__(256) void combine_wide_kernel(const CombineParams p
   finish_row(p, sel, res, have_res_set, row, c4);
 }
 
+// ------------------------------------------------------------------------------ refresh fold
+// Refresh step with a small block (at most kMaxInlineBlock keys): after the streaming pass over the
+// prefix, ONE kernel folds the split partials (Eq. 5), writes the folded external partial to the
+// caller's cache, computes the block-internal attention of its rows with plain FMAs (Eq. 7) and
+// writes the Eq. 8-9 merge as the step's output.  Workgroup = kFoldRows rows of one query head
+// (the block's K/V are staged in LDS once per workgroup); wavefront w owns row w for the
+// attention part, all 256 threads share the split loads of every row.
+__device__ __forceinline__ float4 load4(const void* base, size_t i, int is_bf16) {
+  if (is_bf16) {
+    const uint2 u = *(const uint2*)((const uint16_t*)base + i);
+    return make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xffff0000u),
+                       __uint_as_float(u.y << 16), __uint_as_float(u.y & 0xffff0000u));
+  }
+  return *(const float4*)((const float*)base + i);
+}
+__device__ __forceinline__ float wave_max_f(float x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, 64));
+  return x;
+}
+__device__ __forceinline__ float wave_sum_f(float x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+  return x;
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void refresh_fold_kernel(const CombineParams p) {
+  constexpr int RW = kFoldRows;
+  constexpr int per_row = D / 4, nsl = 256 / per_row;
+  constexpr int ST = D + 4;                        // floats per K / V row in LDS: conflict-free 128-bit row reads
+  constexpr int ES = D + 4;                        // folded external row: o[D], m2, l
+  constexpr int NACC = D / 64;
+  extern __shared__ __align__(16) float lds_f[];
+  float* k_s = lds_f;                              // [Bq][ST]
+  float* v_s = k_s + p.Bq * ST;                    // [Bq][ST]
+  float* q_s = v_s + p.Bq * ST;                    // [RW][D]
+  float* e_s = q_s + RW * D;                       // [RW][ES]
+  Folded* sh = (Folded*)(e_s + RW * ES);           // [RW][256]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int sl = tid / per_row, c4 = tid % per_row;
+  const size_t row0 = (size_t)blockIdx.x * RW;     // Bq % RW == 0: the RW rows belong to one query head
+  const int bh = (int)(row0 / p.Bq), b = bh / p.Hq, kvh = (bh % p.Hq) / p.G;
+  const size_t kvbase = (size_t)(b * p.Hkv + kvh) * p.Bq * D;
+
+  // first CH splits of this thread for all RW rows: every load is issued before any is used, and the
+  // block's K / V / q staging below runs while they are in flight
+  {
+    constexpr int CH = 4;
+    float mv[RW][CH], lv[RW][CH];
+    float4 ov[RW][CH];
+#pragma unroll
+    for (int r = 0; r < RW; ++r)
+#pragma unroll
+      for (int c = 0; c < CH; ++c) {
+        const int sp = sl + c * nsl;
+        mv[r][c] = -INFINITY;
+        lv[r][c] = 0.f;
+        ov[r][c] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (sp < p.nsplit) {
+          const size_t g = (size_t)sp * p.rows + row0 + r;
+          mv[r][c] = p.ws_m[g];
+          lv[r][c] = p.ws_l[g];
+          ov[r][c] = *(const float4*)(p.ws_o + g * D + c4 * 4);
+        }
+      }
+    for (int c = tid; c < p.Bq * per_row; c += 256) {
+      const int j = c / per_row, cc = c % per_row;
+      *(float4*)(k_s + j * ST + cc * 4) = load4(p.blk_k, kvbase + (size_t)j * D + cc * 4, p.fin_bf16);
+      *(float4*)(v_s + j * ST + cc * 4) = load4(p.blk_v, kvbase + (size_t)j * D + cc * 4, p.fin_bf16);
+    }
+    if (tid < RW * per_row)
+      *(float4*)(q_s + (tid / per_row) * D + (tid % per_row) * 4) =
+          load4(p.blk_q, (row0 + tid / per_row) * D + (tid % per_row) * 4, p.fin_bf16);
+#pragma unroll
+    for (int r = 0; r < RW; ++r) {
+      Folded f = empty_folded();
+      float cm = mv[r][0];
+#pragma unroll
+      for (int c = 1; c < CH; ++c) cm = fmaxf(cm, mv[r][c]);
+      if (cm != -INFINITY) {
+        f.m2 = cm;
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+          const float w = __builtin_amdgcn_exp2f(mv[r][c] - cm);     // raw v_exp_f32: weights in (0, 1], exp2(-inf) = 0
+          f.o.x = fmaf(ov[r][c].x, w, f.o.x);
+          f.o.y = fmaf(ov[r][c].y, w, f.o.y);
+          f.o.z = fmaf(ov[r][c].z, w, f.o.z);
+          f.o.w = fmaf(ov[r][c].w, w, f.o.w);
+          f.l = fmaf(lv[r][c], w, f.l);
+        }
+      }
+      if (p.nsplit > CH * nsl)     // more splits than one chunk per thread covers
+        f = fold_two(f, fold_strided(p.ws_o, p.ws_m, p.ws_l, p.nsplit, p.rows, row0 + r, D, c4, sl + CH * nsl, nsl));
+      sh[r * 256 + tid] = f;
+    }
+  }
+  __syncthreads();
+
+  const bool has_row = wave < RW;                  // wavefronts beyond the workgroup's rows only took part in the loads
+  const size_t row = row0 + (has_row ? wave : 0);
+  if (has_row && lane < per_row) {                 // finish this wavefront's row: fold the split groups in order
+    Folded ext = sh[wave * 256 + lane];
+    for (int j = 1; j < nsl; ++j) ext = fold_two(ext, sh[wave * 256 + j * per_row + lane]);
+    emit(ext, p.o, p.m, p.lse, row, D, lane);
+    *(float4*)(e_s + wave * ES + lane * 4) = ext.o;
+    if (lane == 0) {
+      e_s[wave * ES + D] = ext.m2;
+      e_s[wave * ES + D + 1] = ext.l;
+    }
+  }
+  // block-internal scores of the row: lane = key
+  float s2 = -INFINITY;
+  if (has_row && lane < p.Bq) {
+    const float4* kr = (const float4*)(k_s + lane * ST);
+    const float4* qr = (const float4*)(q_s + wave * D);
+    float d = 0.f;
+#pragma unroll 8
+    for (int i = 0; i < D / 4; ++i) {
+      const float4 a = kr[i], c = qr[i];
+      d = fmaf(a.x, c.x, d);
+      d = fmaf(a.y, c.y, d);
+      d = fmaf(a.z, c.z, d);
+      d = fmaf(a.w, c.w, d);
+    }
+    s2 = d * p.scale_log2;
+  }
+  const float mi = wave_max_f(s2);
+  const float w = (lane < p.Bq) ? __builtin_amdgcn_exp2f(s2 - mi) : 0.f;
+  const float li = wave_sum_f(w);
+  __syncthreads();                                 // the row's folded external statistics are in LDS
+  if (!has_row) return;
+
+  // value accumulation: lane owns columns lane, lane + 64; key j's weight is broadcast from lane j
+  float acc[NACC];
+#pragma unroll
+  for (int i = 0; i < NACC; ++i) acc[i] = 0.f;
+  for (int j = 0; j < p.Bq; ++j) {
+    const float pj = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(w), j));
+#pragma unroll
+    for (int i = 0; i < NACC; ++i) acc[i] = fmaf(pj, v_s[j * ST + lane + 64 * i], acc[i]);
+  }
+  // Eq. 8-9 against the folded external statistics of the row
+  const float me = e_s[wave * ES + D], le = e_s[wave * ES + D + 1];
+  const float M = fmaxf(me, mi);
+  const float we = exp2f(me - M), wi = exp2f(mi - M);      // mi is finite (the block has at least one key)
+  const float den = le * we + li * wi;
+  const float inv = 1.f / den;
+#pragma unroll
+  for (int i = 0; i < NACC; ++i) {
+    const float val = (e_s[wave * ES + lane + 64 * i] * we + acc[i] * wi) * inv;
+    if (p.fin_bf16) ((uint16_t*)p.fin_out)[row * D + lane + 64 * i] = (uint16_t)bf16_rne(val);
+    else ((float*)p.fin_out)[row * D + lane + 64 * i] = val;
+  }
+  if (p.fin_lse != nullptr && lane == 0) p.fin_lse[row] = (M + log2f(den)) * kLn2;
+}
+
 // ------------------------------------------------------------------------------ pooling
 __device__ __forceinline__ float load_elem(const void* base, size_t i, int is_bf16) {
   if (is_bf16) {
@@ -541,6 +699,20 @@ hipError_t ensure_lds(K kern, size_t bytes, bool& done) {
   hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 2048);
   if (e == hipSuccess) done = true;
   return e;
+}
+
+hipError_t launch_refresh_fold(const CombineParams& p, hipStream_t s) {
+  if (p.rows == 0) return hipSuccess;
+  if (p.Bq > kMaxInlineBlock || p.Bq % kFoldRows != 0 || p.blk_q == nullptr || p.nsplit < 1) return hipErrorInvalidValue;
+  const size_t lds = ((size_t)2 * p.Bq * (p.D + 4) + kFoldRows * p.D + kFoldRows * (p.D + 4)) * sizeof(float) +
+                     (size_t)kFoldRows * 256 * sizeof(Folded);
+  static bool raised64 = false, raised128 = false;
+  hipError_t e = p.D == 64 ? ensure_lds(refresh_fold_kernel<64>, lds, raised64) : ensure_lds(refresh_fold_kernel<128>, lds, raised128);
+  if (e != hipSuccess) return e;
+  const dim3 grid((unsigned)(p.rows / kFoldRows));
+  if (p.D == 64) hipLaunchKernelGGL(refresh_fold_kernel<64>, grid, dim3(256), lds, s, p);
+  else hipLaunchKernelGGL(refresh_fold_kernel<128>, grid, dim3(256), lds, s, p);
+  return hipGetLastError();
 }
 
 hipError_t launch_select_topk(const SelectParams& p, hipStream_t s) {

@@ -97,6 +97,10 @@ struct CombineParams {
   // the normalised output (storage type) and its log-normaliser; null = no final output
   const float* blk_o; const float* blk_m; const float* blk_l;
   void* fin_out; float* fin_lse; int fin_bf16;
+  // ... or, for a block of at most kMaxInlineBlock keys, the block's q / k / v themselves (storage type
+  // fin_bf16): the fold kernel computes the block-internal attention of its rows itself
+  const void* blk_q; const void* blk_k; const void* blk_v;
+  int Hq, Hkv, G; float scale_log2;
 };
 
 struct SelectParams {
@@ -128,6 +132,10 @@ struct MaskParams {
 hipError_t launch_attn_f32(const PassParams& p, int D, PassMode mode, hipStream_t s);
 hipError_t launch_attn_bf16(const PassParams& p, int D, PassMode mode, hipStream_t s);
 hipError_t launch_combine(const CombineParams& p, hipStream_t s);
+// Fold + block-internal attention + merge in one kernel; needs blk_q/k/v, Bq <= kMaxInlineBlock, Bq % kFoldRows == 0.
+hipError_t launch_refresh_fold(const CombineParams& p, hipStream_t s);
+constexpr int kMaxInlineBlock = 64;
+constexpr int kFoldRows = 4;
 hipError_t launch_pool_keys(const PoolParams& p, hipStream_t s);
 hipError_t launch_select_topk(const SelectParams& p, hipStream_t s);
 hipError_t launch_build_masks(const MaskParams& p, hipStream_t s);
