@@ -9,6 +9,10 @@ namespace {
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
+// v_exp_f32 directly: every use below has an argument that is <= 0, -inf, or a small positive number,
+// where the library exp2f's extra range handling (denormal results) buys nothing.
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
 // ------------------------------------------------------------------------------ combine
 // A folded partial in the log2 domain: o4 (4 columns of this thread), reference m2, sum l.
 struct Folded {
@@ -28,7 +32,7 @@ __device__ __forceinline__ Folded fold_splits(const float* __restrict__ ws_o, co
   if (M == -INFINITY) return f;
   for (int s = 0; s < nsplit; ++s) {
     const size_t r = (size_t)s * rows + row;
-    const float w = exp2f(ws_m[r] - M);
+    const float w = fast_exp2(ws_m[r] - M);
     const float4 o = *(const float4*)(ws_o + r * D + c4 * 4);
     f.o.x = fmaf(o.x, w, f.o.x);
     f.o.y = fmaf(o.y, w, f.o.y);
@@ -43,7 +47,7 @@ __device__ __forceinline__ Folded fold_two(const Folded& a, const Folded& b) {
   Folded f;
   f.m2 = fmaxf(a.m2, b.m2);
   const float mu = (f.m2 == -INFINITY) ? 0.f : f.m2;
-  const float wa = exp2f(a.m2 - mu), wb = exp2f(b.m2 - mu);
+  const float wa = fast_exp2(a.m2 - mu), wb = fast_exp2(b.m2 - mu);
   f.o.x = a.o.x * wa + b.o.x * wb;
   f.o.y = a.o.y * wa + b.o.y * wb;
   f.o.z = a.o.z * wa + b.o.z * wb;
@@ -61,7 +65,7 @@ __device__ __forceinline__ void emit(const Folded& f, float* __restrict__ o, flo
   if (f.l > 0.f) {
     m_nat = f.m2 * kLn2;
     const float back = m_nat * kLog2e;
-    const float adj = exp2f(f.m2 - back);
+    const float adj = fast_exp2(f.m2 - back);
     v = make_float4(f.o.x * adj, f.o.y * adj, f.o.z * adj, f.o.w * adj);
     L = (f.m2 + log2f(f.l)) * kLn2;
   }
@@ -94,7 +98,7 @@ __device__ __forceinline__ void finish_row(const CombineParams& p, const Folded&
     if (lse != -INFINITY) {
       const float m = p.res_in_m[row];
       res.m2 = m * kLog2e;
-      res.l = exp2f((lse - m) * kLog2e);
+      res.l = fast_exp2((lse - m) * kLog2e);
       res.o = *(const float4*)(p.res_in_o + row * p.D + c4 * 4);
     }
   }
@@ -167,12 +171,12 @@ __device__ __forceinline__ Folded fold_strided(const float* __restrict__ ws_o, c
     for (int c = 1; c < CH; ++c) cm = fmaxf(cm, mv[c]);
     const float Mn = fmaxf(f.m2, cm);
     if (Mn == -INFINITY) continue;
-    const float a = exp2f(f.m2 - Mn);
+    const float a = fast_exp2(f.m2 - Mn);
     f.o.x *= a; f.o.y *= a; f.o.z *= a; f.o.w *= a;
     f.l *= a;
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
-      const float w = exp2f(mv[c] - Mn);
+      const float w = fast_exp2(mv[c] - Mn);
       f.o.x = fmaf(ov[c].x, w, f.o.x);
       f.o.y = fmaf(ov[c].y, w, f.o.y);
       f.o.z = fmaf(ov[c].z, w, f.o.z);
@@ -289,7 +293,7 @@ __global__ __launch_bounds__(256) void refresh_fold_kernel(const CombineParams p
         f.m2 = cm;
 #pragma unroll
         for (int c = 0; c < CH; ++c) {
-          const float w = __builtin_amdgcn_exp2f(mv[r][c] - cm);     // raw v_exp_f32: weights in (0, 1], exp2(-inf) = 0
+          const float w = fast_exp2(mv[r][c] - cm);
           f.o.x = fmaf(ov[r][c].x, w, f.o.x);
           f.o.y = fmaf(ov[r][c].y, w, f.o.y);
           f.o.z = fmaf(ov[r][c].z, w, f.o.z);
@@ -333,7 +337,7 @@ __global__ __launch_bounds__(256) void refresh_fold_kernel(const CombineParams p
     s2 = d * p.scale_log2;
   }
   const float mi = wave_max_f(s2);
-  const float w = (lane < p.Bq) ? __builtin_amdgcn_exp2f(s2 - mi) : 0.f;
+  const float w = (lane < p.Bq) ? fast_exp2(s2 - mi) : 0.f;
   const float li = wave_sum_f(w);
   __syncthreads();                                 // the row's folded external statistics are in LDS
   if (!has_row) return;
@@ -350,7 +354,7 @@ __global__ __launch_bounds__(256) void refresh_fold_kernel(const CombineParams p
   // Eq. 8-9 against the folded external statistics of the row
   const float me = e_s[wave * ES + D], le = e_s[wave * ES + D + 1];
   const float M = fmaxf(me, mi);
-  const float we = exp2f(me - M), wi = exp2f(mi - M);      // mi is finite (the block has at least one key)
+  const float we = fast_exp2(me - M), wi = fast_exp2(mi - M);      // mi is finite (the block has at least one key)
   const float den = le * we + li * wi;
   const float inv = 1.f / den;
 #pragma unroll
