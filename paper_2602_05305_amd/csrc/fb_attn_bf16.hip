@@ -874,8 +874,8 @@ hipError_t launch_d(const PassParams& p, PassMode mode, hipStream_t s) {
     }
     case kPassRefreshFused: {
       const int tiles = (p.nkeys + kKeyTile - 1) / kKeyTile;
-      if (tiles >= 8 * p.nsplit) return launch_one<D, kPassRefreshFused, kKeyTile, 1, 2>(p, s);
-      return launch_one<D, kPassRefreshFused, kKeyTile, 1, 1>(p, s);
+      if (p.nsplit > 1 && tiles >= 8 * p.nsplit) return launch_one<D, kPassRefreshFused, kKeyTile, 1, 2>(p, s);
+      return launch_one<D, kPassRefreshFused, kKeyTile, 1, 1>(p, s);   // unsplit (many row tiles): as the dense pass
     }
     case kPassDensePaged: {
       const int tiles = (p.nkeys + kKeyTile - 1) / kKeyTile;
