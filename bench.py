@@ -578,7 +578,11 @@ def main():
         "full_recompute": {"us_per_step": round(us_full, 3), "speedup_cached_vs_full": round(us_full / us_step, 3),
                            "note": "same kernels with refresh interval 1"},
     }
-    del dev
+    # the same external pass with the prefix resident in the last-level cache (one K/V set, never rotated)
+    dev_warm = DeviceBlock(w, 1, fused=fused)
+    pw = profile_external(dev_warm, 31, w.refresh)
+    line["steps_detail"]["external_attn_kernel_us_prefix_in_llc"] = round(pw["attn_ms"] * 1e3, 2)
+    del dev_warm, dev
     torch.cuda.empty_cache()
 
     if not args.no_long:
@@ -592,8 +596,27 @@ def main():
         r2["external_call_us"] = round((p2["attn_ms"] + p2["combine_ms"]) * 1e3, 2)
         r2["refresh_step_us"] = round(p2["refresh_step_ms"] * 1e3, 2)
         r2["reuse_step_us"] = round(p2["reuse_step_ms"] * 1e3, 2)
+        # refresh-interval sweep (speedup of caching against full recomputation = R 1), eager launches
+        sweep = {}
+        for R in (1, 2, 4, 8):
+            n = 40 * wl128.steps
+            sweep[f"R={R}"] = round(time_steps(d2, n, wl128.steps, R, False) / n * 1e6, 2)
+        r2["us_per_step_by_refresh_interval"] = sweep
+        r2["speedup_R8_vs_R1"] = round(sweep["R=1"] / sweep["R=8"], 3)
         line["external_128k"] = r2
         del d2
+        torch.cuda.empty_cache()
+        # batch 4 at the same context length (2.1 GB of K/V per pass)
+        w4 = wl.CONFIGS["long_128k_b4"]
+        d4 = DeviceBlock(w4, 2, fused=fused)
+        for _ in range(3):
+            d4.step(0, 0, w4.refresh)
+        p4 = profile_external(d4, 11, w4.refresh)
+        r4 = roofline_obj(w4, p4["attn_ms"], None, fused)
+        r4["workload"] = describe(w4)
+        r4["refresh_step_us"] = round(p4["refresh_step_ms"] * 1e3, 2)
+        line["external_128k_batch4"] = r4
+        del d4
         torch.cuda.empty_cache()
 
     if not args.no_extras:
@@ -603,6 +626,15 @@ def main():
         torch.cuda.empty_cache()
         line["paged_b32"] = paged_extra(torch, fb, wl)
         torch.cuda.empty_cache()
+
+    if not args.no_extras:
+        # the tiny fp32 configuration: launch-bound, reported for completeness
+        wt = wl.CONFIGS["tiny_f32"]
+        dt_ = DeviceBlock(wt, 2, fused=fused)
+        nt = 50 * wt.steps
+        line["tiny_f32"] = {"workload": describe(wt), "us_per_step": round(time_steps(dt_, nt, wt.steps, wt.refresh, False) / nt * 1e6, 2),
+                            "note": "launch-bound: a roofline fraction is not meaningful at this size"}
+        del dt_
 
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(w)
