@@ -256,3 +256,12 @@ def test_binding_has_no_cpu_fallback(monkeypatch, tmp_path):
     monkeypatch.setattr(fb, "LIB_PATH", str(tmp_path / "missing.so"))
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         fb.load_library()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build has no multi-GPU part: bench.py --gpus N > 1 exits with a message (before touching any GPU)."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=60, cwd=ROOT)
+    assert r.returncode != 0 and "one GPU" in r.stderr
