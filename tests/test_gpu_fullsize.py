@@ -156,3 +156,26 @@ def test_sparse_64k_refresh_and_reuse_step():
         kth = np.sort(sc[0, h])[::-1][w.topk - 1]
         spread = sc[0, h].max() - sc[0, h].min()
         assert all(abs(sc[0, h, c] - kth) <= 1e-3 * spread for c in diff), (h, diff)
+
+
+@pytest.mark.parametrize("name,seed", [("llm_32k", 2100), ("long_128k", 3300)])
+def test_refresh_step_entry_point_at_full_size(name, seed):
+    """The benchmark's default refresh step (fb_refresh_step: streaming pass + fold / internal / merge
+    kernel) at the full 32K and 128K shapes: cached partial, output and log-normaliser on all rows."""
+    w = wl.CONFIGS[name]
+    print(f"[case] refresh_step {w.name}", flush=True)
+    Kp, Vp = wl.make_prefix(w, seed)
+    Q, Kb, Vb = wl.make_block_steps(w, seed, steps=1)[0]
+    shape = T.shape_of(w)
+    q, kb, vb = T.to_dev(Q, "bf16"), T.to_dev(Kb, "bf16"), T.to_dev(Vb, "bf16")
+    ext = T.Partial(w)
+    out = torch.empty_like(q)
+    lse = torch.empty(q.shape[:3], device=T.DEV, dtype=torch.float32)
+    fb.fb_refresh_step(shape, q, T.to_dev(Kp, "bf16"), T.to_dev(Vp, "bf16"), kb, vb, ext.o, ext.m, ext.lse, out, lse,
+                       T.workspace(shape))
+    torch.cuda.synchronize()
+    ora_ext = orc.partial(Q, Kp, Vp)
+    T.check_partial(ext.numpy(), ora_ext, "bf16", f"{name} refresh_step ext")
+    ora_out, ora_lse = orc.merge(ora_ext, orc.partial(Q, Kb, Vb))
+    T.assert_close(out.double().cpu().numpy(), ora_out, "bf16", f"{name} refresh_step out")
+    T.assert_close(lse.double().cpu().numpy(), ora_lse, "bf16", f"{name} refresh_step lse", lse=True)
