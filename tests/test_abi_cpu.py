@@ -265,3 +265,29 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
                        timeout=60, cwd=ROOT)
     assert r.returncode != 0 and "one GPU" in r.stderr
+
+
+def test_header_is_plain_c_and_links(tmp_path):
+    """include/flashblock.h is a C header (C99, no C++ needed) and a C program links against the library."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "use.c"
+    src.write_text('#include "flashblock.h"\n#include <stdio.h>\n'
+                   "int main(void) {\n"
+                   "  fb_shape s = {sizeof(fb_shape), 1, 4, 2, 64, 16, 256, FB_F32, 0.0f};\n"
+                   "  fb_paged_kv kv; kv.struct_size = sizeof kv; (void)kv;\n"
+                   '  printf("%d %d %d %zu\\n", fb_version(), (int)fb_check_shape(&s), (int)fb_external_splits(&s),\n'
+                   "         fb_workspace_bytes(&s, 0, 0, 0));\n"
+                   "  return 0;\n}\n")
+    exe = tmp_path / "use"
+    libdir = os.path.dirname(fb.LIB_PATH)
+    r = subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src),
+                        "-o", str(exe), "-L", libdir, "-l:libflashblock.so", f"-Wl,-rpath,{libdir}",
+                        "-Wl,-rpath,/opt/rocm/lib", "-L/opt/rocm/lib"], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    out = subprocess.run([str(exe)], capture_output=True, text=True, timeout=60)
+    assert out.returncode == 0, out.stderr
+    ver, ok, splits, ws = out.stdout.split()
+    assert int(ver) == 100 and int(ok) == fb.FB_OK and int(splits) >= 1 and int(ws) >= 256
