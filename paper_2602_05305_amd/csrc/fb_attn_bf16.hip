@@ -516,25 +516,27 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
     // many wavefronts fit a SIMD, they are issued only in front of the epilogue.
     constexpr int NEO = (MODE == kPassInternal) ? NDBL * 4 : 1;
     constexpr bool kExtEarly = (WS > 1);
+    // eo is deliberately left unset when there is no cached partial (it is only read under has_ext):
+    // a zero default would have to be merged with the loaded values at the end of the branch, which
+    // makes the compiler wait for the loads right there, in front of the first tile.
     f32x4 eo[NEO];
     float ext_m_v = -INFINITY, ext_lse_v = -INFINITY;
+    const bool has_ext = (MODE == kPassInternal) && (p.ext_o != nullptr);     // workgroup-uniform
     auto load_ext = [&]() {
       typedef const __attribute__((address_space(1))) f32x4* gptr_f4;
       typedef const __attribute__((address_space(1))) float* gptr_f;
-      const bool have = (p.ext_o != nullptr) && row_ok;
-#pragma unroll
-      for (int i = 0; i < NEO; ++i) eo[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-      if (have) {
-        ext_m_v = *((gptr_f)p.ext_m + grow);
-        ext_lse_v = *((gptr_f)p.ext_lse + grow);
+      if (has_ext) {
+        const size_t er = row_ok ? grow : grow_last;   // rows past the end read the group's last row; never stored
+        ext_m_v = *((gptr_f)p.ext_m + er);
+        ext_lse_v = *((gptr_f)p.ext_lse + er);
 #pragma unroll
         for (int db = 0; db < NDBL; ++db)
 #pragma unroll
           for (int q4 = 0; q4 < 4; ++q4)
-            eo[db * 4 + q4] = *(gptr_f4)(p.ext_o + grow * D + 32 * (db_base + db) + 8 * q4 + 4 * h);
+            eo[db * 4 + q4] = *(gptr_f4)(p.ext_o + er * D + 32 * (db_base + db) + 8 * q4 + 4 * h);
       }
     };
-    if constexpr (MODE == kPassInternal && kExtEarly) load_ext();
+    if constexpr (MODE == kPassInternal && kExtEarly) { if (ntiles == 0) load_ext(); }
     WaveState<NDBL> sel;
     sel.init();
     WaveState<(MODE == kPassSparseRefresh && !kSetSplit) ? NDBL : 1> res;
@@ -571,6 +573,7 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
     if (ntiles > 0) {
       if (common > 0 || extra) tile_store<D, KT, kSetSplit>(regs, smem, tid, grp);
       __syncthreads();
+      if constexpr (MODE == kPassInternal && kExtEarly) load_ext();   // in flight under the attention work
       for (int i = 0; i < common - 1; ++i) {       // steady state: one barrier per tile
         if (i + 2 < mine) k0_nn = entry_k0(tile_entry(i + 2), mask_nn);
         load_tile(k0_next, mask_next);
@@ -626,6 +629,13 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
     if constexpr (MODE == kPassInternal) {
       if constexpr (!kExtEarly) load_ext();
       if (!row_ok) return;
+      // keep the use of the cached statistics down here: hoisted into the prologue, it would make the
+      // first tile wait for the cached partial's loads
+      asm volatile("" : "+v"(ext_m_v), "+v"(ext_lse_v));
+      if constexpr (kExtEarly) {
+#pragma unroll
+        for (int i = 0; i < NEO; ++i) asm volatile("" : "+v"(eo[i]));
+      }
       float me2 = -INFINITY, le = 0.f;
       if (ext_lse_v != -INFINITY) {
         me2 = ext_m_v * kLog2e;
@@ -643,7 +653,7 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
           const int d0 = 32 * (db_base + db) + 8 * q4 + 4 * h;
-          const f32x4 e = eo[(MODE == kPassInternal) ? db * 4 + q4 : 0];   // o of an empty partial is 0 by contract
+          const f32x4 e = has_ext ? eo[(MODE == kPassInternal) ? db * 4 + q4 : 0] : f32x4{0.f, 0.f, 0.f, 0.f};
           float r[4];
 #pragma unroll
           for (int i = 0; i < 4; ++i) r[i] = (sel.o[db][4 * q4 + i] * wi + e[i] * we) * inv;
