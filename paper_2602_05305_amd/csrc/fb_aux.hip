@@ -275,14 +275,57 @@ __global__ __launch_bounds__(256) void refresh_fold_kernel(const CombineParams p
           ov[r][c] = *(const float4*)(p.ws_o + g * D + c4 * 4);
         }
       }
-    for (int c = tid; c < p.Bq * per_row; c += 256) {
-      const int j = c / per_row, cc = c % per_row;
-      *(float4*)(k_s + j * ST + cc * 4) = load4(p.blk_k, kvbase + (size_t)j * D + cc * 4, p.fin_bf16);
-      *(float4*)(v_s + j * ST + cc * 4) = load4(p.blk_v, kvbase + (size_t)j * D + cc * 4, p.fin_bf16);
+    // block K / V / q -> LDS.  All global loads of the staging are issued before the first LDS store
+    // (a load-then-store loop would wait for every load in flight, the split loads included, on
+    // each trip); chunks past the block's end are clamped to its last chunk and not stored.
+    constexpr int NST = kMaxInlineBlock * per_row / 256;      // staging trips at the largest block
+    const int nchunk = p.Bq * per_row;
+    const size_t qoff = (row0 + (size_t)((tid % (RW * per_row)) / per_row)) * D + (tid % per_row) * 4;
+    if (p.fin_bf16) {
+      uint2 kr[NST], vr[NST];
+#pragma unroll
+      for (int it = 0; it < NST; ++it) {
+        const int c = min(tid + 256 * it, nchunk - 1);
+        const size_t g = kvbase + (size_t)(c / per_row) * D + (c % per_row) * 4;
+        kr[it] = *(const uint2*)((const uint16_t*)p.blk_k + g);
+        vr[it] = *(const uint2*)((const uint16_t*)p.blk_v + g);
+      }
+      const uint2 qr = *(const uint2*)((const uint16_t*)p.blk_q + qoff);
+#pragma unroll
+      for (int it = 0; it < NST; ++it) {
+        const int c = tid + 256 * it;
+        if (c < nchunk) {
+          const int j = c / per_row, cc = c % per_row;
+          *(float4*)(k_s + j * ST + cc * 4) = make_float4(__uint_as_float(kr[it].x << 16), __uint_as_float(kr[it].x & 0xffff0000u),
+                                                          __uint_as_float(kr[it].y << 16), __uint_as_float(kr[it].y & 0xffff0000u));
+          *(float4*)(v_s + j * ST + cc * 4) = make_float4(__uint_as_float(vr[it].x << 16), __uint_as_float(vr[it].x & 0xffff0000u),
+                                                          __uint_as_float(vr[it].y << 16), __uint_as_float(vr[it].y & 0xffff0000u));
+        }
+      }
+      if (tid < RW * per_row)
+        *(float4*)(q_s + (tid / per_row) * D + (tid % per_row) * 4) =
+            make_float4(__uint_as_float(qr.x << 16), __uint_as_float(qr.x & 0xffff0000u), __uint_as_float(qr.y << 16),
+                        __uint_as_float(qr.y & 0xffff0000u));
+    } else {
+      float4 kr[NST], vr[NST];
+#pragma unroll
+      for (int it = 0; it < NST; ++it) {
+        const int c = min(tid + 256 * it, nchunk - 1);
+        const size_t g = kvbase + (size_t)(c / per_row) * D + (c % per_row) * 4;
+        kr[it] = *(const float4*)((const float*)p.blk_k + g);
+        vr[it] = *(const float4*)((const float*)p.blk_v + g);
+      }
+      const float4 qr = *(const float4*)((const float*)p.blk_q + qoff);
+#pragma unroll
+      for (int it = 0; it < NST; ++it) {
+        const int c = tid + 256 * it;
+        if (c < nchunk) {
+          *(float4*)(k_s + (c / per_row) * ST + (c % per_row) * 4) = kr[it];
+          *(float4*)(v_s + (c / per_row) * ST + (c % per_row) * 4) = vr[it];
+        }
+      }
+      if (tid < RW * per_row) *(float4*)(q_s + (tid / per_row) * D + (tid % per_row) * 4) = qr;
     }
-    if (tid < RW * per_row)
-      *(float4*)(q_s + (tid / per_row) * D + (tid % per_row) * 4) =
-          load4(p.blk_q, (row0 + tid / per_row) * D + (tid % per_row) * 4, p.fin_bf16);
 #pragma unroll
     for (int r = 0; r < RW; ++r) {
       Folded f = empty_folded();
