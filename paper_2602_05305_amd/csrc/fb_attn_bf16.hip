@@ -776,6 +776,10 @@ __global__ __launch_bounds__(256) void block_mass_bf16_kernel(const MassParams p
   const float lse2 = live ? lse * kLog2e : 0.f;
   store_k<D, kKeyTile>(kr, stages, tid);
   __syncthreads();
+  // Touch the query registers here: otherwise the waits for their loads end up inside the loop, where
+  // (load counters being in order) they would also wait for the next tile's prefetch on every trip.
+#pragma unroll
+  for (int ks = 0; ks < C::NKS; ++ks) asm volatile("" ::"v"(qreg[ks]));
 
   float acc = 0.f;
   for (int t = t0; t < t1; ++t) {

@@ -513,7 +513,15 @@ __global__ __launch_bounds__(256) void select_topk_kernel(const SelectParams p) 
     for (int c = tid; c < nblk; c += 256) {
       const float* r = rm + (size_t)c * ((size_t)p.Hq * p.Bq);
       float s = 0.f;
-      for (int i = 0; i < p.Bq; ++i) s += r[i];
+      int i = 0;
+      for (; i + 8 <= p.Bq; i += 8) {          // eight independent loads per trip, summed in index order
+        float x[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) x[u] = r[i + u];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += x[u];
+      }
+      for (; i < p.Bq; ++i) s += r[i];
       s /= (float)p.Bq;
       key[c] = order_key(s);
       if (p.score_out != nullptr) p.score_out[(size_t)bh * nblk + c] = s;
@@ -632,9 +640,19 @@ __global__ __launch_bounds__(256) void build_masks_kernel(const MaskParams p) {
   if (p.sel_idx != nullptr) {
     const int n = p.G * p.topk;
     const int32_t* base = p.sel_idx + (size_t)(b * p.Hq + kvh * p.G) * p.topk;
-    for (int i = tid; i < n; i += 256) {
-      const int c = base[i];
-      if (c >= 0 && c < nblk) atomicOr(&lmask[c], 1u << (i / p.topk));
+    // four selection entries per thread and trip, loaded before any is used (one memory round trip per trip)
+    for (int i0 = tid; i0 < n; i0 += 4 * 256) {
+      int c[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int i = i0 + 256 * u;
+        c[u] = (i < n) ? base[i] : -1;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int i = i0 + 256 * u;
+        if (c[u] >= 0 && c[u] < nblk) atomicOr(&lmask[c[u]], 1u << (i / p.topk));
+      }
     }
   }
   __syncthreads();
