@@ -308,10 +308,11 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
                     MODE == kPassSparseReuse || kSetSplit,
                 "unsupported group mode");
 
-  // wavefront-uniform by construction; in the paged pass, telling the compiler so keeps the block-table
-  // lookups and page address arithmetic in scalar registers
-  const int grp = (NG > 1) ? ((MODE == kPassDensePaged) ? __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 8))
-                                                        : (int)(threadIdx.x >> 8))
+  // wavefront-uniform by construction; in the list-driven passes (paged, sparse reuse), telling the compiler
+  // so turns the per-tile table lookups into scalar loads, which do not queue behind the tile's vector loads
+  const int grp = (NG > 1) ? ((MODE == kPassDensePaged || MODE == kPassSparseReuse)
+                                  ? __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 8))
+                                  : (int)(threadIdx.x >> 8))
                            : 0;
   const int tid = threadIdx.x & 255, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, h = lane >> 5;
