@@ -574,6 +574,11 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
     if (ntiles > 0) {
       if (common > 0 || extra) tile_store<D, KT, kSetSplit>(regs, smem, tid, grp);
       __syncthreads();
+      // the query registers have arrived by now (their loads went out with the first tile's); saying so here
+      // keeps waits for them out of the tile loop, where in-order load counters would turn them into waits
+      // for the next tile's prefetch
+#pragma unroll
+      for (int ks = 0; ks < C::NKS; ++ks) asm volatile("" ::"v"(qreg[ks]));
       if constexpr (MODE == kPassInternal && kExtEarly) load_ext();   // in flight under the attention work
       for (int i = 0; i < common - 1; ++i) {       // steady state: one barrier per tile
         if (i + 2 < mine) k0_nn = entry_k0(tile_entry(i + 2), mask_nn);
