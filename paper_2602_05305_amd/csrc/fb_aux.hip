@@ -237,6 +237,7 @@ __device__ __forceinline__ float wave_sum_f(float x) {
 template <int D>
 __global__ __launch_bounds__(256) void refresh_fold_kernel(const CombineParams p) {
   constexpr int RW = kFoldRows;
+  static_assert(RW % 4 == 0 && RW <= 4, "block length is a multiple of RW: the value loop below steps by 4 keys; one wavefront per row");
   constexpr int per_row = D / 4, nsl = 256 / per_row;
   constexpr int ST = D + 4;                        // floats per K / V row in LDS: conflict-free 128-bit row reads
   constexpr int ES = D + 4;                        // folded external row: o[D], m2, l
@@ -389,10 +390,18 @@ __global__ __launch_bounds__(256) void refresh_fold_kernel(const CombineParams p
   float acc[NACC];
 #pragma unroll
   for (int i = 0; i < NACC; ++i) acc[i] = 0.f;
-  for (int j = 0; j < p.Bq; ++j) {
-    const float pj = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(w), j));
+  for (int j = 0; j < p.Bq; j += 4) {             // Bq % 4 == 0 on this path; four keys' LDS reads in flight per trip
+    float pj[4], vv[4][NACC];
 #pragma unroll
-    for (int i = 0; i < NACC; ++i) acc[i] = fmaf(pj, v_s[j * ST + lane + 64 * i], acc[i]);
+    for (int u = 0; u < 4; ++u) {
+      pj[u] = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(w), j + u));
+#pragma unroll
+      for (int i = 0; i < NACC; ++i) vv[u][i] = v_s[(j + u) * ST + lane + 64 * i];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int i = 0; i < NACC; ++i) acc[i] = fmaf(pj[u], vv[u][i], acc[i]);
   }
   // Eq. 8-9 against the folded external statistics of the row
   const float me = e_s[wave * ES + D], le = e_s[wave * ES + D + 1];
