@@ -427,7 +427,8 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
     } else {
       total = (nkeys + KT - 1) / KT;
     }
-    TileRange tr = split_range(total, p.nsplit, split);
+    TileRange tr = (MODE == kPassInternal) ? TileRange{0, total}     // never split: no run-time division in its short prologue
+                                           : split_range(total, p.nsplit, split);
     if constexpr (kFused) {
       if (own_block) {
         tr = TileRange{0, total};
@@ -470,7 +471,8 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
     // all but the first of them.  The statistics do not depend on the tile order.
     const int ntiles = tr.end - tr.begin;
     const uint32_t rsrc = (p.div_rowtiles.d == 1) ? blockIdx.x : unit;
-    const int rot = ntiles > 0 ? (int)((rsrc * 13u + (rsrc >> 5) * 7u) % (unsigned)ntiles) : 0;
+    const int rot = (MODE == kPassInternal || ntiles <= 0) ? 0      // the block's K/V are small and cache-resident
+                                                            : (int)((rsrc * 13u + (rsrc >> 5) * 7u) % (unsigned)ntiles);
     auto tile_entry = [&](int i) -> int {   // i-th tile of this wavefront group
       int j = TG * i + (kSetSplit ? 0 : grp) + rot;
       if (j >= ntiles) j -= ntiles;
