@@ -252,8 +252,6 @@ __global__ __launch_bounds__(256) void refresh_fold_kernel(const CombineParams p
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int sl = tid / per_row, c4 = tid % per_row;
   const size_t row0 = (size_t)blockIdx.x * RW;     // Bq % RW == 0: the RW rows belong to one query head
-  const int bh = (int)(row0 / p.Bq), b = bh / p.Hq, kvh = (bh % p.Hq) / p.G;
-  const size_t kvbase = (size_t)(b * p.Hkv + kvh) * p.Bq * D;
 
   // first CH splits of this thread for all RW rows: every load is issued before any is used, and the
   // block's K / V / q staging below runs while they are in flight
@@ -279,6 +277,9 @@ __global__ __launch_bounds__(256) void refresh_fold_kernel(const CombineParams p
     // block K / V / q -> LDS.  All global loads of the staging are issued before the first LDS store
     // (a load-then-store loop would wait for every load in flight, the split loads included, on
     // each trip); chunks past the block's end are clamped to its last chunk and not stored.
+    // (the head arithmetic needs integer divisions: it comes after the split loads have been issued)
+    const int bh = (int)(row0 / p.Bq), b = bh / p.Hq, kvh = (bh % p.Hq) / p.G;
+    const size_t kvbase = (size_t)(b * p.Hkv + kvh) * p.Bq * D;
     constexpr int NST = kMaxInlineBlock * per_row / 256;      // staging trips at the largest block
     const int nchunk = p.Bq * per_row;
     const size_t qoff = (row0 + (size_t)((tid % (RW * per_row)) / per_row)) * D + (tid % per_row) * 4;
