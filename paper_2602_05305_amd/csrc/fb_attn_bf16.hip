@@ -428,13 +428,13 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
       total = (nkeys + KT - 1) / KT;
     }
     TileRange tr = (MODE == kPassInternal) ? TileRange{0, total}     // never split: no run-time division in its short prologue
-                                           : split_range(total, p.nsplit, split);
+                                           : split_range(total, p.div_nsplit, split);
     if constexpr (kFused) {
       if (own_block) {
         tr = TileRange{0, total};
       } else {
         // the last split's workgroup also runs the block phase: it gets blk_cost tiles fewer
-        tr = split_range(total + p.blk_cost, p.nsplit, split);
+        tr = split_range(total + p.blk_cost, p.div_nsplit, split);
         tr.begin = min(tr.begin, total);
         tr.end = min(tr.end, total);
       }

@@ -164,4 +164,13 @@ __device__ __forceinline__ TileRange split_range(int total, int nsplit, int spli
   return r;
 }
 
+// The same cut with the division by nsplit done through its precomputed magic number.
+__device__ __forceinline__ TileRange split_range(int total, const FastDiv& by_nsplit, int split) {
+  const int base = (int)fastdiv((uint32_t)total, by_nsplit), rem = total - base * (int)by_nsplit.d;
+  TileRange r;
+  r.begin = split * base + min(split, rem);
+  r.end = r.begin + base + (split < rem ? 1 : 0);
+  return r;
+}
+
 }  // namespace fb
