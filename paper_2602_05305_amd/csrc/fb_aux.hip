@@ -20,29 +20,6 @@ struct Folded {
   float m2, l;
 };
 
-__device__ __forceinline__ Folded fold_splits(const float* __restrict__ ws_o, const float* __restrict__ ws_m,
-                                              const float* __restrict__ ws_l, int nsplit, size_t rows,
-                                              size_t row, int D, int c4) {
-  Folded f;
-  f.o = make_float4(0.f, 0.f, 0.f, 0.f);
-  f.l = 0.f;
-  float M = -INFINITY;
-  for (int s = 0; s < nsplit; ++s) M = fmaxf(M, ws_m[(size_t)s * rows + row]);
-  f.m2 = M;
-  if (M == -INFINITY) return f;
-  for (int s = 0; s < nsplit; ++s) {
-    const size_t r = (size_t)s * rows + row;
-    const float w = fast_exp2(ws_m[r] - M);
-    const float4 o = *(const float4*)(ws_o + r * D + c4 * 4);
-    f.o.x = fmaf(o.x, w, f.o.x);
-    f.o.y = fmaf(o.y, w, f.o.y);
-    f.o.z = fmaf(o.z, w, f.o.z);
-    f.o.w = fmaf(o.w, w, f.o.w);
-    f.l = fmaf(ws_l[r], w, f.l);
-  }
-  return f;
-}
-
 __device__ __forceinline__ Folded fold_two(const Folded& a, const Folded& b) {
   Folded f;
   f.m2 = fmaxf(a.m2, b.m2);
@@ -126,23 +103,7 @@ __device__ __forceinline__ void finish_row(const CombineParams& p, const Folded&
   }
 }
 
-// Few splits: one thread per (row, 4 columns) walks the splits.
-__global__ __launch_bounds__(256) void combine_kernel(const CombineParams p) {
-  const int per_row = p.D / 4;
-  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= (size_t)p.rows * per_row) return;
-  const size_t row = idx / per_row;
-  const int c4 = (int)(idx % per_row);
-  if (p.head_on != nullptr && p.head_on[row / p.Bq] == 0) return;
-  Folded sel = empty_folded(), res = empty_folded();
-  if (p.ws_o != nullptr && p.nsplit > 0) sel = fold_splits(p.ws_o, p.ws_m, p.ws_l, p.nsplit, p.rows, row, p.D, c4);
-  const bool have_res_set = p.ws_o2 != nullptr;
-  if (have_res_set) res = fold_splits(p.ws_o2, p.ws_m2, p.ws_l2, p.nsplit, p.rows, row, p.D, c4);
-  finish_row(p, sel, res, have_res_set, row, c4);
-}
-
-// Many splits: one workgroup per row; NSL = 256/(D/4) thread groups each fold every NSL-th split
-// (independent 16-byte loads in flight), then one group folds the NSL results in fixed order.
+// Fold of the splits first, first + stride, ... of one row (4 columns of it).
 __device__ __forceinline__ Folded fold_strided(const float* __restrict__ ws_o, const float* __restrict__ ws_m,
                                                const float* __restrict__ ws_l, int nsplit, size_t rows,
                                                size_t row, int D, int c4, int first, int stride) {
@@ -188,6 +149,24 @@ __device__ __forceinline__ Folded fold_strided(const float* __restrict__ ws_o, c
   return f;
 }
 
+// Few splits: one thread per (row, 4 columns) walks the splits.
+__global__ __launch_bounds__(256) void combine_kernel(const CombineParams p) {
+  const int per_row = p.D / 4;
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (size_t)p.rows * per_row) return;
+  const size_t row = idx / per_row;
+  const int c4 = (int)(idx % per_row);
+  if (p.head_on != nullptr && p.head_on[row / p.Bq] == 0) return;
+  Folded sel = empty_folded(), res = empty_folded();
+  // chunks of four splits with all loads in flight (one memory round trip for up to four splits)
+  if (p.ws_o != nullptr && p.nsplit > 0) sel = fold_strided(p.ws_o, p.ws_m, p.ws_l, p.nsplit, p.rows, row, p.D, c4, 0, 1);
+  const bool have_res_set = p.ws_o2 != nullptr;
+  if (have_res_set) res = fold_strided(p.ws_o2, p.ws_m2, p.ws_l2, p.nsplit, p.rows, row, p.D, c4, 0, 1);
+  finish_row(p, sel, res, have_res_set, row, c4);
+}
+
+// Many splits: one workgroup per row; NSL = 256/(D/4) thread groups each fold every NSL-th split
+// (fold_strided above), then one group folds the NSL results in fixed order.
 __global__ __launch_bounds__(256) void combine_wide_kernel(const CombineParams p) {
   __shared__ Folded sh[2][256];
   const int per_row = p.D / 4, nsl = 256 / per_row;
