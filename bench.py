@@ -312,7 +312,9 @@ def sparse_extra(torch, fb, wl):
     i = [0]
     t_pool = _ev_median_us(torch, lambda: fb.fb_pool_keys(d.shape, d.K[0], w.key_block, pooled[0]))
     fb.fb_pool_keys(d.shape, d.K[1], w.key_block, pooled[1])
-    t_sel = _ev_median_us(torch, lambda: fb.fb_select_topk(d.shape, q, pooled[0], w.key_block, w.topk, idx))
+    t_sel1 = _ev_median_us(torch, lambda: fb.fb_select_topk(d.shape, q, pooled[0], w.key_block, w.topk, idx))
+    sws = torch.empty(fb.fb_select_workspace_bytes(d.shape, w.key_block), device="cuda", dtype=torch.uint8)
+    t_sel = _ev_median_us(torch, lambda: fb.fb_select_topk(d.shape, q, pooled[0], w.key_block, w.topk, idx, sws))
     wsm = torch.empty(fb.fb_select_mass_workspace_bytes(d.shape, w.key_block), device="cuda", dtype=torch.uint8)
     fb.fb_external_partial(d.shape, q, d.K[0], d.V[0], d.o, d.m, d.lse, ws)
     idx_m = torch.empty_like(idx)
@@ -335,6 +337,7 @@ def sparse_extra(torch, fb, wl):
     union_bytes = union * w.key_block * w.head_dim * 2 * 2
     return {"workload": describe(w) + f", key_block {w.key_block}, topk {w.topk}",
             "pool_keys_us": round(t_pool, 1), "select_topk_us": round(t_sel, 1),
+            "select_topk_without_workspace_us": round(t_sel1, 1),
             "select_topk_mass_us": round(t_mass, 1),
             "sparse_refresh_call_us": round(t_refresh, 1), "sparse_reuse_call_us": round(t_reuse, 1),
             "sparse_reuse_call_rebuilding_masks_us": round(t_reuse_rebuild, 1),
@@ -521,10 +524,11 @@ def main():
         rows = (ws_.batch, ws_.n_q_heads, ws_.block_len)
         ro, rm, rl = torch.empty(rows + (ws_.head_dim,), device="cuda"), torch.empty(rows, device="cuda"), torch.empty(rows, device="cuda")
         q = d.steps[0][0]
+        sws = torch.empty(fb.fb_select_workspace_bytes(d.shape, ws_.key_block), device="cuda", dtype=torch.uint8)
         for i in range(args.profile_sparse):
             s_ = i % 2
             fb.fb_pool_keys(d.shape, d.K[s_], ws_.key_block, pooled)
-            fb.fb_select_topk(d.shape, q, pooled, ws_.key_block, ws_.topk, idx)
+            fb.fb_select_topk(d.shape, q, pooled, ws_.key_block, ws_.topk, idx, sws)
             for mode in (fb.FB_SPARSE_REFRESH, fb.FB_SPARSE_REUSE):
                 fb.fb_sparse_external_residual(d.shape, mode, q, d.K[s_], d.V[s_], ws_.key_block, ws_.topk, idx,
                                                ro, rm, rl, d.o, d.m, d.lse, wsb)

@@ -260,11 +260,18 @@ fb_status fb_refresh_step_prof(const fb_shape* shape, const void* q, const void*
  *   the largest score, ties to the lower block index, written in ascending block order to
  *   sel_idx [B,Hq,topk] int32.  If topk exceeds the number of blocks the tail is filled
  *   with -1 (consumers skip negative entries).  Scores are computed in fp32.
+ *   workspace: device scratch of >= fb_select_workspace_bytes(shape, key_block) bytes (mean
+ *   queries and block scores), or NULL.  With it the scoring runs as kernels of its own across
+ *   the whole GPU and only the selection proper runs one workgroup per head; without it one
+ *   kernel does both (same result bit for bit, slower for prefixes of many key blocks).
+ *   A workspace that is given but too small is FB_ERR_WORKSPACE.
  */
 fb_status fb_pool_keys(const fb_shape* shape, const void* k_prefix, int32_t key_block,
                        float* k_pooled, void* hip_stream);
+size_t fb_select_workspace_bytes(const fb_shape* shape, int32_t key_block);
 fb_status fb_select_topk(const fb_shape* shape, const void* q, const float* k_pooled,
-                         int32_t key_block, int32_t topk, int32_t* sel_idx, void* hip_stream);
+                         int32_t key_block, int32_t topk, int32_t* sel_idx, void* workspace,
+                         size_t workspace_bytes, void* hip_stream);
 
 /*
  * Key-block selection by attention mass (appendix on adapting the sparse method to block

@@ -465,8 +465,17 @@ fb_status fb_pool_keys(const fb_shape* shape, const void* k_prefix, int32_t key_
   return FB_OK;
 }
 
+size_t fb_select_workspace_bytes(const fb_shape* shape, int32_t key_block) {
+  if (check_shape(shape) != FB_OK) return 0;
+  int nblk = 0;
+  if (check_key_block(shape, key_block, 0, &nblk) != FB_OK) return 0;
+  const size_t heads = (size_t)shape->batch * shape->n_q_heads;
+  return align256(heads * shape->head_dim * sizeof(float)) + align256(heads * nblk * sizeof(float)) + 256;
+}
+
 fb_status fb_select_topk(const fb_shape* shape, const void* q, const float* k_pooled, int32_t key_block,
-                         int32_t topk, int32_t* sel_idx, void* hip_stream) {
+                         int32_t topk, int32_t* sel_idx, void* workspace, size_t workspace_bytes,
+                         void* hip_stream) {
   fb_status st = check_shape(shape);
   if (st != FB_OK) return st;
   int nblk = 0;
@@ -474,10 +483,16 @@ fb_status fb_select_topk(const fb_shape* shape, const void* q, const float* k_po
   if (st != FB_OK) return st;
   if (topk == 0) return FB_OK;
   if (!q || !sel_idx || (nblk > 0 && !k_pooled)) return FB_ERR_NULL;
-  if (!aligned16(q) || !aligned16(k_pooled) || !aligned16(sel_idx)) return FB_ERR_ALIGN;
+  if (!aligned16(q) || !aligned16(k_pooled) || !aligned16(sel_idx) || !aligned16(workspace)) return FB_ERR_ALIGN;
+  if (workspace && workspace_bytes < fb_select_workspace_bytes(shape, key_block)) return FB_ERR_WORKSPACE;
   fb::SelectParams p;
   memset(&p, 0, sizeof(p));
   p.q = q; p.k_pooled = k_pooled; p.sel_idx = sel_idx;
+  if (workspace) {
+    p.qbar_ws = (float*)workspace;
+    p.scores_ws = (float*)((char*)workspace +
+                           align256((size_t)shape->batch * shape->n_q_heads * shape->head_dim * sizeof(float)));
+  }
   p.B = shape->batch; p.Hq = shape->n_q_heads; p.Hkv = shape->n_kv_heads;
   p.G = shape->n_q_heads / shape->n_kv_heads; p.Bq = shape->block_len; p.D = shape->head_dim;
   p.nblk = nblk; p.topk = topk; p.is_bf16 = shape->dtype == FB_BF16;

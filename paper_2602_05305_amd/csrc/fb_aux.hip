@@ -479,7 +479,105 @@ __device__ __forceinline__ int block_exclusive_prefix(int v, int* wtot, int tid)
   return base + inc - v;
 }
 
-// grid (B*Hq), 256 threads, dynamic LDS: qbar[D] | red[256] | key[nblk] | flag[nblk]
+typedef uint32_t sel_u32x4 __attribute__((ext_vector_type(4)));
+
+// Mean over the Bq rows of query head bh -> qbar[D] (LDS).  Thread = (row lane, 16-byte chunk of a row):
+// up to eight row loads in flight per trip, per-lane sums in row order, then the row lanes meet through
+// red[256 * 8] in lane order.  Ends with a barrier.
+__device__ __forceinline__ void head_qbar(const void* q, int bh, int Bq, int D, int is_bf16, float* qbar,
+                                          float* red, int tid) {
+  const int E = is_bf16 ? 8 : 4, esz = is_bf16 ? 2 : 4;
+  const int cpr = D / E, nrl = 256 / cpr, chunk = tid % cpr, rl = tid / cpr;
+  const size_t rowbytes = (size_t)D * esz;
+  const char* base = (const char*)q + (size_t)bh * Bq * rowbytes + (size_t)chunk * 16;
+  float acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+  for (int r0 = rl; r0 < Bq; r0 += 8 * nrl) {
+    sel_u32x4 x[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int r = r0 + u * nrl;
+      if (r < Bq) x[u] = *(const sel_u32x4*)(base + (size_t)r * rowbytes);
+      else x[u] = sel_u32x4{0u, 0u, 0u, 0u};
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if (is_bf16) {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          acc[2 * w] += __uint_as_float(x[u][w] << 16);
+          acc[2 * w + 1] += __uint_as_float(x[u][w] & 0xffff0000u);
+        }
+      } else {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) acc[w] += __uint_as_float(x[u][w]);
+      }
+    }
+  }
+  for (int i = 0; i < E; ++i) red[rl * D + chunk * E + i] = acc[i];
+  __syncthreads();
+  if (tid < D) {
+    float t = 0.f;
+    for (int j = 0; j < nrl; ++j) t += red[j * D + tid];
+    qbar[tid] = t / (float)Bq;
+  }
+  __syncthreads();
+}
+
+// One 16-byte chunk of a pooled-key row against the same chunk of a mean query.
+__device__ __forceinline__ float chunk_dot(const float4 a, const float4 q4) {
+  return fmaf(a.w, q4.w, fmaf(a.z, q4.z, fmaf(a.y, q4.y, a.x * q4.x)));
+}
+
+// grid (B*Hq), 256 threads: qbar_out[bh][D] = mean query of the head (first kernel of the three-kernel selection).
+__global__ __launch_bounds__(256) void head_qbar_kernel(const SelectParams p) {
+  __shared__ float qbar[128];
+  __shared__ float red[256 * 8];
+  head_qbar(p.q, blockIdx.x, p.Bq, p.D, p.is_bf16, qbar, red, threadIdx.x);
+  if ((int)threadIdx.x < p.D) p.qbar_ws[(size_t)blockIdx.x * p.D + threadIdx.x] = qbar[threadIdx.x];
+}
+
+// grid (ceil(nblk / rows per workgroup), B*Hkv), 256 threads: scores of a run of key blocks for the G heads of
+// a KV group: every pooled row is read once for the whole group.  A wavefront instruction covers 64 / (D/4)
+// rows; kScoreU of them are in flight; a row's partial sums meet by xor-shuffles inside its lane group (the
+// same arithmetic, in the same order, as the one-kernel selection).
+constexpr int kScoreU = 4;
+__global__ __launch_bounds__(256) void block_scores_kernel(const SelectParams p) {
+  extern __shared__ __align__(16) float qb[];              // [G][D]
+  const int D = p.D, nblk = p.nblk, tid = threadIdx.x;
+  const int bk = blockIdx.y, b = bk / p.Hkv, kvh = bk % p.Hkv;
+  const int cpr = D / 4, rpw = 64 / cpr;
+  const int lane = tid & 63, wave = tid >> 6, c = lane % cpr, rsub = lane / cpr;
+  const int r_base = blockIdx.x * (4 * rpw * kScoreU) + wave * (rpw * kScoreU) + rsub;
+  const float* kp = p.k_pooled + (size_t)bk * nblk * D;
+  float4 a[kScoreU];
+#pragma unroll
+  for (int u = 0; u < kScoreU; ++u) {
+    const int r = min(r_base + u * rpw, nblk - 1);         // clamped: in bounds, result discarded
+    a[u] = *(const float4*)(kp + (size_t)r * D + 4 * c);
+  }
+  const float* qsrc = p.qbar_ws + (size_t)(b * p.Hq + kvh * p.G) * D;
+  for (int i = tid; i < p.G * D; i += 256) qb[i] = qsrc[i];
+  __syncthreads();
+  for (int g = 0; g < p.G; ++g) {
+    const float4 q4 = *(const float4*)(qb + g * D + 4 * c);
+    float part[kScoreU];
+#pragma unroll
+    for (int u = 0; u < kScoreU; ++u) part[u] = chunk_dot(a[u], q4);
+    for (int o = cpr / 2; o > 0; o >>= 1)
+#pragma unroll
+      for (int u = 0; u < kScoreU; ++u) part[u] += __shfl_xor(part[u], o, 64);
+    float* dst = p.scores_ws + (size_t)(b * p.Hq + kvh * p.G + g) * nblk;
+#pragma unroll
+    for (int u = 0; u < kScoreU; ++u) {
+      const int r = r_base + u * rpw;
+      if (c == 0 && r < nblk) dst[r] = part[u];
+    }
+  }
+}
+
+// grid (B*Hq), 256 threads, dynamic LDS: qbar[D] | red[256 * 8] | key[nblk] | flag[nblk]
 // Selection = the k largest scores, ties to the lower block index: the k-th largest key T is
 // found by a 4-pass radix select over its bytes (256-bin LDS histogram of the keys that match the
 // digits fixed so far), then blocks with key > T are taken plus the first k - count(key > T)
@@ -488,7 +586,7 @@ __global__ __launch_bounds__(256) void select_topk_kernel(const SelectParams p) 
   extern __shared__ __align__(16) float lds[];
   float* qbar = lds;
   float* red = qbar + p.D;
-  uint32_t* key = (uint32_t*)(red + 256);
+  uint32_t* key = (uint32_t*)(red + 256 * 8);
   int* flag = (int*)(key + p.nblk);
   __shared__ int sel_digit, sel_rest, wtot[4];
 
@@ -503,6 +601,16 @@ __global__ __launch_bounds__(256) void select_topk_kernel(const SelectParams p) 
       const float* r = rm + (size_t)c * ((size_t)p.Hq * p.Bq);
       float s = 0.f;
       int i = 0;
+      if ((p.Bq & 3) == 0) {                   // 16-byte aligned rows: up to 32 masses per trip in eight wide loads
+        for (; i < p.Bq; i += 32) {
+          float4 x[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u)
+            x[u] = (i + 4 * u < p.Bq) ? *(const float4*)(r + i + 4 * u) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+          for (int u = 0; u < 8; ++u) s += x[u].x, s += x[u].y, s += x[u].z, s += x[u].w;
+        }
+      }
       for (; i + 8 <= p.Bq; i += 8) {          // eight independent loads per trip, summed in index order
         float x[8];
 #pragma unroll
@@ -515,19 +623,12 @@ __global__ __launch_bounds__(256) void select_topk_kernel(const SelectParams p) 
       key[c] = order_key(s);
       if (p.score_out != nullptr) p.score_out[(size_t)bh * nblk + c] = s;
     }
+  } else if (p.scores_ws != nullptr) {
+    // scores already computed by block_scores_kernel
+    const float* sc = p.scores_ws + (size_t)bh * nblk;
+    for (int c = tid; c < nblk; c += 256) key[c] = order_key(sc[c]);
   } else {
-    {  // mean over the block's query rows
-      const int d = tid % D, tl = tid / D, ntl = 256 / D;
-      float s = 0.f;
-      for (int r = tl; r < p.Bq; r += ntl) s += load_elem(p.q, ((size_t)bh * p.Bq + r) * D + d, p.is_bf16);
-      red[tid] = s;
-      __syncthreads();
-      if (tl == 0) {
-        for (int j = 1; j < ntl; ++j) s += red[j * D + d];
-        qbar[d] = s / (float)p.Bq;
-      }
-      __syncthreads();
-    }
+    head_qbar(p.q, bh, p.Bq, D, p.is_bf16, qbar, red, tid);
     // score = qbar . pooled key of the block.  A wavefront reads 64 consecutive 16-byte chunks per
     // instruction (2 rows at D = 128, 4 at D = 64); a row's partial sums meet by xor-shuffles inside
     // its lane group; 8 such loads are in flight per wavefront.
@@ -543,7 +644,7 @@ __global__ __launch_bounds__(256) void select_topk_kernel(const SelectParams p) 
       for (int u = 0; u < U; ++u) {
         const int r = min(r0 + u * 4 * rpw + rsub, nblk - 1);       // clamped: in bounds, result discarded
         const float4 a = *(const float4*)(kp + (size_t)r * D + 4 * c);
-        part[u] = fmaf(a.w, q4.w, fmaf(a.z, q4.z, fmaf(a.y, q4.y, a.x * q4.x)));
+        part[u] = chunk_dot(a, q4);
       }
       for (int o = cpr / 2; o > 0; o >>= 1)
 #pragma unroll
@@ -771,9 +872,16 @@ hipError_t launch_refresh_fold(const CombineParams& p, hipStream_t s) {
 
 hipError_t launch_select_topk(const SelectParams& p, hipStream_t s) {
   static bool raised = false;
-  const size_t lds = (size_t)(p.D + 256 + 2 * p.nblk) * 4;
+  const size_t lds = (size_t)(p.D + 256 * 8 + 2 * p.nblk) * 4;
   hipError_t e = ensure_lds(select_topk_kernel, lds, raised);
   if (e != hipSuccess) return e;
+  if (p.scores_ws != nullptr && p.rowmass == nullptr && p.nblk > 0) {
+    // three kernels: mean queries, block scores spread over the whole chip, then the selection proper
+    hipLaunchKernelGGL(head_qbar_kernel, dim3(p.B * p.Hq), dim3(256), 0, s, p);
+    const int rows_per_wg = 4 * (64 / (p.D / 4)) * kScoreU;
+    const dim3 grid((unsigned)((p.nblk + rows_per_wg - 1) / rows_per_wg), (unsigned)(p.B * p.Hkv));
+    hipLaunchKernelGGL(block_scores_kernel, grid, dim3(256), (size_t)p.G * p.D * sizeof(float), s, p);
+  }
   hipLaunchKernelGGL(select_topk_kernel, dim3(p.B * p.Hq), dim3(256), lds, s, p);
   return hipGetLastError();
 }

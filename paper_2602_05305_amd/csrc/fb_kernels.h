@@ -109,6 +109,9 @@ struct SelectParams {
   // score source "attention mass": per-row masses [B][nblk][Hq*Bq] (then q / k_pooled are unused), and an
   // optional copy of the block scores [B,Hq,nblk]
   const float* rowmass; float* score_out;
+  // optional scratch: mean queries [B,Hq,D] and block scores [B,Hq,nblk]; both set = scoring runs as kernels of
+  // its own over the whole chip instead of inside the (one workgroup per head) selection kernel
+  float* qbar_ws; float* scores_ws;
 };
 
 // Attention mass of every (query row, key block): sum over the block's keys of exp(s - lse).

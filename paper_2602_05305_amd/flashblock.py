@@ -60,7 +60,9 @@ _SIGNATURES = {
     "fb_refresh_step": (c_int, [POINTER(fb_shape)] + [c_void_p] * 11 + [c_size_t, c_void_p]),
     "fb_refresh_step_prof": (c_int, [POINTER(fb_shape)] + [c_void_p] * 11 + [c_size_t] + [c_void_p] * 4),
     "fb_pool_keys": (c_int, [POINTER(fb_shape), c_void_p, c_int32, c_void_p, c_void_p]),
-    "fb_select_topk": (c_int, [POINTER(fb_shape), c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p]),
+    "fb_select_workspace_bytes": (c_size_t, [POINTER(fb_shape), c_int32]),
+    "fb_select_topk": (c_int, [POINTER(fb_shape), c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_size_t,
+                               c_void_p]),
     "fb_select_mass_workspace_bytes": (c_size_t, [POINTER(fb_shape), c_int32]),
     "fb_select_topk_mass": (c_int, [POINTER(fb_shape), c_void_p, c_void_p, c_void_p, c_int32, c_int32, c_void_p,
                                     c_void_p, c_void_p, c_size_t, c_void_p]),
@@ -220,9 +222,14 @@ def fb_pool_keys(shape, k_prefix, key_block, k_pooled, stream=None):
     _check(st, "fb_pool_keys")
 
 
-def fb_select_topk(shape, q, k_pooled, key_block, topk, sel_idx, stream=None):
+def fb_select_workspace_bytes(shape, key_block) -> int:
+    return int(load_library().fb_select_workspace_bytes(ctypes.byref(shape), key_block))
+
+
+def fb_select_topk(shape, q, k_pooled, key_block, topk, sel_idx, workspace=None, stream=None):
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     st = load_library().fb_select_topk(ctypes.byref(shape), _ptr(q), _ptr(k_pooled), key_block, topk, _ptr(sel_idx),
-                                       _stream(stream))
+                                       _ptr(workspace), nbytes, _stream(stream))
     _check(st, "fb_select_topk")
 
 

@@ -211,8 +211,14 @@ def test_sparse_error_paths():
     assert call(ctypes.byref(s), 0, *a) == fb.FB_ERR_ALIGN
     assert lib.fb_pool_keys(ctypes.byref(s), FAKE, 32, FAKE, None) == fb.FB_ERR_UNSUPPORTED
     assert lib.fb_pool_keys(ctypes.byref(s), None, 64, FAKE, None) == fb.FB_ERR_NULL
-    assert lib.fb_select_topk(ctypes.byref(s), None, FAKE, 64, 2, FAKE, None) == fb.FB_ERR_NULL
-    assert lib.fb_select_topk(ctypes.byref(s), FAKE, FAKE, 64, 2, ODD, None) == fb.FB_ERR_ALIGN
+    assert lib.fb_select_topk(ctypes.byref(s), None, FAKE, 64, 2, FAKE, None, 0, None) == fb.FB_ERR_NULL
+    assert lib.fb_select_topk(ctypes.byref(s), FAKE, FAKE, 64, 2, ODD, None, 0, None) == fb.FB_ERR_ALIGN
+    n = fb.fb_select_workspace_bytes(s, 64)
+    heads = s.batch * s.n_q_heads
+    assert n >= heads * (s.head_dim + -(-s.prefix_len // 64)) * 4 and n % 256 == 0
+    assert fb.fb_select_workspace_bytes(s, 48) == 0
+    assert lib.fb_select_topk(ctypes.byref(s), FAKE, FAKE, 64, 2, FAKE, FAKE, n - 1, None) == fb.FB_ERR_WORKSPACE
+    assert lib.fb_select_topk(ctypes.byref(s), FAKE, FAKE, 64, 2, FAKE, ODD, n, None) == fb.FB_ERR_ALIGN
     huge = _ok_shape(prefix_len=64 * 16385)
     assert lib.fb_pool_keys(ctypes.byref(huge), FAKE, 64, FAKE, None) == fb.FB_ERR_UNSUPPORTED
 

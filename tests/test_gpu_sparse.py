@@ -102,6 +102,8 @@ def test_sparse_refresh_step_is_exact_and_negative_or_duplicate_indices():
     ("f32", 1, 4, 2, 64, 4096, 16, 64, 16),
     ("bf16", 2, 8, 2, 128, 8000, 32, 64, 30),
     ("bf16", 1, 2, 2, 128, 700, 8, 128, 9),     # topk beyond the 6 blocks: tail filled with -1
+    ("f32", 1, 6, 2, 128, 64 * 37 + 5, 12, 64, 7),   # 3 heads per group, ragged last block, rows not a lane multiple
+    ("bf16", 1, 8, 1, 64, 64 * 70, 40, 64, 20),      # 8 heads per group, head_dim 64, more rows than one trip
 ])
 def test_select_topk_matches_oracle(dtype, B, Hq, Hkv, d, P, Bq, kb, topk):
     """fb_pool_keys + fb_select_topk against the oracle's selection.  The selected sets must be
@@ -116,7 +118,12 @@ def test_select_topk_matches_oracle(dtype, B, Hq, Hkv, d, P, Bq, kb, topk):
     fb.fb_pool_keys(shape, T.to_dev(Kp, dtype), kb, pooled)
     idx = torch.full((B, Hq, topk), -7, device=T.DEV, dtype=torch.int32)
     fb.fb_select_topk(shape, T.to_dev(Q, dtype), pooled, kb, topk, idx)
+    # the same selection with the scoring spread over the chip (workspace given): identical indices
+    idx_ws = torch.full((B, Hq, topk), -7, device=T.DEV, dtype=torch.int32)
+    sws = torch.empty(fb.fb_select_workspace_bytes(shape, kb), device=T.DEV, dtype=torch.uint8)
+    fb.fb_select_topk(shape, T.to_dev(Q, dtype), pooled, kb, topk, idx_ws, sws)
     torch.cuda.synchronize()
+    assert torch.equal(idx, idx_ws)
     ora_pooled = orc.pool_keys(Kp, kb)
     assert np.abs(pooled.double().cpu().numpy() - ora_pooled).max() < 1e-5
     sc = orc.select_scores(Q, ora_pooled)
