@@ -6,6 +6,15 @@
 namespace fb {
 namespace {
 
+// Workgroup ids are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of work items, the same
+// cut the attention pass uses for its (batch, KV head, split) units, so that rows are folded on the XCD whose
+// L2 their split partials were written through.
+__device__ __forceinline__ uint32_t xcd_contiguous(uint32_t bid, uint32_t n) {
+  const uint32_t q8 = n / 8, r8 = n % 8, xcd = bid % 8, j = bid / 8;
+  return (xcd < r8 ? xcd * (q8 + 1) : r8 * (q8 + 1) + (xcd - r8) * q8) + j;
+}
+
+
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -171,7 +180,7 @@ __global__ __launch_bounds__(256) void combine_wide_kernel(const CombineParams p
   __shared__ Folded sh[2][256];
   const int per_row = p.D / 4, nsl = 256 / per_row;
   const int tid = threadIdx.x, sl = tid / per_row, c4 = tid % per_row;
-  const size_t row = blockIdx.x;
+  const size_t row = xcd_contiguous(blockIdx.x, gridDim.x);
   if (p.head_on != nullptr && p.head_on[row / p.Bq] == 0) return;   // workgroup-uniform
   const bool have_res_set = p.ws_o2 != nullptr;
   sh[0][tid] = fold_strided(p.ws_o, p.ws_m, p.ws_l, p.nsplit, p.rows, row, p.D, c4, sl, nsl);
@@ -230,7 +239,7 @@ __global__ __launch_bounds__(256) void refresh_fold_kernel(const CombineParams p
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int sl = tid / per_row, c4 = tid % per_row;
-  const size_t row0 = (size_t)blockIdx.x * RW;     // Bq % RW == 0: the RW rows belong to one query head
+  const size_t row0 = (size_t)xcd_contiguous(blockIdx.x, gridDim.x) * RW;     // Bq % RW == 0: the RW rows belong to one query head
 
   // first CH splits of this thread for all RW rows: every load is issued before any is used, and the
   // block's K / V / q staging below runs while they are in flight
