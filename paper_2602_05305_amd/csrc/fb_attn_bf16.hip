@@ -293,7 +293,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
 // groups own the same 128 rows, stream alternate tiles of the workgroup's key range through their
 // own pair of LDS stages, and group 1 hands its statistics to group 0 through LDS at the end.
 // Same wavefronts per CU as two 4-wave workgroups, half as many split partials to write and fold.
-template <int D, int MODE, int KT, int WS, int NG>
+template <int D, int MODE, int KT, int WS, int NG, bool RP = false>
 __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS > 1) || MODE == kPassSparseRefresh) ? 1 : 2) void attn_bf16_kernel(const PassParams p) {
   using C = Cfg<D, KT>;
   extern __shared__ __align__(16) unsigned char smem_all[];
@@ -303,9 +303,13 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
   // head routes it to its set, and every wavefront keeps ONE set: two wavefronts per SIMD
   // instead of the one that two sets in a single wavefront allow.
   constexpr bool kSetSplit = (MODE == kPassSparseRefresh && NG == 2);
-  constexpr int TG = kSetSplit ? 1 : NG;          // wavefront groups that own separate tile streams
+  // RP ("row pair", compute-bound passes with many rows): the two wavefront groups own DIFFERENT rows (256 per
+  // workgroup) and share one tile stream and its LDS stages, so a staged tile serves twice the rows.
+  static_assert(!RP || (NG == 2 && WS == 1 && (MODE == kPassDense || MODE == kPassInternal)), "row-pair mode");
+  constexpr bool kShare = kSetSplit || RP;        // one tile stream, loaded cooperatively by both groups
+  constexpr int TG = kShare ? 1 : NG;             // wavefront groups that own separate tile streams
   static_assert(NG == 1 || MODE == kPassDense || MODE == kPassDenseHeads || MODE == kPassDensePaged || MODE == kPassRefreshFused ||
-                    MODE == kPassSparseReuse || kSetSplit,
+                    MODE == kPassSparseReuse || kSetSplit || MODE == kPassInternal,
                 "unsupported group mode");
 
   // wavefront-uniform by construction; in the list-driven passes (paged, sparse reuse), telling the compiler
@@ -316,7 +320,7 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
                            : 0;
   const int tid = threadIdx.x & 255, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, h = lane >> 5;
-  unsigned char* smem = smem_all + (kSetSplit ? 0 : grp) * 2 * C::STAGE;
+  unsigned char* smem = smem_all + (kShare ? 0 : grp) * 2 * C::STAGE;
 
   // XCD-aware remap: hardware deals consecutive workgroup ids round-robin to the 8 XCDs; make
   // each XCD own a contiguous range of work items (row tiles of one KV head are adjacent).
@@ -387,10 +391,10 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
   // WS wavefronts share one 32-row group and split the output columns between them (each repeats
   // the cheap score / softmax work): used when the pass has too few rows to fill the GPU, where
   // the time is a single wavefront's instruction stream, not throughput.
-  constexpr int ROWS = kRowsPerWgBf16 / WS;
+  constexpr int ROWS = RP ? 2 * kRowsPerWgBf16 : kRowsPerWgBf16 / WS;
   constexpr int NDBL = C::NDB / WS;
   const int db_base = (wave % WS) * NDBL;
-  const int row = rt * ROWS + (wave / WS) * 32 + l32;      // group-flattened row of this lane
+  const int row = rt * ROWS + (RP ? (int)(threadIdx.x >> 6) * 32 : (wave / WS) * 32) + l32;      // group-flattened row of this lane
   const bool row_ok = row < nrows;
   const size_t grow = (size_t)(b * p.Hq + kvh * p.G) * p.Bq + row;   // global row index
   const size_t grow_last = (size_t)(b * p.Hq + kvh * p.G) * p.Bq + (nrows - 1);
@@ -474,12 +478,12 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
     const int rot = (MODE == kPassInternal || ntiles <= 0) ? 0      // the block's K/V are small and cache-resident
                                                             : (int)((rsrc * 13u + (rsrc >> 5) * 7u) % (unsigned)ntiles);
     auto tile_entry = [&](int i) -> int {   // i-th tile of this wavefront group
-      int j = TG * i + (kSetSplit ? 0 : grp) + rot;
+      int j = TG * i + (kShare ? 0 : grp) + rot;
       if (j >= ntiles) j -= ntiles;
       return tr.begin + j;
     };
     const int common = ntiles / TG;                 // tiles every group has
-    const bool extra = !kSetSplit && (ntiles % TG) > grp;   // this group has one more
+    const bool extra = !kShare && (ntiles % TG) > grp;   // this group has one more
     TileRegs regs;
     // Tile descriptors (first key, selection mask) are looked up two tiles ahead: in the list-driven
     // sparse reuse pass they come from dependent scalar loads, whose latency would otherwise sit
@@ -491,9 +495,9 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
         // index k0 + r addresses row (k0 % page_size) + r of this KV head's slab of the page
         const int in_page = k0 - (int)(fastdiv((uint32_t)k0, p.div_page) * p.div_page.d);
         const long long off = (((long long)aux * p.Hkv + kvh) * p.page_size + in_page - k0) * D;
-        tile_load<D, KT, kSetSplit>(regs, K + off, V + off, k0, nkeys, tid, grp);
+        tile_load<D, KT, kShare>(regs, K + off, V + off, k0, nkeys, tid, grp);
       } else {
-        tile_load<D, KT, kSetSplit>(regs, K, V, k0, nkeys, tid, grp);
+        tile_load<D, KT, kShare>(regs, K, V, k0, nkeys, tid, grp);
       }
     };
     uint32_t mask_cur = 0, mask_next = 0, mask_nn = 0;
@@ -574,7 +578,7 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
     };
 
     if (ntiles > 0) {
-      if (common > 0 || extra) tile_store<D, KT, kSetSplit>(regs, smem, tid, grp);
+      if (common > 0 || extra) tile_store<D, KT, kShare>(regs, smem, tid, grp);
       __syncthreads();
       // the query registers have arrived by now (their loads went out with the first tile's); saying so here
       // keeps waits for them out of the tile loop, where in-order load counters would turn them into waits
@@ -586,7 +590,7 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
         if (i + 2 < mine) k0_nn = entry_k0(tile_entry(i + 2), mask_nn);
         load_tile(k0_next, mask_next);
         compute(smem + (i & 1) * C::STAGE, k0_cur, mask_cur);
-        tile_store<D, KT, kSetSplit>(regs, smem + ((i + 1) & 1) * C::STAGE, tid, grp);
+        tile_store<D, KT, kShare>(regs, smem + ((i + 1) & 1) * C::STAGE, tid, grp);
         __syncthreads();
         k0_cur = k0_next;
         mask_cur = mask_next;
@@ -598,7 +602,7 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
         if (extra) load_tile(k0_next, mask_next);
         compute(smem + (i & 1) * C::STAGE, k0_cur, mask_cur);
         if (TG > 1 && (ntiles % TG) != 0) {         // some group has one more tile (workgroup-uniform)
-          if (extra) tile_store<D, KT, kSetSplit>(regs, smem + ((i + 1) & 1) * C::STAGE, tid, grp);
+          if (extra) tile_store<D, KT, kShare>(regs, smem + ((i + 1) & 1) * C::STAGE, tid, grp);
           __syncthreads();
           if (extra) compute(smem + ((i + 1) & 1) * C::STAGE, k0_next, mask_next);
         }
@@ -827,17 +831,17 @@ __global__ __launch_bounds__(256) void block_mass_bf16_kernel(const MassParams p
   }
 }
 
-template <int D, int MODE, int KT, int WS, int NG>
+template <int D, int MODE, int KT, int WS, int NG, bool RP = false>
 hipError_t launch_one(const PassParams& p, hipStream_t s) {
   static bool attr_set = false;   // raising the dynamic-LDS limit is idempotent; the flag only saves calls
-  auto kern = attn_bf16_kernel<D, MODE, KT, WS, NG>;
-  constexpr int lds = Cfg<D, KT>::LDS * ((MODE == kPassSparseRefresh) ? 1 : NG);
+  auto kern = attn_bf16_kernel<D, MODE, KT, WS, NG, RP>;
+  constexpr int lds = Cfg<D, KT>::LDS * ((MODE == kPassSparseRefresh || RP) ? 1 : NG);
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  constexpr int rows_per_wg = kRowsPerWgBf16 / WS;
+  constexpr int rows_per_wg = RP ? 2 * kRowsPerWgBf16 : kRowsPerWgBf16 / WS;
   const int nrows = p.G * p.Bq;
   const int ntile_rows = (nrows + rows_per_wg - 1) / rows_per_wg;
   long long nwg = (long long)p.B * p.Hkv * ntile_rows * p.nsplit;
@@ -852,6 +856,18 @@ hipError_t launch_one(const PassParams& p, hipStream_t s) {
   return hipGetLastError();
 }
 
+// Row-pair workgroups pay off when the pass is compute-bound: many rows per KV head and enough 256-row
+// workgroups to give every CU one.
+inline bool use_row_pairs(const PassParams& p) {
+#if defined(FB_NO_RP)
+  return false;
+#else
+  const int nrows = p.G * p.Bq;
+  const long long wgs = (long long)p.B * p.Hkv * ((nrows + 2 * kRowsPerWgBf16 - 1) / (2 * kRowsPerWgBf16)) * p.nsplit;
+  return nrows >= 1024 && wgs >= 128;
+#endif
+}
+
 template <int D>
 hipError_t launch_d(const PassParams& p, PassMode mode, hipStream_t s) {
   constexpr int WSMAX = (D / 32 >= 4) ? 4 : 2;
@@ -862,6 +878,7 @@ hipError_t launch_d(const PassParams& p, PassMode mode, hipStream_t s) {
       // Small blocks (the paper's 4- and 8-token blocks: G*Bq <= 32 or 64 rows per KV group) would
       // leave three of the four row groups of a workgroup computing padding rows; there the
       // wavefronts share one or two 32-row groups and split the output columns instead.
+      if (use_row_pairs(p)) return launch_one<D, kPassDense, kKeyTile, 1, 2, true>(p, s);
       const int tiles = (p.nkeys + kKeyTile - 1) / kKeyTile;
       const bool groups2 = p.nsplit > 1 && tiles >= 8 * p.nsplit;
       const int nrows = p.G * p.Bq;
@@ -880,6 +897,7 @@ hipError_t launch_d(const PassParams& p, PassMode mode, hipStream_t s) {
       // Few rows (an LLM-sized block): the pass is one wavefront's run-once instruction stream.
       // Spread each 32-row group over WSMAX wavefronts (columns split) and, for a block of at
       // most 32 keys, use the 32-key tile: both shorten that stream.
+      if (use_row_pairs(p)) return launch_one<D, kPassInternal, kKeyTile, 1, 2, true>(p, s);
       const long long wgs = (long long)p.B * p.Hkv * ((p.G * p.Bq + kRowsPerWgBf16 - 1) / kRowsPerWgBf16);
       if (wgs < 128) {
         if (p.nkeys <= 32) return launch_one<D, kPassInternal, 32, WSMAX, 1>(p, s);

@@ -291,3 +291,16 @@ def test_fused_refresh_step(dtype, B, Hq, Hkv, d, P, Bq):
 def test_bf16_maximum_head_grouping(B, Hq, Hkv, d, P, Bq):
     _compare_block(_wl("bf16", B, Hq, Hkv, d, P, Bq), seed=81)
     _compare_refresh_step(_wl("bf16", B, Hq, Hkv, d, P, Bq), seed=82)
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,d,P,Bq,n_splits", [
+    (1, 8, 8, 128, 333, 4100, 0),     # 17 row tiles of 256 per head, ragged last row tile and key tile, one split
+    (1, 8, 8, 128, 700, 4100, 3),     # split partials + combine
+    (2, 8, 4, 64, 200, 1300, 0),      # head_dim 64, 2 query heads per KV head: 2600 rows per KV group, batch 2
+    (1, 16, 16, 128, 130, 2049, 2),   # one row past a row-tile boundary; block keys past a tile boundary
+])
+def test_bf16_many_rows_wide_workgroups(B, Hq, Hkv, d, P, Bq, n_splits):
+    """Passes with >= 1024 rows per KV head and >= 128 workgroups of 256 rows run the variant in which
+    a wavefront owns two 32-row groups (external pass, with and without splits, and the internal pass
+    with its merge epilogue, whose key range here is the many-tile block itself)."""
+    _compare_block(_wl("bf16", B, Hq, Hkv, d, P, Bq, S=2, R=2), seed=23, n_splits=n_splits)
