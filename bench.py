@@ -213,8 +213,8 @@ def roofline_obj(w, attn_ms, traffic=None, fused=False):
     streams_block = fused and (w.block_len > 64 or w.block_len % 4 != 0)
     alg = external_algorithmic_bytes(w, streams_block)
     ach = alg / (attn_ms * 1e-3) / 1e9
-    kern = ("fb::attn_bf16_kernel<128, 6, 64, 1, 2> (refresh step: prefix splits + the block's own keys, one streaming launch)"
-            if streams_block else "fb::attn_bf16_kernel<128, 0, 64, 1, 2> (external pass, streaming attention kernel)")
+    kern = ("fb::attn_bf16_kernel<128, 6, 64, 1, 2, false> (refresh step: prefix splits + the block's own keys, one streaming launch)"
+            if streams_block else "fb::attn_bf16_kernel<128, 0, 64, 1, 2, false> (external pass, streaming attention kernel)")
     return {"bound": "hbm", "kernel": kern,
             "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": traffic,
