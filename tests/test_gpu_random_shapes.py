@@ -110,3 +110,24 @@ def test_random_paged_shape(case):
     n_splits = int(rng.choice([0, 0, 1, 2, 5]))
     w = wl.Workload(f"rpg{case}", B, Hkv * G, Hkv, d, pmax, Bq, 1, 1, dtype, 1.0)
     PG._run_paged(w, seed=300 + case, page_size=page, lens=[int(x) for x in lens], n_splits=n_splits)
+
+
+@pytest.mark.parametrize("case", range(10))
+def test_random_head_mask_shape(case):
+    """Per-head refresh with random masks and hints (0 = none, the true count, or a wrong count)."""
+    import test_gpu_dense as DN
+    rng = np.random.default_rng([20260208, case])
+    dtype = "bf16" if rng.random() < 0.8 else "f32"
+    d = int(rng.choice([64, 128]))
+    Hkv = int(rng.choice([1, 2, 3, 6]))
+    G = int(rng.choice([1, 1, 2, 4]))
+    B = int(rng.choice([1, 2]))
+    if dtype == "bf16":
+        Bq = int(rng.choice([8, 32, 48, 150, 300]))
+        P = int(rng.choice([200, 700, 2100, 4200]))
+    else:
+        Bq, P = int(rng.integers(1, 10)), int(rng.integers(1, 400))
+    Hq = Hkv * G
+    mask = (rng.random(B * Hq) < rng.choice([0.15, 0.5, 0.9])).astype(int).tolist()
+    hint = int(rng.choice([0, sum(mask), max(1, sum(mask) // 2), Hq]))
+    DN.test_head_wise_selective_refresh(dtype, B, Hq, Hkv, d, P, Bq, mask, hint)
