@@ -213,8 +213,12 @@ def roofline_obj(w, attn_ms, traffic=None, fused=False):
     streams_block = fused and (w.block_len > 64 or w.block_len % 4 != 0)
     alg = external_algorithmic_bytes(w, streams_block)
     ach = alg / (attn_ms * 1e-3) / 1e9
-    kern = ("fb::attn_bf16_kernel<128, 6, 64, 1, 2, false> (refresh step: prefix splits + the block's own keys, one streaming launch)"
-            if streams_block else "fb::attn_bf16_kernel<128, 0, 64, 1, 2, false> (external pass, streaming attention kernel)")
+    # last template argument of the external pass: 2 = tiles fetched two ahead (>= 48 tiles per workgroup), else 0
+    from paper_2602_05305_amd import flashblock as fb
+    ns = fb.fb_external_splits(fb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.block_len, w.prefix_len, w.dtype))
+    var = 2 if -(-w.prefix_len // 64) >= 48 * max(ns, 1) else 0
+    kern = ("fb::attn_bf16_kernel<128, 6, 64, 1, 2, 0> (refresh step: prefix splits + the block's own keys, one streaming launch)"
+            if streams_block else f"fb::attn_bf16_kernel<128, 0, 64, 1, 2, {var}> (external pass, streaming attention kernel)")
     return {"bound": "hbm", "kernel": kern,
             "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": traffic,

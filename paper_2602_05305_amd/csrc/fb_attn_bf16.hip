@@ -10,10 +10,12 @@
 //   byte is fetched once per pass); wavefront w owns rows [32w, 32w+32).
 //   grid = batch * Hkv * row_tiles * nsplit workgroups, remapped so that workgroups that share
 //   K/V (row tiles of one KV head) land on the same XCD / L2.
-//   Variants of the one kernel template <D, MODE, KT, WS, NG> (picked on the host, launch_d):
+//   Variants of the one kernel template <D, MODE, KT, WS, NG, VAR> (picked on the host, launch_d):
 //   NG = 2: 8 wavefronts, two groups stream interleaved tiles and merge through LDS (or, in the
 //   sparse refresh pass, own one accumulator set each); WS = 2/4: wavefronts share 32 rows and
-//   split the output columns (few rows per KV group); KT = 32: internal pass over <= 32 keys.
+//   split the output columns (few rows per KV group); KT = 32: internal pass over <= 32 keys;
+//   VAR = 1: row pair (the two groups own different rows, 256 per workgroup, one shared tile
+//   stream: compute-bound passes with many rows); VAR = 2: tiles fetched two ahead (long streams).
 //   MODE: dense external, internal + merge epilogue, sparse refresh, sparse reuse, per-head
 //   refresh, paged external, fused refresh step (PassMode in fb_kernels.h).
 // Per 64-key tile
@@ -293,7 +295,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
 // groups own the same 128 rows, stream alternate tiles of the workgroup's key range through their
 // own pair of LDS stages, and group 1 hands its statistics to group 0 through LDS at the end.
 // Same wavefronts per CU as two 4-wave workgroups, half as many split partials to write and fold.
-template <int D, int MODE, int KT, int WS, int NG, bool RP = false>
+template <int D, int MODE, int KT, int WS, int NG, int VAR = 0>
 __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS > 1) || MODE == kPassSparseRefresh) ? 1 : 2) void attn_bf16_kernel(const PassParams p) {
   using C = Cfg<D, KT>;
   extern __shared__ __align__(16) unsigned char smem_all[];
@@ -302,6 +304,7 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
   // LDS stages (group 0 loads K, group 1 loads V), each wavefront computes a tile only if its
   // head routes it to its set, and every wavefront keeps ONE set: two wavefronts per SIMD
   // instead of the one that two sets in a single wavefront allow.
+  constexpr bool RP = (VAR == 1);
   constexpr bool kSetSplit = (MODE == kPassSparseRefresh && NG == 2);
   // RP ("row pair", compute-bound passes with many rows): the two wavefront groups own DIFFERENT rows (256 per
   // workgroup) and share one tile stream and its LDS stages, so a staged tile serves twice the rows.
@@ -577,6 +580,33 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
       }
     };
 
+    // Dense split pass with two wavefront groups: tiles are fetched TWO ahead (two register sets that alternate),
+    // so each group keeps two 32 KB tiles in flight instead of one; with one, the bytes in flight per CU are just
+    // what the HBM latency-bandwidth product asks for, with no slack.
+    static_assert(VAR != 2 || (MODE == kPassDense && NG == 2 && WS == 1), "deep-prefetch variant");
+    constexpr bool kDeep = (VAR == 2);
+    if constexpr (kDeep) {
+      if (ntiles > 0) {
+        const int maxmine = common + ((ntiles % TG) != 0 ? 1 : 0);      // workgroup-uniform trip count
+        auto k0_of = [&](int i) -> int { return tile_entry(i) * KT; };
+        TileRegs regs_b;
+        if (mine > 1) tile_load<D, KT, false>(regs_b, K, V, k0_of(1), nkeys, tid, grp);
+        if (mine > 0) tile_store<D, KT, false>(regs, smem, tid, grp);
+        __syncthreads();
+#pragma unroll
+        for (int ks = 0; ks < C::NKS; ++ks) asm volatile("" ::"v"(qreg[ks]));
+        auto step = [&](int i, TileRegs& r_load, TileRegs& r_store) __attribute__((always_inline)) {
+          if (i + 2 < mine) tile_load<D, KT, false>(r_load, K, V, k0_of(i + 2), nkeys, tid, grp);
+          if (i < mine) compute(smem + (i & 1) * C::STAGE, k0_of(i), 0xffffffffu);
+          if (i + 1 < mine) tile_store<D, KT, false>(r_store, smem + ((i + 1) & 1) * C::STAGE, tid, grp);
+          __syncthreads();
+        };
+        for (int i = 0; i < maxmine; i += 2) {
+          step(i, regs, regs_b);
+          if (i + 1 < maxmine) step(i + 1, regs_b, regs);
+        }
+      }
+    } else
     if (ntiles > 0) {
       if (common > 0 || extra) tile_store<D, KT, kShare>(regs, smem, tid, grp);
       __syncthreads();
@@ -831,10 +861,11 @@ __global__ __launch_bounds__(256) void block_mass_bf16_kernel(const MassParams p
   }
 }
 
-template <int D, int MODE, int KT, int WS, int NG, bool RP = false>
+template <int D, int MODE, int KT, int WS, int NG, int VAR = 0>
 hipError_t launch_one(const PassParams& p, hipStream_t s) {
   static bool attr_set = false;   // raising the dynamic-LDS limit is idempotent; the flag only saves calls
-  auto kern = attn_bf16_kernel<D, MODE, KT, WS, NG, RP>;
+  constexpr bool RP = (VAR == 1);
+  auto kern = attn_bf16_kernel<D, MODE, KT, WS, NG, VAR>;
   constexpr int lds = Cfg<D, KT>::LDS * ((MODE == kPassSparseRefresh || RP) ? 1 : NG);
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
@@ -878,7 +909,7 @@ hipError_t launch_d(const PassParams& p, PassMode mode, hipStream_t s) {
       // Small blocks (the paper's 4- and 8-token blocks: G*Bq <= 32 or 64 rows per KV group) would
       // leave three of the four row groups of a workgroup computing padding rows; there the
       // wavefronts share one or two 32-row groups and split the output columns instead.
-      if (use_row_pairs(p)) return launch_one<D, kPassDense, kKeyTile, 1, 2, true>(p, s);
+      if (use_row_pairs(p)) return launch_one<D, kPassDense, kKeyTile, 1, 2, 1>(p, s);
       const int tiles = (p.nkeys + kKeyTile - 1) / kKeyTile;
       const bool groups2 = p.nsplit > 1 && tiles >= 8 * p.nsplit;
       const int nrows = p.G * p.Bq;
@@ -890,14 +921,19 @@ hipError_t launch_d(const PassParams& p, PassMode mode, hipStream_t s) {
         if (groups2) return launch_one<D, kPassDense, kKeyTile, 2, 2>(p, s);
         return launch_one<D, kPassDense, kKeyTile, 2, 1>(p, s);
       }
-      if (groups2) return launch_one<D, kPassDense, kKeyTile, 1, 2>(p, s);
+      if (groups2) {
+        // long streams (>= 48 tiles per workgroup): tiles fetched two ahead; measured 4-6 % faster at 64 tiles
+        // per workgroup (128K prefix), neutral at 32, and 1 us slower at 16 (32K prefix: longer start-up)
+        if (tiles >= 48 * p.nsplit) return launch_one<D, kPassDense, kKeyTile, 1, 2, 2>(p, s);
+        return launch_one<D, kPassDense, kKeyTile, 1, 2>(p, s);
+      }
       return launch_one<D, kPassDense, kKeyTile, 1, 1>(p, s);
     }
     case kPassInternal: {
       // Few rows (an LLM-sized block): the pass is one wavefront's run-once instruction stream.
       // Spread each 32-row group over WSMAX wavefronts (columns split) and, for a block of at
       // most 32 keys, use the 32-key tile: both shorten that stream.
-      if (use_row_pairs(p)) return launch_one<D, kPassInternal, kKeyTile, 1, 2, true>(p, s);
+      if (use_row_pairs(p)) return launch_one<D, kPassInternal, kKeyTile, 1, 2, 1>(p, s);
       const long long wgs = (long long)p.B * p.Hkv * ((p.G * p.Bq + kRowsPerWgBf16 - 1) / kRowsPerWgBf16);
       if (wgs < 128) {
         if (p.nkeys <= 32) return launch_one<D, kPassInternal, 32, WSMAX, 1>(p, s);
