@@ -304,3 +304,16 @@ def test_bf16_many_rows_wide_workgroups(B, Hq, Hkv, d, P, Bq, n_splits):
     a wavefront owns two 32-row groups (external pass, with and without splits, and the internal pass
     with its merge epilogue, whose key range here is the many-tile block itself)."""
     _compare_block(_wl("bf16", B, Hq, Hkv, d, P, Bq, S=2, R=2), seed=23, n_splits=n_splits)
+
+
+@pytest.mark.parametrize("d,P,n_splits", [
+    (128, 64 * 96, 2),          # exactly 48 tiles per workgroup, 24 per wavefront group
+    (128, 64 * 101 + 5, 2),     # ragged last tile; 51 tiles per split: the two groups get 26 and 25
+    (128, 64 * 97, 2),          # splits of 49 and 48 tiles
+    (64, 64 * 150 + 1, 3),      # head_dim 64, three splits of 50-51 tiles
+    (128, 64 * 49, 1),          # one split (no groups): the one-ahead loop, final partial written by the kernel
+])
+def test_bf16_long_streams_two_tiles_ahead(d, P, n_splits):
+    """Splits of >= 48 tiles run the variant that fetches tiles two ahead with alternating register sets,
+    including odd tile counts (the wavefront groups then differ by one tile) and a ragged last tile."""
+    _compare_block(_wl("bf16", 1, 8, 2, d, P, 32, S=2, R=2, scale_in=1.0 / np.sqrt(d)), seed=31, n_splits=n_splits)
