@@ -15,7 +15,8 @@
 //   sparse refresh pass, own one accumulator set each); WS = 2/4: wavefronts share 32 rows and
 //   split the output columns (few rows per KV group); KT = 32: internal pass over <= 32 keys;
 //   VAR = 1: row pair (the two groups own different rows, 256 per workgroup, one shared tile
-//   stream: compute-bound passes with many rows); VAR = 2: tiles fetched two ahead (long streams).
+//   stream: compute-bound passes with many rows); VAR = 2: tiles fetched two ahead (long streams);
+//   VAR = 3: both.
 //   MODE: dense external, internal + merge epilogue, sparse refresh, sparse reuse, per-head
 //   refresh, paged external, fused refresh step (PassMode in fb_kernels.h).
 // Per 64-key tile
@@ -35,6 +36,9 @@
 
 namespace fb {
 namespace {
+
+struct SteadyYes { static constexpr bool value = true; };
+struct SteadyNo { static constexpr bool value = false; };
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -304,7 +308,7 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
   // LDS stages (group 0 loads K, group 1 loads V), each wavefront computes a tile only if its
   // head routes it to its set, and every wavefront keeps ONE set: two wavefronts per SIMD
   // instead of the one that two sets in a single wavefront allow.
-  constexpr bool RP = (VAR == 1);
+  constexpr bool RP = (VAR & 1) != 0;
   constexpr bool kSetSplit = (MODE == kPassSparseRefresh && NG == 2);
   // RP ("row pair", compute-bound passes with many rows): the two wavefront groups own DIFFERENT rows (256 per
   // workgroup) and share one tile stream and its LDS stages, so a staged tile serves twice the rows.
@@ -580,30 +584,48 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
       }
     };
 
-    // Dense split pass with two wavefront groups: tiles are fetched TWO ahead (two register sets that alternate),
-    // so each group keeps two 32 KB tiles in flight instead of one; with one, the bytes in flight per CU are just
-    // what the HBM latency-bandwidth product asks for, with no slack.
-    static_assert(VAR != 2 || (MODE == kPassDense && NG == 2 && WS == 1), "deep-prefetch variant");
-    constexpr bool kDeep = (VAR == 2);
+    // Long streams: tiles are fetched TWO ahead (two register sets that alternate).  Dense split pass with two
+    // wavefront groups: each group then keeps two 32 KB tiles in flight instead of one; with one, the bytes in
+    // flight per CU are just what the HBM latency-bandwidth product asks for, with no slack.  Sparse refresh
+    // pass: its two groups share ONE tile stream (each loads half of every tile), so one-ahead leaves a single
+    // tile in flight per CU, half of that product.
+    constexpr bool kDeep = (VAR & 2) != 0;
+    static_assert(!kDeep || (NG == 2 && WS == 1 && (MODE == kPassDense || MODE == kPassSparseRefresh || (RP && MODE == kPassInternal))),
+                  "deep-prefetch variant");
     if constexpr (kDeep) {
       if (ntiles > 0) {
         const int maxmine = common + ((ntiles % TG) != 0 ? 1 : 0);      // workgroup-uniform trip count
         auto k0_of = [&](int i) -> int { return tile_entry(i) * KT; };
         TileRegs regs_b;
-        if (mine > 1) tile_load<D, KT, false>(regs_b, K, V, k0_of(1), nkeys, tid, grp);
-        if (mine > 0) tile_store<D, KT, false>(regs, smem, tid, grp);
+        if (mine > 1) tile_load<D, KT, kShare>(regs_b, K, V, k0_of(1), nkeys, tid, grp);
+        if (mine > 0) tile_store<D, KT, kShare>(regs, smem, tid, grp);
         __syncthreads();
 #pragma unroll
         for (int ks = 0; ks < C::NKS; ++ks) asm volatile("" ::"v"(qreg[ks]));
-        auto step = [&](int i, TileRegs& r_load, TileRegs& r_store) __attribute__((always_inline)) {
-          if (i + 2 < mine) tile_load<D, KT, false>(r_load, K, V, k0_of(i + 2), nkeys, tid, grp);
-          if (i < mine) compute(smem + (i & 1) * C::STAGE, k0_of(i), 0xffffffffu);
-          if (i + 1 < mine) tile_store<D, KT, false>(r_store, smem + ((i + 1) & 1) * C::STAGE, tid, grp);
+        // mask_cur / mask_next hold the selection masks of tiles i and i+1 (all ones in the dense pass).
+        // The steady-state steps are unconditional: a load under a condition would make the number of loads in
+        // flight path-dependent, and the wait in front of the LDS store would then have to be for all of them,
+        // the just-issued tile included.
+        auto step = [&](int i, TileRegs& r_load, TileRegs& r_store, auto steady) __attribute__((always_inline)) {
+          constexpr bool kSteady = decltype(steady)::value;
+          if (kSteady || i + 2 < mine) {
+            k0_nn = entry_k0(tile_entry(i + 2), mask_nn);
+            tile_load<D, KT, kShare>(r_load, K, V, k0_nn, nkeys, tid, grp);
+          }
+          if (kSteady || i < mine) compute(smem + (i & 1) * C::STAGE, k0_of(i), mask_cur);
+          if (kSteady || i + 1 < mine) tile_store<D, KT, kShare>(r_store, smem + ((i + 1) & 1) * C::STAGE, tid, grp);
           __syncthreads();
+          mask_cur = mask_next;
+          mask_next = mask_nn;
         };
-        for (int i = 0; i < maxmine; i += 2) {
-          step(i, regs, regs_b);
-          if (i + 1 < maxmine) step(i + 1, regs_b, regs);
+        int i = 0;
+        for (; kShare && i + 3 < common; i += 2) {          // every group has tiles i .. i+3 (shared stream only: in the dense pass the unguarded steps cost 97 spilled registers)
+          step(i, regs, regs_b, SteadyYes{});
+          step(i + 1, regs_b, regs, SteadyYes{});
+        }
+        for (; i < maxmine; i += 2) {
+          step(i, regs, regs_b, SteadyNo{});
+          if (i + 1 < maxmine) step(i + 1, regs_b, regs, SteadyNo{});
         }
       }
     } else
@@ -864,7 +886,7 @@ __global__ __launch_bounds__(256) void block_mass_bf16_kernel(const MassParams p
 template <int D, int MODE, int KT, int WS, int NG, int VAR = 0>
 hipError_t launch_one(const PassParams& p, hipStream_t s) {
   static bool attr_set = false;   // raising the dynamic-LDS limit is idempotent; the flag only saves calls
-  constexpr bool RP = (VAR == 1);
+  constexpr bool RP = (VAR & 1) != 0;
   auto kern = attn_bf16_kernel<D, MODE, KT, WS, NG, VAR>;
   constexpr int lds = Cfg<D, KT>::LDS * ((MODE == kPassSparseRefresh || RP) ? 1 : NG);
   if (!attr_set) {
@@ -909,6 +931,7 @@ hipError_t launch_d(const PassParams& p, PassMode mode, hipStream_t s) {
       // Small blocks (the paper's 4- and 8-token blocks: G*Bq <= 32 or 64 rows per KV group) would
       // leave three of the four row groups of a workgroup computing padding rows; there the
       // wavefronts share one or two 32-row groups and split the output columns instead.
+      // (row pair + two tiles ahead, VAR = 3, measured: 0.6 % faster with 9 spilled registers; not used)
       if (use_row_pairs(p)) return launch_one<D, kPassDense, kKeyTile, 1, 2, 1>(p, s);
       const int tiles = (p.nkeys + kKeyTile - 1) / kKeyTile;
       const bool groups2 = p.nsplit > 1 && tiles >= 8 * p.nsplit;
@@ -941,9 +964,13 @@ hipError_t launch_d(const PassParams& p, PassMode mode, hipStream_t s) {
       }
       return launch_one<D, kPassInternal, kKeyTile, 1, 1>(p, s);
     }
-    case kPassSparseRefresh:
-      // 8 wavefronts, the two groups specialised by accumulator set (see the kernel)
+    case kPassSparseRefresh: {
+      // 8 wavefronts, the two groups specialised by accumulator set (see the kernel); tiles two ahead unless
+      // the workgroups' streams are short
+      const int tiles = (p.nkeys + kKeyTile - 1) / kKeyTile;
+      if (tiles >= 8 * p.nsplit) return launch_one<D, kPassSparseRefresh, kKeyTile, 1, 2, 2>(p, s);
       return launch_one<D, kPassSparseRefresh, kKeyTile, 1, 2>(p, s);
+    }
     case kPassDenseHeads: {
       const int tiles = (p.nkeys + kKeyTile - 1) / kKeyTile;
       // 8-wavefront workgroups also without splits: workgroups of unflagged heads leave at once, and the
