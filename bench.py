@@ -19,6 +19,7 @@ from __future__ import annotations
 import argparse
 import ctypes
 import json
+import math
 import os
 import sys
 import time
@@ -403,6 +404,94 @@ def paged_extra(torch, fb, wl):
     return info
 
 
+def gamma_calibration(torch, fb, wl, gamma=0.85):
+    """Head-wise selective reuse (Section 4.2, the video rule) end to end on synthetic drift, all on the HIP path.
+    The 12 heads of the video shape drift at different rates (per-step query perturbation sigma_h from 0.02 to
+    1.5).  Calibration block: the external partial is recomputed at every step and fb_head_similarity gives each
+    head's cosine similarity of A_out between consecutive steps (the quantity of Figure 1); heads whose mean
+    similarity exceeds gamma become reuse heads.  Evaluation block (fresh inputs): step 0 refreshes every head, the
+    later steps refresh only the other heads through fb_external_partial_heads; reported are the mean L1 distance
+    of the merged output to full recomputation per head class and the external-pass time per step."""
+    w = wl.CONFIGS["video"]
+    dt = torch.bfloat16
+    H, Bq, D = w.n_q_heads, w.block_len, w.head_dim
+    sig = torch.logspace(math.log10(0.02), math.log10(1.5), H, device="cuda").view(1, H, 1, 1)
+    shape = fb.make_shape(w.batch, H, w.n_kv_heads, D, Bq, w.prefix_len, w.dtype)
+    ws = torch.empty(fb.fb_workspace_bytes(shape), device="cuda", dtype=torch.uint8)
+    rows = (w.batch, H, Bq)
+    mk = lambda: (torch.empty(rows + (D,), device="cuda"), torch.empty(rows, device="cuda"), torch.empty(rows, device="cuda"))
+
+    def block(seed):
+        g = torch.Generator(device="cuda").manual_seed(seed)
+        ks = (w.batch, w.n_kv_heads, w.prefix_len, D)
+        K = (torch.randn(ks, device="cuda", generator=g) * w.input_scale).to(dt)
+        V = (torch.randn(ks, device="cuda", generator=g) * w.input_scale).to(dt)
+        q = torch.randn(rows + (D,), device="cuda", generator=g) * w.input_scale
+        kb = torch.randn((w.batch, w.n_kv_heads, Bq, D), device="cuda", generator=g) * w.input_scale
+        vb = torch.randn((w.batch, w.n_kv_heads, Bq, D), device="cuda", generator=g) * w.input_scale
+        steps = []
+        for _ in range(w.steps):
+            steps.append((q.to(dt).contiguous(), kb.to(dt).contiguous(), vb.to(dt).contiguous()))
+            q = steps[-1][0].float() + sig * torch.randn(q.shape, device="cuda", generator=g)
+            kb = steps[-1][1].float() + w.step_sigma * torch.randn(kb.shape, device="cuda", generator=g)
+            vb = steps[-1][2].float() + w.step_sigma * torch.randn(vb.shape, device="cuda", generator=g)
+        return K, V, steps
+
+    # calibration: similarity of consecutive fresh partials
+    K, V, steps = block(501)
+    prev, cur = mk(), mk()
+    sim = torch.empty((w.batch, H), device="cuda")
+    sims = []
+    for t, (q, kb, vb) in enumerate(steps):
+        fb.fb_external_partial(shape, q, K, V, *cur, ws)
+        if t > 0:
+            fb.fb_head_similarity(shape, prev[0], cur[0], sim)
+            sims.append(sim.clone())
+        prev, cur = cur, prev
+    mean_sim = torch.stack(sims).mean(dim=0)[0]
+    reuse = (mean_sim > gamma)
+    n_refresh = int((~reuse).sum())
+    mask = (~reuse).to(torch.uint8).view(w.batch, H).contiguous()
+    wsh = torch.empty(max(fb.fb_workspace_bytes(shape, 0, 0, max(fb.fb_external_heads_splits(shape, n_refresh), 1)),
+                          fb.fb_workspace_bytes(shape)), device="cuda", dtype=torch.uint8)
+
+    # evaluation on fresh inputs
+    K, V, steps = block(502)
+    part, full, stale = mk(), mk(), mk()
+    out_sel, out_full, out_stale = (torch.empty_like(steps[0][0]) for _ in range(3))
+    err, err_stale = [], []
+    for t, (q, kb, vb) in enumerate(steps):
+        fb.fb_external_partial(shape, q, K, V, *full, ws)
+        fb.fb_internal_merge(shape, q, kb, vb, *full, out_full)
+        if t == 0:
+            fb.fb_external_partial(shape, q, K, V, *part, wsh)
+            fb.fb_external_partial(shape, q, K, V, *stale, wsh)      # never refreshed again: every head reused
+        elif n_refresh > 0:
+            fb.fb_external_partial_heads(shape, q, K, V, mask, *part, wsh, n_refresh)
+        fb.fb_internal_merge(shape, q, kb, vb, *part, out_sel)
+        fb.fb_internal_merge(shape, q, kb, vb, *stale, out_stale)
+        if t > 0:
+            err.append((out_sel.float() - out_full.float()).abs().mean(dim=(0, 2, 3)))
+            err_stale.append((out_stale.float() - out_full.float()).abs().mean(dim=(0, 2, 3)))
+    err = torch.stack(err).mean(dim=0)
+    err_stale = torch.stack(err_stale).mean(dim=0)
+    q = steps[1][0]
+    t_full = _ev_median_us(torch, lambda: fb.fb_external_partial(shape, q, K, V, *full, ws), 9, 3)
+    t_sel = (_ev_median_us(torch, lambda: fb.fb_external_partial_heads(shape, q, K, V, mask, *part, wsh, n_refresh), 9, 3)
+             if n_refresh > 0 else 0.0)
+    ref_scale = float(out_full.float().abs().mean())
+    return {"workload": describe(w), "gamma": gamma,
+            "per_step_query_sigma_by_head": [round(float(x), 3) for x in sig.view(-1)],
+            "mean_similarity_by_head": [round(float(x), 4) for x in mean_sim],
+            "reuse_heads": [int(i) for i in torch.nonzero(reuse).view(-1)],
+            "refreshed_heads_per_reuse_step": n_refresh,
+            "mean_abs_output": round(ref_scale, 5),
+            "l1_to_full_recompute_reuse_heads": round(float(err[reuse].mean()) if reuse.any() else 0.0, 6),
+            "l1_to_full_recompute_refreshed_heads": round(float(err[~reuse].mean()) if (~reuse).any() else 0.0, 6),
+            "l1_of_those_heads_if_they_were_reused_too": round(float(err_stale[~reuse].mean()) if (~reuse).any() else 0.0, 6),
+            "external_us_all_heads": round(t_full, 1), "external_us_selected_heads": round(t_sel, 1)}
+
+
 def sparse_accuracy(torch, fb, wl, prefix_len=32768):
     """Synthetic analogue of the paper's Table 3: mean L1 distance to full attention on reuse steps
     of sparse attention alone vs. sparse attention + the cached residual, per attention density.
@@ -479,6 +568,8 @@ def main():
                     help="only run N whole blocks of the workload, eagerly (for rocprofv3), print nothing else")
     ap.add_argument("--sparse-accuracy", action="store_true",
                     help="only print the sparse-vs-full L1 table (synthetic analogue of the paper's Table 3)")
+    ap.add_argument("--gamma-calibration", action="store_true",
+                    help="only print the head-wise selective-reuse report (similarity calibration on synthetic drift)")
     ap.add_argument("--profile-sparse", type=int, default=0, metavar="N",
                     help="only run N sparse refresh + reuse call pairs of the sparse_64k workload (for rocprofv3)")
     ap.add_argument("--profile-paged", type=int, default=0, metavar="N",
@@ -517,6 +608,9 @@ def main():
         return
     if args.sparse_accuracy:
         print(json.dumps(sparse_accuracy(torch, fb, wl)))
+        return
+    if args.gamma_calibration:
+        print(json.dumps(gamma_calibration(torch, fb, wl)))
         return
     if args.profile_sparse > 0:
         ws_ = wl.CONFIGS["sparse_64k"]

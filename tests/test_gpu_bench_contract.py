@@ -29,3 +29,19 @@ def test_bench_prints_one_json_line_with_the_contract_fields():
     assert rf["bound"] == "hbm" and rf["unit"] == "GB/s" and rf["peak"] == 8000.0
     assert abs(rf["frac"] - rf["achieved"] / rf["peak"]) < 1e-3
     assert 0.05 < rf["frac"] < 1.0 and 1.0 < d["value"] < 1000.0
+
+
+def test_gamma_calibration_report():
+    """Head-wise selective reuse on synthetic drift: similarity falls with the drift rate, the threshold splits
+    the heads, refreshed heads match full recomputation, reused heads stay far closer to it than the refreshed
+    heads would if they were reused too, and refreshing a subset of heads is faster than refreshing all."""
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gamma-calibration"],
+                       capture_output=True, text=True, timeout=300, cwd=ROOT)
+    assert r.returncode == 0, r.stderr[-2000:]
+    d = json.loads([ln for ln in r.stdout.splitlines() if ln.strip()][-1])
+    sim = d["mean_similarity_by_head"]
+    assert all(a >= b - 1e-3 for a, b in zip(sim, sim[1:])) and sim[0] > 0.99 and sim[-1] < 0.85
+    assert 0 < d["refreshed_heads_per_reuse_step"] < len(sim)
+    assert d["l1_to_full_recompute_refreshed_heads"] < 1e-3
+    assert d["l1_to_full_recompute_reuse_heads"] < 0.2 * d["l1_of_those_heads_if_they_were_reused_too"]
+    assert d["external_us_selected_heads"] < 0.6 * d["external_us_all_heads"]
