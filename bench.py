@@ -492,6 +492,99 @@ def gamma_calibration(torch, fb, wl, gamma=0.85):
             "external_us_all_heads": round(t_full, 1), "external_us_selected_heads": round(t_sel, 1)}
 
 
+def tau_policy(torch, fb, wl, n_blocks=24):
+    """The dLLM refresh rule (Section 4.2: refresh the cached external partial iff the number of tokens updated
+    in the step is at least tau) on a synthetic unmasking schedule, all on the HIP path, at the llm_32k shape.
+    Per step a random number M_t in 0..4 of the block's 32 tokens is unmasked: their Q / K / V rows are redrawn,
+    the other rows drift slightly (sigma 0.01).  For each tau the block runs with "refresh iff t == 0 or
+    M_t >= tau"; reported are the fraction of refresh steps, the mean L1 distance of the step output to full
+    recomputation, and the measured attention time per step (refresh steps through fb_refresh_step)."""
+    w = wl.CONFIGS["llm_32k"]
+    dt = torch.bfloat16
+    d0 = DeviceBlock(w, 2, seed=99)
+    shape, ws = d0.shape, d0.ws
+    g = torch.Generator(device="cuda").manual_seed(4242)
+    gcpu = torch.Generator().manual_seed(4242)
+    qs = (w.batch, w.n_q_heads, w.block_len, w.head_dim)
+    ks = (w.batch, w.n_kv_heads, w.block_len, w.head_dim)
+    rows = (w.batch, w.n_q_heads, w.block_len)
+    mk = lambda: (torch.empty(rows + (w.head_dim,), device="cuda"), torch.empty(rows, device="cuda"), torch.empty(rows, device="cuda"))
+    full, part = mk(), mk()
+    out_f, out_p = torch.empty(qs, device="cuda", dtype=dt), torch.empty(qs, device="cuda", dtype=dt)
+    taus = [1, 2, 3, 5]           # 5 > max M_t: refresh at t = 0 only
+    stats = {tau: {"refresh": 0, "steps": 0, "l1": 0.0} for tau in taus}
+    blocks = []
+    for blk in range(n_blocks):
+        K, V = d0.K[blk % 2], d0.V[blk % 2]
+        q = torch.randn(qs, device="cuda", generator=g) * w.input_scale
+        kb = torch.randn(ks, device="cuda", generator=g) * w.input_scale
+        vb = torch.randn(ks, device="cuda", generator=g) * w.input_scale
+        sched, counts = [], []       # counts[t] = tokens updated on the way into step t
+        for t in range(w.steps):
+            if t == 0:
+                counts.append(w.block_len)
+            else:
+                m_t = int(torch.randint(0, 5, (1,), generator=gcpu))
+                counts.append(m_t)
+                q = sched[-1][0].float() + 0.01 * w.input_scale * torch.randn(qs, device="cuda", generator=g)
+                kb = sched[-1][1].float() + 0.01 * w.input_scale * torch.randn(ks, device="cuda", generator=g)
+                vb = sched[-1][2].float() + 0.01 * w.input_scale * torch.randn(ks, device="cuda", generator=g)
+                if m_t > 0:
+                    upd = torch.randperm(w.block_len, generator=gcpu)[:m_t].to("cuda")
+                    q[:, :, upd] = torch.randn((w.batch, w.n_q_heads, m_t, w.head_dim), device="cuda", generator=g) * w.input_scale
+                    kb[:, :, upd] = torch.randn((w.batch, w.n_kv_heads, m_t, w.head_dim), device="cuda", generator=g) * w.input_scale
+                    vb[:, :, upd] = torch.randn((w.batch, w.n_kv_heads, m_t, w.head_dim), device="cuda", generator=g) * w.input_scale
+            sched.append((q.to(dt).contiguous(), kb.to(dt).contiguous(), vb.to(dt).contiguous()))
+        blocks.append((K, V, sched, counts))
+        fulls = []
+        for t, (qt, kt, vt) in enumerate(sched):
+            fb.fb_external_partial(shape, qt, K, V, *full, ws)
+            fb.fb_internal_merge(shape, qt, kt, vt, *full, out_f)
+            fulls.append(out_f.float().clone())
+        for tau in taus:
+            for t, (qt, kt, vt) in enumerate(sched):
+                if t == 0 or counts[t] >= tau:
+                    fb.fb_refresh_step(shape, qt, K, V, kt, vt, *part, out_p, None, ws)
+                    stats[tau]["refresh"] += 1
+                else:
+                    fb.fb_internal_merge(shape, qt, kt, vt, *part, out_p, None)
+                stats[tau]["steps"] += 1
+                stats[tau]["l1"] += float((out_p.float() - fulls[t]).abs().mean())
+    ref = float(sum(float(f.abs().mean()) for f in fulls) / len(fulls))
+
+    def timed(tau):
+        """All blocks' steps under the rule, launched back to back, timed as a whole (as the headline is)."""
+        def run():
+            for K, V, sched, counts in blocks:
+                for t, (qt, kt, vt) in enumerate(sched):
+                    if t == 0 or counts[t] >= tau:
+                        fb.fb_refresh_step(shape, qt, K, V, kt, vt, *part, out_p, None, ws)
+                    else:
+                        fb.fb_internal_merge(shape, qt, kt, vt, *part, out_p, None)
+        run()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(3):
+            run()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / (3 * n_blocks * w.steps)
+
+    table = []
+    for tau in taus + [0]:          # 0: every step refreshes (full recomputation)
+        us = timed(tau)
+        if tau == 0:
+            table.append({"tau": "every step refreshes", "refresh_fraction": 1.0, "l1_to_full_recompute": 0.0,
+                          "attention_us_per_step": round(us, 2)})
+            continue
+        st = stats[tau]
+        table.append({"tau": tau if tau <= 4 else "never (t = 0 only)", "refresh_fraction": round(st["refresh"] / st["steps"], 3),
+                      "l1_to_full_recompute": round(st["l1"] / st["steps"], 7), "attention_us_per_step": round(us, 2)})
+    return {"workload": describe(w), "updated_tokens_per_step": "uniform 0..4 of 32 rows redrawn, the rest drift with sigma 0.01",
+            "mean_abs_output": round(ref, 5), "by_tau": table}
+
+
 def sparse_accuracy(torch, fb, wl, prefix_len=32768):
     """Synthetic analogue of the paper's Table 3: mean L1 distance to full attention on reuse steps
     of sparse attention alone vs. sparse attention + the cached residual, per attention density.
@@ -568,6 +661,8 @@ def main():
                     help="only run N whole blocks of the workload, eagerly (for rocprofv3), print nothing else")
     ap.add_argument("--sparse-accuracy", action="store_true",
                     help="only print the sparse-vs-full L1 table (synthetic analogue of the paper's Table 3)")
+    ap.add_argument("--tau-policy", action="store_true",
+                    help="only print the updated-token-count refresh rule report (synthetic unmasking schedule)")
     ap.add_argument("--gamma-calibration", action="store_true",
                     help="only print the head-wise selective-reuse report (similarity calibration on synthetic drift)")
     ap.add_argument("--profile-sparse", type=int, default=0, metavar="N",
@@ -611,6 +706,9 @@ def main():
         return
     if args.gamma_calibration:
         print(json.dumps(gamma_calibration(torch, fb, wl)))
+        return
+    if args.tau_policy:
+        print(json.dumps(tau_policy(torch, fb, wl)))
         return
     if args.profile_sparse > 0:
         ws_ = wl.CONFIGS["sparse_64k"]

@@ -45,3 +45,20 @@ def test_gamma_calibration_report():
     assert d["l1_to_full_recompute_refreshed_heads"] < 1e-3
     assert d["l1_to_full_recompute_reuse_heads"] < 0.2 * d["l1_of_those_heads_if_they_were_reused_too"]
     assert d["external_us_selected_heads"] < 0.6 * d["external_us_all_heads"]
+
+
+def test_tau_policy_report():
+    """The updated-token-count rule on a synthetic unmasking schedule: a larger threshold refreshes less often,
+    costs less attention time per step and drifts further from full recomputation."""
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--tau-policy"],
+                       capture_output=True, text=True, timeout=300, cwd=ROOT)
+    assert r.returncode == 0, r.stderr[-2000:]
+    d = json.loads([ln for ln in r.stdout.splitlines() if ln.strip()][-1])
+    rows = d["by_tau"]
+    assert [x["tau"] for x in rows[:3]] == [1, 2, 3] and rows[-1]["refresh_fraction"] == 1.0
+    fr = [x["refresh_fraction"] for x in rows[:4]]
+    us = [x["attention_us_per_step"] for x in rows[:4]]
+    l1 = [x["l1_to_full_recompute"] for x in rows[:4]]
+    assert fr == sorted(fr, reverse=True) and abs(fr[3] - 0.125) < 1e-9
+    assert us == sorted(us, reverse=True) and us[0] < rows[-1]["attention_us_per_step"]
+    assert l1 == sorted(l1) and l1[3] < 0.05 * d["mean_abs_output"]
