@@ -312,7 +312,7 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
   constexpr bool kSetSplit = (MODE == kPassSparseRefresh && NG == 2);
   // RP ("row pair", compute-bound passes with many rows): the two wavefront groups own DIFFERENT rows (256 per
   // workgroup) and share one tile stream and its LDS stages, so a staged tile serves twice the rows.
-  static_assert(!RP || (NG == 2 && WS == 1 && (MODE == kPassDense || MODE == kPassInternal)), "row-pair mode");
+  static_assert(!RP || (NG == 2 && WS == 1 && (MODE == kPassDense || MODE == kPassInternal || MODE == kPassRefreshFused)), "row-pair mode");
   constexpr bool kShare = kSetSplit || RP;        // one tile stream, loaded cooperatively by both groups
   constexpr int TG = kShare ? 1 : NG;             // wavefront groups that own separate tile streams
   static_assert(NG == 1 || MODE == kPassDense || MODE == kPassDenseHeads || MODE == kPassDensePaged || MODE == kPassRefreshFused ||
@@ -980,6 +980,7 @@ hipError_t launch_d(const PassParams& p, PassMode mode, hipStream_t s) {
     }
     case kPassRefreshFused: {
       const int tiles = (p.nkeys + kKeyTile - 1) / kKeyTile;
+      if (p.nsplit == 1 && use_row_pairs(p)) return launch_one<D, kPassRefreshFused, kKeyTile, 1, 2, 1>(p, s);   // many rows, unsplit
       if (p.nsplit > 1 && tiles >= 8 * p.nsplit) return launch_one<D, kPassRefreshFused, kKeyTile, 1, 2>(p, s);
       return launch_one<D, kPassRefreshFused, kKeyTile, 1, 1>(p, s);   // unsplit (many row tiles): as the dense pass
     }

@@ -277,6 +277,10 @@ def _compare_refresh_step(w, seed):
     ("bf16", 1, 32, 8, 128, 4096 + 33, 64),
     ("bf16", 1, 32, 8, 128, 4096, 65),          # block of two key tiles, the second ragged
     ("bf16", 1, 8, 8, 128, 8192, 1),
+    # many rows per KV head, unsplit: the streaming kernel runs 256-row workgroups (two groups, shared tile stream)
+    ("bf16", 1, 8, 8, 128, 333, 4100),
+    ("bf16", 2, 8, 4, 64, 200, 1300),
+    ("bf16", 1, 16, 16, 128, 130, 2049),
 ])
 def test_fused_refresh_step(dtype, B, Hq, Hkv, d, P, Bq):
     _compare_refresh_step(_wl(dtype, B, Hq, Hkv, d, P, Bq), seed=51)
