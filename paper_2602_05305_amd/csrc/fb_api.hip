@@ -96,6 +96,21 @@ int auto_splits(const fb_shape* s, int active_heads = 0) {
 
 // Split counts of the sparse passes (bf16): one workgroup per CU in both modes - 8 wavefronts in
 // the reuse pass, 4 wavefronts with two accumulator sets in the refresh pass.
+// Splits of the plain dense external pass.  KV groups above 128 rows run 256-row, 8-wavefront workgroups, one per
+// CU: as many splits as keep the workgroup count within the 256 CUs (one round), each with at least 8 tiles.
+int dense_splits(const fb_shape* s) {
+  const int G = s->n_q_heads / s->n_kv_heads;
+  const long long nrows = (long long)G * s->block_len;
+  if (s->dtype != FB_BF16 || !fb::dense_row_pairs((int)std::min<long long>(nrows, 1 << 30), s->head_dim)) return auto_splits(s);
+  const int tiles = (s->prefix_len + fb::kKeyTile - 1) / fb::kKeyTile;
+  const long long groups = (long long)s->batch * s->n_kv_heads * ((nrows + 2 * fb::kRowsPerWgBf16 - 1) / (2 * fb::kRowsPerWgBf16));
+  long long ns = 256 / groups;
+  if (ns > tiles / 8) ns = tiles / 8;
+  if (ns > FB_MAX_SPLITS) ns = FB_MAX_SPLITS;
+  if (ns < 1) ns = 1;
+  return (int)ns;
+}
+
 int sparse_splits(const fb_shape* s, bool refresh) {
   (void)refresh;
   if (s->dtype != FB_BF16) return auto_splits(s);
@@ -204,7 +219,7 @@ fb_status fb_check_shape(const fb_shape* shape) { return check_shape(shape); }
 
 int32_t fb_external_splits(const fb_shape* shape) {
   if (check_shape(shape) != FB_OK) return 0;
-  return auto_splits(shape);
+  return dense_splits(shape);
 }
 
 int32_t fb_paged_splits(const fb_shape* shape) {
@@ -215,7 +230,7 @@ int32_t fb_paged_splits(const fb_shape* shape) {
 size_t fb_workspace_bytes(const fb_shape* shape, int32_t key_block, int32_t topk, int32_t n_splits) {
   if (check_shape(shape) != FB_OK) return 0;
   if (n_splits < 0 || n_splits > FB_MAX_SPLITS) return 0;
-  const int ns = n_splits > 0 ? n_splits : auto_splits(shape);
+  const int ns = n_splits > 0 ? n_splits : std::max(auto_splits(shape), dense_splits(shape));
   size_t t = ws_layout(shape, ns, 2, 0, 1).total;   // + one block-internal partial for fb_refresh_step
   if (key_block != 0) {
     int nblk = 0;
@@ -254,7 +269,9 @@ fb_status external_partial_impl(const fb_shape* shape, const void* q, const void
       !aligned16(m_part) || !aligned16(lse_part) || !aligned16(workspace))
     return FB_ERR_ALIGN;
   if (n_active_heads < 0) return FB_ERR_SHAPE;
-  const int ns = n_splits > 0 ? n_splits : (paged ? paged_splits(shape) : auto_splits(shape, n_active_heads));
+  const int ns = n_splits > 0 ? n_splits
+                             : (paged ? paged_splits(shape)
+                                      : use_head_mask ? auto_splits(shape, n_active_heads) : dense_splits(shape));
   const WsLayout w = ws_layout(shape, ns, 1, 0);
   if (!workspace || workspace_bytes < w.total) return FB_ERR_WORKSPACE;
 
@@ -392,7 +409,13 @@ fb_status fb_refresh_step_prof(const fb_shape* shape, const void* q, const void*
       !aligned16(v_block) || !aligned16(o_part) || !aligned16(m_part) || !aligned16(lse_part) ||
       !aligned16(out) || !aligned16(lse_out) || !aligned16(workspace))
     return FB_ERR_ALIGN;
-  const int ns = auto_splits(shape);
+  // Small block and many splits (the LLM shapes): the prefix splits already fill every CU, so the
+  // block's own keys are not streamed by the attention kernel at all (plain dense pass, with its split
+  // count); one fold kernel (4 rows per workgroup) folds the splits, computes the rows' block-internal
+  // attention and merges.
+  const bool small_block = shape->block_len <= fb::kMaxInlineBlock && shape->block_len % fb::kFoldRows == 0 &&
+                           dense_splits(shape) >= 8;
+  const int ns = small_block ? dense_splits(shape) : auto_splits(shape);
   const WsLayout w = ws_layout(shape, ns, 2, 0, 1);
   if (!workspace || workspace_bytes < w.total) return FB_ERR_WORKSPACE;
 
@@ -408,10 +431,6 @@ fb_status fb_refresh_step_prof(const fb_shape* shape, const void* q, const void*
   }
   p.ws_o = (float*)(ws + w.o[0]); p.ws_m = (float*)(ws + w.m[0]); p.ws_l = (float*)(ws + w.l[0]);
   p.ws_o2 = (float*)(ws + w.o[1]); p.ws_m2 = (float*)(ws + w.m[1]); p.ws_l2 = (float*)(ws + w.l[1]);
-  // Small block and many splits (the LLM shapes): the prefix splits already fill every CU, so the
-  // block's own keys are not streamed by the attention kernel at all; one fold kernel (4 rows per
-  // workgroup) folds the splits, computes the rows' block-internal attention and merges.
-  const bool small_block = shape->block_len <= fb::kMaxInlineBlock && shape->block_len % fb::kFoldRows == 0 && ns >= 8;
   hipError_t e = hipSuccess;
   if (ev_begin && (e = hipEventRecord((hipEvent_t)ev_begin, stream)) != hipSuccess) return hip_fail(e);
   e = launch_attn(shape, p, small_block ? fb::kPassDense : fb::kPassRefreshFused, stream);

@@ -909,8 +909,9 @@ hipError_t launch_one(const PassParams& p, hipStream_t s) {
   return hipGetLastError();
 }
 
-// Row-pair workgroups pay off when the pass is compute-bound: many rows per KV head and enough 256-row
-// workgroups to give every CU one.
+// Internal and fused passes (never or rarely split): row-pair workgroups when the pass is compute-bound, i.e. many
+// rows per KV head and enough 256-row workgroups to give every CU one.  (The dense external pass uses them for
+// every KV group above 128 rows, see dense_row_pairs.)
 inline bool use_row_pairs(const PassParams& p) {
 #if defined(FB_NO_RP)
   return false;
@@ -932,7 +933,7 @@ hipError_t launch_d(const PassParams& p, PassMode mode, hipStream_t s) {
       // leave three of the four row groups of a workgroup computing padding rows; there the
       // wavefronts share one or two 32-row groups and split the output columns instead.
       // (row pair + two tiles ahead, VAR = 3, measured: 0.6 % faster with 9 spilled registers; not used)
-      if (use_row_pairs(p)) return launch_one<D, kPassDense, kKeyTile, 1, 2, 1>(p, s);
+      if (dense_row_pairs(p.G * p.Bq, D)) return launch_one<D, kPassDense, kKeyTile, 1, 2, 1>(p, s);
       const int tiles = (p.nkeys + kKeyTile - 1) / kKeyTile;
       const bool groups2 = p.nsplit > 1 && tiles >= 8 * p.nsplit;
       const int nrows = p.G * p.Bq;
