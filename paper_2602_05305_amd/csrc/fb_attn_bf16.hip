@@ -913,13 +913,9 @@ hipError_t launch_one(const PassParams& p, hipStream_t s) {
 // rows per KV head and enough 256-row workgroups to give every CU one.  (The dense external pass uses them for
 // every KV group above 128 rows, see dense_row_pairs.)
 inline bool use_row_pairs(const PassParams& p) {
-#if defined(FB_NO_RP)
-  return false;
-#else
   const int nrows = p.G * p.Bq;
   const long long wgs = (long long)p.B * p.Hkv * ((nrows + 2 * kRowsPerWgBf16 - 1) / (2 * kRowsPerWgBf16)) * p.nsplit;
   return nrows >= 1024 && wgs >= 128;
-#endif
 }
 
 template <int D>
