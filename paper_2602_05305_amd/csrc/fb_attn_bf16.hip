@@ -87,7 +87,12 @@ __device__ __forceinline__ void load_k(u32x4 (&r)[4], const __bf16* __restrict__
     const int row = c / (D / 8), col = c % (D / 8);
     const int key = min(k0 + row, last);
     if (C::KCHUNKS % 256 == 0 || c < C::KCHUNKS) r[i] = gload128(K + (size_t)key * D + col * 8);
+    else r[i] = u32x4{0u, 0u, 0u, 0u};
   }
+  // every element defined on every path: a partly written array is kept in scratch memory by the compiler, and
+  // the store to it waits for the tile load right after issuing it
+#pragma unroll
+  for (int i = C::NK; i < 4; ++i) r[i] = u32x4{0u, 0u, 0u, 0u};
 }
 
 template <int D, int KT>
@@ -101,6 +106,9 @@ __device__ __forceinline__ void load_v(u32x4 (&r)[4], const __bf16* __restrict__
       const int key = min(k0 + 4 * kq + j, last);
       r[j] = gload128(V + (size_t)key * D + doct * 8);
     }
+  } else {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) r[j] = u32x4{0u, 0u, 0u, 0u};
   }
 }
 
@@ -321,7 +329,7 @@ __global__ __launch_bounds__(256 * NG, (NG > 1 || (MODE == kPassInternal && WS >
 
   // wavefront-uniform by construction; in the list-driven passes (paged, sparse reuse), telling the compiler
   // so turns the per-tile table lookups into scalar loads, which do not queue behind the tile's vector loads
-  const int grp = (NG > 1) ? ((MODE == kPassDensePaged || MODE == kPassSparseReuse)
+  const int grp = (NG > 1) ? ((MODE == kPassDensePaged || MODE == kPassSparseReuse || MODE == kPassSparseRefresh || (VAR & 1) != 0)
                                   ? __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 8))
                                   : (int)(threadIdx.x >> 8))
                            : 0;

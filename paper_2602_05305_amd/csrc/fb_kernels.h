@@ -151,8 +151,8 @@ hipError_t launch_head_similarity(const float* o_a, const float* o_b, float* sim
 constexpr int kRowsPerWgBf16 = 128;  // 4 waves x 32 rows
 constexpr int kRowsPerWgF32 = 4;     // 4 waves x 1 row
 // bf16 dense external pass: KV groups of more than 128 rows run row-pair workgroups (8 wavefronts, 256 rows, one
-// shared tile stream), so every K/V tile is staged once per 256 rows.  At head_dim 64 the tiles are half the bytes
-// and a single shared stream per CU is latency-bound (measured 34 -> 44 us at 256 rows, 32K keys), so there only
+// shared tile stream), so every K/V tile is staged once per 256 rows.  At head_dim 64 that measures the same as
+// 128-row workgroups (32.6 vs 33.8 us at 256 rows, 32K keys) but leaves twice the splits to fold, so there only
 // from 1024 rows on, where the pass is compute-bound.  Shared by the split heuristic and the launcher.
 inline bool dense_row_pairs(int nrows, int head_dim) {
   return nrows >= 1024 || (head_dim >= 128 && nrows > kRowsPerWgBf16);
