@@ -282,7 +282,8 @@ def video_extra(torch, fb, wl):
     t_int = _ev_median_us(torch, lambda: fb.fb_internal_merge(d.shape, q, kb, vb, d.o, d.m, d.lse, d.out, None), 7, 2)
     hm = torch.zeros((w.batch, w.n_q_heads), device="cuda", dtype=torch.uint8)
     hm[:, ::2] = 1                       # head-wise selective refresh: every other head recomputed
-    ws_h = torch.empty(fb.fb_workspace_bytes(d.shape, 0, 0, 8), device="cuda", dtype=torch.uint8)
+    ns_h = max(fb.fb_external_heads_splits(d.shape, w.n_q_heads // 2), fb.fb_external_heads_splits(d.shape, 1), 1)
+    ws_h = torch.empty(fb.fb_workspace_bytes(d.shape, 0, 0, ns_h), device="cuda", dtype=torch.uint8)
     t_half = _ev_median_us(torch, lambda: fb.fb_external_partial_heads(d.shape, q, d.K[0], d.V[0], hm, d.o, d.m, d.lse,
                                                                        ws_h, w.n_q_heads // 2), 7, 2)
     hm1 = torch.zeros((w.batch, w.n_q_heads), device="cuda", dtype=torch.uint8)
