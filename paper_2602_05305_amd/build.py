@@ -16,9 +16,11 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libflashblock.so")
-SOURCES = ["fb_api.hip", "fb_attn_f32.hip", "fb_attn_bf16.hip", "fb_aux.hip"]
+SOURCES = ["fb_api.hip", "fb_attn_f32.hip", "fb_attn_bf16.hip", "fb_stream_bf16.hip", "fb_aux.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
+         # the direct-to-LDS loads set M0 from inline assembly and say so in the clobber list
+         "-Wno-inline-asm",
          # keep the compiler from forming packed fp32 VALU ops
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

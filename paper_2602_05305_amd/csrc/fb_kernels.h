@@ -134,6 +134,9 @@ struct MaskParams {
 // Host-side launchers; each returns the hipError_t of its launch(es).
 hipError_t launch_attn_f32(const PassParams& p, int D, PassMode mode, hipStream_t s);
 hipError_t launch_attn_bf16(const PassParams& p, int D, PassMode mode, hipStream_t s);
+// Streaming form of the bf16 pass (direct-to-LDS tile ring); covers a subset of (shape, mode) combinations.
+bool stream_bf16_covers(const PassParams& p, PassMode mode);
+hipError_t launch_stream_bf16(const PassParams& p, int D, PassMode mode, hipStream_t s);
 hipError_t launch_combine(const CombineParams& p, hipStream_t s);
 // Fold + block-internal attention + merge in one kernel; needs blk_q/k/v, Bq <= kMaxInlineBlock, Bq % kFoldRows == 0.
 hipError_t launch_refresh_fold(const CombineParams& p, hipStream_t s);
