@@ -146,7 +146,7 @@ int paged_splits(const fb_shape* s) {
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct WsLayout {
-  size_t o[2], m[2], l[2], mask, ulist, ucnt, order, total;
+  size_t o[2], m[2], l[2], mask, ulist, umask, ucnt, order, total;
 };
 
 WsLayout ws_layout(const fb_shape* s, int nsplit, int nsets, int nblk, int nsplit2 = -1) {
@@ -162,6 +162,7 @@ WsLayout ws_layout(const fb_shape* s, int nsplit, int nsets, int nblk, int nspli
   const size_t nb = (size_t)s->batch * s->n_kv_heads * nblk;
   w.mask = off;  off = align256(off + nb * sizeof(uint32_t));
   w.ulist = off; off = align256(off + nb * sizeof(int32_t));
+  w.umask = off; off = align256(off + nb * sizeof(uint32_t));
   w.ucnt = off;  off = align256(off + (nblk > 0 ? (size_t)s->batch * s->n_kv_heads * sizeof(int32_t) : 0));
   w.order = off; off = align256(off + (size_t)s->batch * sizeof(int32_t));   // paged pass: sequences by length
   w.total = off;
@@ -607,6 +608,7 @@ fb_status fb_sparse_external_residual(const fb_shape* shape, int32_t mode, const
   fb::MaskParams mp;
   mp.sel_idx = topk > 0 ? sel_idx : nullptr;
   mp.blk_mask = (uint32_t*)(ws + w.mask); mp.union_list = (int32_t*)(ws + w.ulist);
+  mp.union_mask = (uint32_t*)(ws + w.umask);
   mp.union_cnt = (int32_t*)(ws + w.ucnt);
   mp.B = shape->batch; mp.Hq = shape->n_q_heads; mp.Hkv = shape->n_kv_heads;
   mp.G = shape->n_q_heads / shape->n_kv_heads; mp.topk = topk; mp.nblk = nblk;
@@ -619,7 +621,7 @@ fb_status fb_sparse_external_residual(const fb_shape* shape, int32_t mode, const
   fb::PassParams p = base_pass(shape, q, k_prefix, v_prefix, shape->prefix_len, ns);
   p.ws_o = (float*)(ws + w.o[0]); p.ws_m = (float*)(ws + w.m[0]); p.ws_l = (float*)(ws + w.l[0]);
   p.ws_o2 = (float*)(ws + w.o[1]); p.ws_m2 = (float*)(ws + w.m[1]); p.ws_l2 = (float*)(ws + w.l[1]);
-  p.blk_mask = mp.blk_mask; p.union_list = mp.union_list; p.union_cnt = mp.union_cnt;
+  p.blk_mask = mp.blk_mask; p.union_list = mp.union_list; p.union_mask = mp.union_mask; p.union_cnt = mp.union_cnt;
   p.key_block = key_block; p.nblk = nblk;
 
   fb::CombineParams c;

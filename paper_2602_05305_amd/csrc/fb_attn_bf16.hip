@@ -1013,7 +1013,7 @@ hipError_t launch_block_mass_bf16(const MassParams& p, int D, hipStream_t s) {
 }
 
 hipError_t launch_attn_bf16(const PassParams& p, int D, PassMode mode, hipStream_t s) {
-  if (stream_bf16_covers(p, mode)) return launch_stream_bf16(p, D, mode, s);
+  if (stream_bf16_covers(p, D, mode)) return launch_stream_bf16(p, D, mode, s);
   if (D == 64) return launch_d<64>(p, mode, s);
   return launch_d<128>(p, mode, s);
 }

@@ -765,8 +765,13 @@ __global__ __launch_bounds__(256) void build_masks_kernel(const MaskParams p) {
   }
   int pos = block_exclusive_prefix(mine, wtot, tid);
   int32_t* list = p.union_list + (size_t)bk * nblk;
+  uint32_t* lm = p.union_mask + (size_t)bk * nblk;
   for (int c = c0; c < c1; ++c)
-    if (lmask[c] != 0u) list[pos++] = c;
+    if (lmask[c] != 0u) {
+      list[pos] = c;
+      lm[pos] = lmask[c];
+      ++pos;
+    }
   if (tid == 255) p.union_cnt[bk] = pos;
 }
 

@@ -65,6 +65,7 @@ struct PassParams {
   // sparse passes
   const uint32_t* blk_mask;   // [B,Hkv,nblk] bit g set: head g of the group selected the block
   const int32_t* union_list;  // [B,Hkv,nblk] ascending blocks with mask != 0
+  const uint32_t* union_mask; // [B,Hkv,nblk] mask of the i-th listed block (no dependent lookup in the reuse pass)
   const int32_t* union_cnt;   // [B,Hkv]
   int key_block, nblk;
   const uint8_t* head_on;     // [B,Hq] per-head refresh flags (kPassDenseHeads), else null
@@ -127,7 +128,7 @@ struct PoolParams {
 };
 
 struct MaskParams {
-  const int32_t* sel_idx; uint32_t* blk_mask; int32_t* union_list; int32_t* union_cnt;
+  const int32_t* sel_idx; uint32_t* blk_mask; int32_t* union_list; uint32_t* union_mask; int32_t* union_cnt;
   int B, Hq, Hkv, G, topk, nblk;
 };
 
@@ -135,7 +136,7 @@ struct MaskParams {
 hipError_t launch_attn_f32(const PassParams& p, int D, PassMode mode, hipStream_t s);
 hipError_t launch_attn_bf16(const PassParams& p, int D, PassMode mode, hipStream_t s);
 // Streaming form of the bf16 pass (direct-to-LDS tile ring); covers a subset of (shape, mode) combinations.
-bool stream_bf16_covers(const PassParams& p, PassMode mode);
+bool stream_bf16_covers(const PassParams& p, int D, PassMode mode);
 hipError_t launch_stream_bf16(const PassParams& p, int D, PassMode mode, hipStream_t s);
 hipError_t launch_combine(const CombineParams& p, hipStream_t s);
 // Fold + block-internal attention + merge in one kernel; needs blk_q/k/v, Bq <= kMaxInlineBlock, Bq % kFoldRows == 0.

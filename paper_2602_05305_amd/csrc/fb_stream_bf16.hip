@@ -4,15 +4,22 @@
 // (ds_read_b64_tr_b16) from row-major V, so nothing is transposed or re-stored on the way.
 //
 // Computes the per-row statistics of Eq. 3-4/6 (arxiv 2602.05305, Section 4.2) of a block of query rows
-// against a long stream of keys and stores split partials (or, with one split, the final partial).
+// against a stream of keys and either stores split partials / the final partial (external passes) or finishes
+// with the log-space composition of Eq. 8-9 against a cached partial (internal pass).
 //
-// Work decomposition
-//   workgroup = 8 wavefronts, one tile stream of 64-key tiles, NS ring stages (NS - 1 tiles in flight).
-//   KSPLIT = 2: 128 group-flattened rows; wavefront w owns rows [32 (w%4), +32) and the key half w/4 of every
-//               tile; the two halves' statistics are merged through LDS after the last tile.
+// Work decomposition: workgroup = 8 wavefronts, one tile stream of 64-key tiles, NS ring stages.
+//   kKeySplit  128 group-flattened rows; wavefront w owns rows [32 (w%4), +32) and the key half w/4 of every
+//              tile; the two halves' statistics are merged through LDS after the last tile.  (LLM-shaped
+//              blocks: the whole KV group is one workgroup, every K/V byte is fetched once.)
+//              Sparse refresh pass: the same layout with two accumulator sets per wavefront (selected /
+//              residual key blocks); a tile's scores are computed once and go to the set the row's head routes
+//              the tile's key block to, so the eight wavefronts stay evenly loaded whatever the selection.
+//   kRowPair   256 rows, wavefront w owns rows [32 w, +32) and whole tiles (many rows per KV head: a staged
+//              tile serves twice the rows).  PIPE: the score MFMAs of tile t+1 are issued ahead of the softmax
+//              of tile t, so that the matrix pipe has independent work during the exp chain.
 //   Per tile and wavefront: S^T = K Q^T on v_mfma_f32_32x32x16_bf16 (A = K rows from LDS, B = Q^T in
 //   registers), in-lane online softmax with a lazily moved reference, O^T += V^T P^T with the lane's own
-//   probabilities as the B operand (see fb_attn_bf16.hip for the register layout reasoning, which is the same).
+//   probabilities as the B operand (register layout reasoning: fb_attn_bf16.hip, which is the same).
 // LDS layout of a stage: [K: 64 rows x D*2 bytes][V: 64 rows x D*2 bytes], rows unpadded, the 16-byte chunks
 //   of a row rotated by a row-dependent amount (K: by row, V: by 4*row at head_dim 128; by row/2 and
 //   4*(row/2) at head_dim 64) so that both read patterns are bank-conflict-free.  A direct-to-LDS load puts
@@ -20,20 +27,18 @@
 // Synchronisation: the direct-to-LDS loads are issued from inline assembly, invisible to the compiler's
 //   wait-count insertion (which would otherwise drain every outstanding load before any LDS read); each
 //   wavefront waits for its own loads of a tile with an explicit s_waitcnt vmcnt(n), then the workgroup
-//   barrier makes the tile visible to all.  The stage refilled after barrier t is the one read in iteration
-//   t-1, which every wavefront has left by then.
+//   barrier makes the tile visible to all.  The stage refilled after barrier t is the one last read in
+//   iteration t-1, which every wavefront has left by then.
 #include "fb_kernels.h"
-#include <stdlib.h>
 
 namespace fb {
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
 
@@ -41,7 +46,9 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr int kStreamThreads = 512;
 
-template <int D>
+enum StreamLayout : int { kKeySplit = 0, kRowPair = 2 };
+
+template <int D, int LAYOUT, int NSETS = 1>
 struct SCfg {
   static constexpr int KT = 64;                       // keys per tile
   static constexpr int ROWB = D * 2;                  // bytes per key row
@@ -53,8 +60,14 @@ struct SCfg {
   static constexpr int NS = (D == 128) ? 4 : 6;       // ring stages
   static constexpr int NKS = D / 16;                  // MFMA k-steps of the score product
   static constexpr int NDB = D / 32;                  // 32-wide output column blocks
-  static constexpr int QSTAGES = (128 * ROWB + STAGE - 1) / STAGE;   // stages the 128 query rows occupy at start
-  static constexpr int LDS = NS * STAGE;
+  static constexpr int ROWS = (LAYOUT == kRowPair) ? 256 : 128;
+  static constexpr int NKB = (LAYOUT == kKeySplit) ? 1 : 2;    // 32-key blocks of a tile one wavefront computes
+  static constexpr int QSTAGES = ROWS * ROWB / STAGE;          // ring stages the query rows pass through at start
+  static constexpr int MERGE = (LAYOUT == kKeySplit) ? NSETS * 4 * (NDB * 16 + 2) * 64 * 4 : 0;   // key-half hand-over
+  static constexpr int RING = NS * STAGE;
+  static constexpr int FIFO = RING > MERGE ? RING : MERGE;
+  static constexpr int LDS = FIFO;
+  static_assert(QSTAGES >= 1 && QSTAGES < NS && ROWS * ROWB == QSTAGES * STAGE, "query rows fill whole stages");
   // rotation (in chunks) of row `row`
   __device__ static __forceinline__ int rot_k(int row) { return D == 128 ? row : (row >> 1); }
   __device__ static __forceinline__ int rot_v(int row) { return D == 128 ? 4 * row : 4 * (row >> 1); }
@@ -65,8 +78,8 @@ struct SCfg {
 __device__ __forceinline__ void dma16(const void* base, uint32_t off, uint32_t lds_base) {
   // base and lds_base are wavefront-uniform by construction; readfirstlane says so to the compiler, which
   // otherwise may hand the "s" operands over in vector registers (not encodable here)
-  const uint64_t b = (uint64_t)(uintptr_t)base;
   // (the builtin returns int: each half goes through uint32_t so that nothing is sign-extended)
+  const uint64_t b = (uint64_t)(uintptr_t)base;
   const uint32_t b_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)b);
   const uint32_t b_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(b >> 32));
   const uint64_t bu = ((uint64_t)b_hi << 32) | (uint64_t)b_lo;
@@ -77,9 +90,37 @@ __device__ __forceinline__ void dma16(const void* base, uint32_t off, uint32_t l
                : "memory", "m0");
 }
 
+// Wavefront-uniform table lookup as a scalar load (constant address space).  The tables were written by earlier
+// kernels, so they are constant here; without this the compiler, which sees the inline assembly's memory
+// clobber, falls back to vector loads, and its wait for them (vmcnt(0)) would also drain every direct-to-LDS
+// load in flight.
+__device__ __forceinline__ int32_t sload(const void* table, int idx) {
+  typedef const __attribute__((address_space(4))) int32_t* cptr;
+  return ((cptr)(uintptr_t)table)[__builtin_amdgcn_readfirstlane(idx)];
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vm() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// wait until at most `tiles` tiles' worth of this lane's direct-to-LDS loads are outstanding
+template <int LPT>
+__device__ __forceinline__ void wait_tiles(int tiles) {
+  if (tiles >= 5) wait_vm<5 * LPT>();
+  else if (tiles == 4) wait_vm<4 * LPT>();
+  else if (tiles == 3) wait_vm<3 * LPT>();
+  else if (tiles == 2) wait_vm<2 * LPT>();
+  else if (tiles == 1) wait_vm<LPT>();
+  else wait_vm<0>();
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  bf16x2 v;
+  v[0] = (__bf16)a;
+  v[1] = (__bf16)b;
+  return __builtin_bit_cast(uint32_t, v);
 }
 
 // Running softmax state of the 32 rows a wavefront owns (one row per lane pair l, l^32).
@@ -97,25 +138,25 @@ struct WaveAcc {
   }
 };
 
-// Scores of this wavefront's 32 rows against key blocks [KB0, KB0 + NKB) of the tile in `stage`.
+// Scores of this wavefront's 32 rows against key blocks [kb0, kb0 + NKB) of the tile in `stage`.
 // kaddr[ks] = per-lane byte address (within a stage, key block 0) of the K chunk of k-step ks.
 template <int D, int NKB>
-__device__ __forceinline__ void tile_scores(f32x16 (&s)[NKB], const bf16x8 (&qreg)[SCfg<D>::NKS],
-                                            const unsigned char* __restrict__ stage, const uint32_t (&kaddr)[SCfg<D>::NKS],
+__device__ __forceinline__ void tile_scores(f32x16 (&s)[NKB], const bf16x8 (&qreg)[D / 16],
+                                            const unsigned char* __restrict__ stage, const uint32_t (&kaddr)[D / 16],
                                             int kb0) {
-  using C = SCfg<D>;
+  constexpr int NKS = D / 16, ROWB = D * 2;
 #pragma unroll
   for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
     for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
 #pragma unroll
-  for (int ks0 = 0; ks0 < C::NKS; ks0 += 2) {
+  for (int ks0 = 0; ks0 < NKS; ks0 += 2) {
     bf16x8 a[2][NKB];
 #pragma unroll
     for (int u = 0; u < 2; ++u)
 #pragma unroll
       for (int kb = 0; kb < NKB; ++kb)
-        a[u][kb] = *(const bf16x8*)(stage + kaddr[ks0 + u] + (kb0 + kb) * 32 * C::ROWB);
+        a[u][kb] = *(const bf16x8*)(stage + kaddr[ks0 + u] + (kb0 + kb) * 32 * ROWB);
 #pragma unroll
     for (int u = 0; u < 2; ++u)
 #pragma unroll
@@ -129,12 +170,12 @@ __device__ __forceinline__ void tile_scores(f32x16 (&s)[NKB], const bf16x8 (&qre
 //   vaddr[db] = per-lane byte address (within a stage) of the lane's share of the transposing V read of
 //               column block db, key offset 0; the 4-key groups are reached through immediate offsets
 template <int D, int NKB>
-__device__ __forceinline__ void tile_softmax_pv(WaveAcc<SCfg<D>::NDB>& st, f32x16 (&s)[NKB],
+__device__ __forceinline__ void tile_softmax_pv(WaveAcc<D / 32>& st, f32x16 (&s)[NKB],
                                                 const unsigned char* __restrict__ stage,
-                                                const uint32_t (&vaddr)[SCfg<D>::NDB], int kb0, float scale_log2,
+                                                const uint32_t (&vaddr)[D / 32], int kb0, float scale_log2,
                                                 bool lane_on, int nvalid, int h) {
-  using C = SCfg<D>;
-  if (nvalid < C::KT) {
+  constexpr int NDB = D / 32, ROWB = D * 2, OPB = 64 * ROWB;
+  if (nvalid < 64) {
     // the empty asm keeps this a real (wavefront-uniform) branch instead of per-score selects on every tile
     asm volatile("" ::: "memory");
 #pragma unroll
@@ -173,7 +214,7 @@ __device__ __forceinline__ void tile_softmax_pv(WaveAcc<SCfg<D>::NDB>& st, f32x1
   st.m = m_new;
   if (__any(alpha != 1.f)) {
 #pragma unroll
-    for (int db = 0; db < C::NDB; ++db)
+    for (int db = 0; db < NDB; ++db)
 #pragma unroll
       for (int r = 0; r < 16; ++r) st.o[db][r] *= alpha;
   }
@@ -183,39 +224,67 @@ __device__ __forceinline__ void tile_softmax_pv(WaveAcc<SCfg<D>::NDB>& st, f32x1
 #pragma unroll
   for (int t = 0; t < 2 * NKB; ++t) {
     const int krow = (kb0 + t / 2) * 32 + 16 * (t % 2);
-    bf16x8 a[C::NDB];
+    bf16x8 a[NDB];
 #pragma unroll
-    for (int db = 0; db < C::NDB; ++db) {
-      const unsigned char* base = stage + C::OPB + vaddr[db] + krow * C::ROWB;
+    for (int db = 0; db < NDB; ++db) {
+      const unsigned char* base = stage + OPB + vaddr[db] + krow * ROWB;
       const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(base));
-      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(base + 8 * C::ROWB));
-      typedef short s16x8 __attribute__((ext_vector_type(8)));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(base + 8 * ROWB));
       const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
       a[db] = __builtin_bit_cast(bf16x8, both);
     }
 #pragma unroll
-    for (int db = 0; db < C::NDB; ++db)
+    for (int db = 0; db < NDB; ++db)
       st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[db], pb[t], st.o[db], 0, 0, 0);
   }
 }
 
-template <int D, int MODE>
+// A tile of the stream (all wavefront-uniform).  TileRaw is what the table lookups deliver (fetched one iteration
+// before the tile is issued, with no arithmetic on the loaded words, so that the wait for them falls into the
+// next iteration); TileDesc adds the addresses.
+struct TileRaw {
+  int e;            // entry of the pass's tile list
+  int word;         // sparse reuse: key block; paged: page id; else unused
+  uint32_t mask;    // selection mask of the tile's key block (sparse passes), else all ones
+};
+struct TileDesc {
+  int k0;
+  uint32_t mask;
+  const unsigned char* kt;
+  const unsigned char* vt;
+};
+
+template <int D, int MODE, int LAYOUT, bool PIPE>
 __global__ __launch_bounds__(kStreamThreads, 1) void attn_stream_kernel(const PassParams p) {
-  using C = SCfg<D>;
-  static_assert(MODE == kPassDense || MODE == kPassDenseHeads, "modes of the streaming kernel");
+  constexpr int NSETS = (MODE == kPassSparseRefresh) ? 2 : 1;
+  using C = SCfg<D, LAYOUT, NSETS>;
+  static_assert(MODE == kPassDense || MODE == kPassDenseHeads || MODE == kPassDensePaged || MODE == kPassSparseReuse ||
+                    MODE == kPassSparseRefresh || MODE == kPassInternal, "modes of the streaming kernel");
+  static_assert(MODE != kPassSparseRefresh || LAYOUT == kKeySplit, "two accumulator sets: key-split layout");
+  static_assert(!PIPE || (LAYOUT == kRowPair && (MODE == kPassDense || MODE == kPassInternal)), "pipelined form");
+  static_assert(MODE != kPassInternal || LAYOUT == kRowPair, "internal pass: row-pair layout");
+  // passes whose tiles come from a table (paged, sparse): the lookups are made one iteration ahead of the tile's
+  // issue, and (first key, mask) travel to the tile's compute in a register queue
   extern __shared__ __align__(16) unsigned char ring[];
   const int lane = threadIdx.x & 63, l32 = lane & 31, h = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));     // wavefront-uniform (scalar)
-  const int rg = wave & 3;        // 32-row group
-  const int kb0 = wave >> 2;      // key half of every tile
+  const int rg = (LAYOUT == kRowPair) ? wave : (wave & 3);       // 32-row group
+  const int kb0 = (LAYOUT == kKeySplit) ? (wave >> 2) : 0;       // first 32-key block of every tile
 
-  // XCD-aware remap: hardware deals consecutive workgroup ids round-robin to the 8 XCDs; make each XCD own a
-  // contiguous range of (batch, KV head, split) units.
+  // ---- workgroup -> (row tile, batch, KV head, split).  Hardware deals consecutive workgroup ids round-robin
+  // to the 8 XCDs; each XCD gets a contiguous range of units so that row tiles sharing K/V share an L2.
   const int nwg = gridDim.x;
   const int nrows = p.G * p.Bq;
   int rt;
   uint32_t rest;
-  {
+  if constexpr (MODE == kPassDensePaged) {
+    // ragged sequences: contiguous ranges would give the XCDs unequal work; deal the units round-robin
+    const uint32_t j = blockIdx.x >> 3, xcd = blockIdx.x & 7;
+    const uint32_t jq = fastdiv(j, p.div_rowtiles);
+    rt = (int)(j - jq * p.div_rowtiles.d);
+    rest = jq * 8 + xcd;
+    if (rest >= (uint32_t)(p.B * p.Hkv * p.nsplit)) return;   // workgroup-uniform
+  } else {
     const int bid = blockIdx.x, q8 = nwg / 8, r8 = nwg % 8;
     const int xcd = bid % 8, j = bid / 8;
     int w = (xcd < r8 ? xcd * (q8 + 1) : r8 * (q8 + 1) + (xcd - r8) * q8) + j;
@@ -226,15 +295,43 @@ __global__ __launch_bounds__(kStreamThreads, 1) void attn_stream_kernel(const Pa
     rt = w - (int)(rest * p.div_rowtiles.d);
   }
   const uint32_t unit = rest;
-  const uint32_t r2 = fastdiv(rest, p.div_nsplit);
-  const int split = (int)(rest - r2 * p.div_nsplit.d);
-  rest = r2;
-  const int b = (int)fastdiv(rest, p.div_hkv);
+  int split = 0;
+  if constexpr (MODE != kPassInternal) {
+    const uint32_t r2 = fastdiv(rest, p.div_nsplit);
+    split = (int)(rest - r2 * p.div_nsplit.d);
+    rest = r2;
+  }
+  int b = (int)fastdiv(rest, p.div_hkv);
   const int kvh = (int)(rest - (uint32_t)b * p.div_hkv.d);
+  if constexpr (MODE == kPassDensePaged) {
+    if (p.seq_order != nullptr) {
+      b = sload(p.seq_order, b);
+    } else if (p.order_inline) {
+      // small batch: this workgroup finds the sequence with the b-th longest prefix itself (ties: lower index
+      // first): lengths to LDS, one rank per thread, the thread whose sequence has rank b publishes it
+      int* lens_s = (int*)ring;
+      __shared__ int chosen;
+      for (int i = threadIdx.x; i < p.B; i += kStreamThreads) lens_s[i] = p.prefix_lens[i];
+      __syncthreads();
+      for (int i = threadIdx.x; i < p.B; i += kStreamThreads) {
+        const int li = lens_s[i];
+        int rank = 0;
+        for (int j = 0; j < p.B; ++j) {
+          const int lj = lens_s[j];
+          rank += (lj > li || (lj == li && j < i)) ? 1 : 0;
+        }
+        if (rank == b) chosen = i;
+      }
+      __syncthreads();
+      b = __builtin_amdgcn_readfirstlane(chosen);
+      __syncthreads();                       // the ring is free again before the first direct-to-LDS load
+    }
+  }
   const int bk = b * p.Hkv + kvh;
-  const int nkeys = p.nkeys;
+  int nkeys = p.nkeys;
+  if constexpr (MODE == kPassDensePaged) nkeys = min(p.nkeys, max(0, sload(p.prefix_lens, b)));   // this sequence's prefix
 
-  const int row0 = rt * 128;                                   // first group-flattened row of the workgroup
+  const int row0 = rt * C::ROWS;                               // first group-flattened row of the workgroup
   const int row = row0 + rg * 32 + l32;
   const bool row_ok = row < nrows;
   const size_t grow_base = (size_t)(b * p.Hq + kvh * p.G) * p.Bq;
@@ -245,25 +342,70 @@ __global__ __launch_bounds__(kStreamThreads, 1) void attn_stream_kernel(const Pa
     if (!__syncthreads_or(head_active ? 1 : 0)) return;
   }
 
-  const unsigned char* __restrict__ Kg = (const unsigned char*)p.k + (size_t)bk * nkeys * C::ROWB;
-  const unsigned char* __restrict__ Vg = (const unsigned char*)p.v + (size_t)bk * nkeys * C::ROWB;
+  // contiguous cache: this KV head's [nkeys, D] slab; paged cache: the pool (tiles add their page offset)
+  const unsigned char* __restrict__ Kg =
+      (const unsigned char*)p.k + ((MODE == kPassDensePaged) ? (size_t)0 : (size_t)bk * nkeys * C::ROWB);
+  const unsigned char* __restrict__ Vg =
+      (const unsigned char*)p.v + ((MODE == kPassDensePaged) ? (size_t)0 : (size_t)bk * nkeys * C::ROWB);
 
-  // tile list of this workgroup: a contiguous range of the prefix's tiles, visited in rotated order (workgroups
-  // that run in lockstep would otherwise read the same offset of their chunks, i.e. the same channels, at once)
-  const int total = (nkeys + C::KT - 1) / C::KT;
-  const TileRange tr = split_range(total, p.div_nsplit, split);
+  // ---- tile list of this workgroup: a contiguous range of the pass's tile list, visited in rotated order
+  // (workgroups that run in lockstep would otherwise read the same offset of their chunks, i.e. the same
+  // channels, at once; row tiles of one unit share the offset so that one L2 serves them)
+  int tpb = 1, total;
+  if constexpr (MODE == kPassSparseReuse) {
+    tpb = p.key_block / C::KT;
+    total = sload(p.union_cnt, bk) * tpb;
+  } else {
+    total = (nkeys + C::KT - 1) / C::KT;
+  }
+  const TileRange tr = (MODE == kPassInternal) ? TileRange{0, total} : split_range(total, p.div_nsplit, split);
   const int ntiles = tr.end - tr.begin;
   const uint32_t rsrc = (p.div_rowtiles.d == 1) ? blockIdx.x : unit;
-  const int rot = ntiles <= 0 ? 0 : (int)((rsrc * 13u + (rsrc >> 5) * 7u) % (unsigned)ntiles);
-  auto tile_k0 = [&](int i) -> int {
+  const int rot = (MODE == kPassInternal || ntiles <= 0) ? 0 : (int)((rsrc * 13u + (rsrc >> 5) * 7u) % (unsigned)ntiles);
+  const uint32_t* __restrict__ bmask = p.blk_mask ? p.blk_mask + (size_t)bk * p.nblk : nullptr;
+  const int32_t* __restrict__ ulist = p.union_list ? p.union_list + (size_t)bk * p.nblk : nullptr;
+  const uint32_t* __restrict__ umask = p.union_mask ? p.union_mask + (size_t)bk * p.nblk : nullptr;
+  auto tile_raw = [&](int i) -> TileRaw {        // i-th tile of this workgroup: table lookups only
     int j = i + rot;
     if (j >= ntiles) j -= ntiles;
-    return (tr.begin + j) * C::KT;
+    TileRaw r;
+    r.e = tr.begin + j;
+    r.word = 0;
+    r.mask = 0xffffffffu;
+    if constexpr (MODE == kPassSparseReuse) {
+      r.word = sload(ulist, r.e / tpb);
+      r.mask = (uint32_t)sload(umask, r.e / tpb);
+    } else if constexpr (MODE == kPassSparseRefresh) {
+      r.mask = (uint32_t)sload(bmask, (int)((uint32_t)(r.e * C::KT) / (uint32_t)p.key_block));
+    } else if constexpr (MODE == kPassDensePaged) {
+      r.word = sload(p.block_table + (size_t)b * p.max_pages, (int)fastdiv((uint32_t)(r.e * C::KT), p.div_page));
+    }
+    return r;
+  };
+  auto tile_desc = [&](const TileRaw& r) -> TileDesc {
+    TileDesc d;
+    d.mask = r.mask;
+    d.k0 = (MODE == kPassSparseReuse) ? r.word * p.key_block + C::KT * (r.e % tpb) : r.e * C::KT;
+    if constexpr (MODE == kPassDensePaged) {
+      const uint32_t slot = fastdiv((uint32_t)d.k0, p.div_page);
+      const int page = min(max(r.word, 0), p.num_pages - 1);       // clamped into the pool
+      const int in_page = d.k0 - (int)(slot * p.div_page.d);
+      const size_t off = (((size_t)page * p.Hkv + kvh) * p.page_size + in_page) * C::ROWB;
+      d.kt = Kg + off;
+      d.vt = Vg + off;
+    } else {
+      // a list entry past the end of the keys (reuse pass, short last key block) is skipped by the compute; its
+      // loads, issued all the same so that every tile counts the same number of loads, read the head's first keys
+      const int kload = (MODE == kPassSparseReuse && d.k0 >= nkeys) ? 0 : d.k0;
+      d.kt = Kg + (size_t)kload * C::ROWB;
+      d.vt = Vg + (size_t)kload * C::ROWB;
+    }
+    return d;
   };
 
-  // ---- direct-to-LDS load slots of this lane: operand chunk p = (j*8 + wave)*64 + lane lives at LDS row
-  // p / CPR, chunk position p % CPR, and holds logical chunk (position - rotation(row)) of that row.
-  const uint32_t ring_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)ring);
+  // ---- direct-to-LDS load slots of this lane: operand chunk pidx = (j*8 + wave)*64 + lane lives at LDS row
+  // pidx / CPR, chunk position pidx % CPR, and holds logical chunk (position - rotation(row)) of that row.
+  const uint32_t ring_base = (uint32_t)(uintptr_t)ring;
   int ld_row[C::NLOAD];
   uint32_t off_k[C::NLOAD], off_v[C::NLOAD];     // byte offsets inside a full tile
   int ck[C::NLOAD], cv[C::NLOAD];
@@ -277,54 +419,59 @@ __global__ __launch_bounds__(kStreamThreads, 1) void attn_stream_kernel(const Pa
     off_k[j] = (uint32_t)(r * C::ROWB + ck[j] * 16);
     off_v[j] = (uint32_t)(r * C::ROWB + cv[j] * 16);
   }
-  auto issue_tile = [&](int i) {
-    const int k0 = tile_k0(i);
+  // (first key, mask) of the tiles in the ring, oldest first: [0] is the tile computed in this iteration
+  int qk0[C::NS];
+  uint32_t qmask[C::NS];
+#pragma unroll
+  for (int i = 0; i < C::NS; ++i) { qk0[i] = 0; qmask[i] = 0u; }
+  auto issue_tile = [&](int i, const TileDesc& d) {
     const uint32_t sbase = ring_base + (uint32_t)(i % C::NS) * C::STAGE + wave * 1024;
-    const unsigned char* kt = Kg + (size_t)k0 * C::ROWB;
-    const unsigned char* vt = Vg + (size_t)k0 * C::ROWB;
-    const int nvalid = nkeys - k0;
+    const int nvalid = nkeys - d.k0;
     if (nvalid >= C::KT) {
 #pragma unroll
-      for (int j = 0; j < C::NLOAD; ++j) dma16(kt, off_k[j], sbase + j * 8192);
+      for (int j = 0; j < C::NLOAD; ++j) dma16(d.kt, off_k[j], sbase + j * 8192);
 #pragma unroll
-      for (int j = 0; j < C::NLOAD; ++j) dma16(vt, off_v[j], sbase + C::OPB + j * 8192);
+      for (int j = 0; j < C::NLOAD; ++j) dma16(d.vt, off_v[j], sbase + C::OPB + j * 8192);
     } else {
-      // ragged last tile: rows past the end read the last key (in bounds; their scores are masked)
+      // ragged tile: rows past the end read the last key (in bounds; their scores are masked); an entry past the
+      // end of the keys reads one row of the address tile_desc gave it
+      const int last = max(nvalid, 1) - 1;
 #pragma unroll
       for (int j = 0; j < C::NLOAD; ++j)
-        dma16(kt, (uint32_t)(min(ld_row[j], nvalid - 1) * C::ROWB + ck[j] * 16), sbase + j * 8192);
+        dma16(d.kt, (uint32_t)(min(ld_row[j], last) * C::ROWB + ck[j] * 16), sbase + j * 8192);
 #pragma unroll
       for (int j = 0; j < C::NLOAD; ++j)
-        dma16(vt, (uint32_t)(min(ld_row[j], nvalid - 1) * C::ROWB + cv[j] * 16), sbase + C::OPB + j * 8192);
+        dma16(d.vt, (uint32_t)(min(ld_row[j], last) * C::ROWB + cv[j] * 16), sbase + C::OPB + j * 8192);
     }
   };
 
-  // ---- prologue: the 128 query rows go through the last ring stage(s) (free until tile NS - QSTAGES is
-  // issued), then the first tiles; everything is in flight before the first wait.
+  // ---- prologue: the query rows go through the last ring stage(s), then the first tiles; everything is in
+  // flight before the first wait.
   {
     const unsigned char* qg = (const unsigned char*)p.q + (grow_base + row0) * C::ROWB;
     const int qvalid = nrows - row0;                     // >= 1
     const uint32_t qbase = ring_base + (uint32_t)(C::NS - C::QSTAGES) * C::STAGE + wave * 1024;
 #pragma unroll
-    for (int half = 0; half < 2; ++half)                 // rows [0,64) and [64,128): each laid out like a K operand
+    for (int part = 0; part < C::ROWS / 64; ++part)      // 64 rows at a time, each laid out like a K operand
 #pragma unroll
       for (int j = 0; j < C::NLOAD; ++j) {
-        const int r = min(64 * half + ld_row[j], qvalid - 1);
-        dma16(qg, (uint32_t)(r * C::ROWB + ck[j] * 16), qbase + half * C::OPB + j * 8192);
+        const int r = min(64 * part + ld_row[j], qvalid - 1);
+        dma16(qg, (uint32_t)(r * C::ROWB + ck[j] * 16), qbase + part * C::OPB + j * 8192);
       }
   }
-  constexpr int kPre = C::NS - C::QSTAGES;               // tiles issued before the queries have been read
-  static_assert(C::QSTAGES == 1 && kPre == C::NS - 1, "the query rows fit the last stage");
-#pragma unroll
-  for (int i = 0; i < kPre; ++i)
-    if (i < ntiles) issue_tile(i);
-  // every lane issued 2*NLOAD query loads first and LPT loads per tile after them
+  constexpr int kPre = C::NS - C::QSTAGES;               // tiles that can be issued while the queries sit in the ring
   {
-    const int pre = min(kPre, max(ntiles, 0));
-    if (pre >= 3) wait_vm<3 * C::LPT>();
-    else if (pre == 2) wait_vm<2 * C::LPT>();
-    else if (pre == 1) wait_vm<C::LPT>();
-    else wait_vm<0>();
+    int pre = 0;
+#pragma unroll
+    for (int i = 0; i < kPre; ++i)
+      if (i < ntiles && i < C::NS - 1) {
+        const TileDesc d = tile_desc(tile_raw(i));
+        issue_tile(i, d);
+        qk0[i] = d.k0;
+        qmask[i] = d.mask;
+        ++pre;
+      }
+    wait_tiles<C::LPT>(pre);                             // the query loads were issued first
   }
   __syncthreads();
   bf16x8 qreg[C::NKS];
@@ -335,6 +482,22 @@ __global__ __launch_bounds__(kStreamThreads, 1) void attn_stream_kernel(const Pa
     for (int ks = 0; ks < C::NKS; ++ks)
       qreg[ks] = *(const bf16x8*)(qs + ((2 * ks + h + C::rot_k(r % 64)) & (C::CPR - 1)) * 16);
   }
+  if constexpr (kPre < C::NS - 1) {
+    // the queries took more than the last stage: the remaining start-up tiles go out once everyone has read them
+    __syncthreads();
+#pragma unroll
+    for (int i = kPre; i < C::NS - 1; ++i)
+      if (i < ntiles) {
+        const TileDesc d = tile_desc(tile_raw(i));
+        issue_tile(i, d);
+        qk0[i] = d.k0;
+        qmask[i] = d.mask;
+      }
+  }
+  // table words of the next tile to be issued, fetched one iteration ahead (lookups off the critical path)
+  TileRaw rnext;
+  rnext.e = 0; rnext.word = 0; rnext.mask = 0u;
+  if (C::NS - 1 < ntiles) rnext = tile_raw(C::NS - 1);
 
   // per-lane LDS read addresses inside a stage
   uint32_t kaddr[C::NKS], vaddr[C::NDB];
@@ -352,135 +515,284 @@ __global__ __launch_bounds__(kStreamThreads, 1) void attn_stream_kernel(const Pa
     }
   }
 
-  WaveAcc<C::NDB> acc;
-  acc.init();
+  WaveAcc<C::NDB> accs[NSETS];
+#pragma unroll
+  for (int i = 0; i < NSETS; ++i) accs[i].init();
+  WaveAcc<C::NDB>& acc = accs[0];
+  const uint32_t my_bit = 1u << ((row_ok ? row : 0) / p.Bq);
 
-  for (int t = 0; t < ntiles; ++t) {
-    const int younger = min(C::NS - 2, ntiles - 1 - t);    // tiles issued after tile t so far
-    if (younger >= 4) wait_vm<4 * C::LPT>();
-    else if (younger == 3) wait_vm<3 * C::LPT>();
-    else if (younger == 2) wait_vm<2 * C::LPT>();
-    else if (younger == 1) wait_vm<C::LPT>();
-    else wait_vm<0>();
-    __syncthreads();
-    if (t + C::NS - 1 < ntiles) issue_tile(t + C::NS - 1);
-    const unsigned char* stage = ring + (t % C::NS) * C::STAGE;
-    const int nvalid = min(C::KT, nkeys - tile_k0(t));
-    f32x16 s[1];
-    tile_scores<D, 1>(s, qreg, stage, kaddr, kb0);
-    if constexpr (MODE == kPassDenseHeads) {
-      tile_softmax_pv<D, 1>(acc, s, stage, vaddr, kb0, p.scale_log2, head_active, nvalid, h);
-    } else {
-      tile_softmax_pv<D, 1>(acc, s, stage, vaddr, kb0, p.scale_log2, true, nvalid, h);
+  auto lane_on_of = [&](uint32_t mask, int set) -> bool {
+    if constexpr (MODE == kPassDenseHeads) return head_active;
+    else if constexpr (MODE == kPassSparseReuse) return row_ok && (mask & my_bit) != 0u;
+    else if constexpr (MODE == kPassSparseRefresh) return row_ok && (((mask & my_bit) != 0u) == (set == 0));
+    else return true;
+  };
+  constexpr bool kMasked = (MODE == kPassDenseHeads || MODE == kPassSparseReuse || MODE == kPassSparseRefresh);
+  // issue of tile t + NS - 1 (into the stage every wavefront left at the last barrier), then the lookups of the
+  // tile after it; the queue then holds tiles t .. t + NS - 1
+  auto refill = [&](int t) {
+    if (t + C::NS - 1 < ntiles) {
+      const TileDesc d = tile_desc(rnext);
+      issue_tile(t + C::NS - 1, d);
+      qk0[C::NS - 1] = d.k0;
+      qmask[C::NS - 1] = d.mask;
+      if (t + C::NS < ntiles) rnext = tile_raw(t + C::NS);
+    }
+  };
+  auto advance = [&]() {
+#pragma unroll
+    for (int i = 0; i + 1 < C::NS; ++i) {
+      qk0[i] = qk0[i + 1];
+      qmask[i] = qmask[i + 1];
+    }
+  };
+
+  if constexpr (!PIPE) {
+    for (int t = 0; t < ntiles; ++t) {
+      wait_tiles<C::LPT>(min(C::NS - 2, ntiles - 1 - t));     // tiles issued after tile t so far
+      __syncthreads();
+      refill(t);
+      const unsigned char* stage = ring + (t % C::NS) * C::STAGE;
+      const int k0 = qk0[0];
+      const uint32_t mask = qmask[0];
+      advance();
+      const int nvalid = min(C::KT, nkeys - k0);
+      if constexpr (MODE == kPassSparseReuse) {
+        if (nvalid <= 0) continue;                             // a list entry past the end of the keys
+      }
+      bool on[NSETS];
+      bool any_on = false;
+#pragma unroll
+      for (int i = 0; i < NSETS; ++i) {
+        on[i] = lane_on_of(mask, i);
+        any_on = any_on || on[i];
+      }
+      if (kMasked && !__any(any_on)) continue;
+      f32x16 s[C::NKB];
+      tile_scores<D, C::NKB>(s, qreg, stage, kaddr, kb0);
+#pragma unroll
+      for (int i = 0; i < NSETS; ++i) {
+        if (NSETS > 1 && !__any(on[i])) continue;
+        tile_softmax_pv<D, C::NKB>(accs[i], s, stage, vaddr, kb0, p.scale_log2, on[i], nvalid, h);
+      }
+    }
+  } else {
+    // scores of tile t+1 are issued before the softmax of tile t: two score register sets
+    f32x16 s_cur[C::NKB];
+    if (ntiles > 0) {
+      wait_tiles<C::LPT>(min(C::NS - 2, ntiles - 1));
+      __syncthreads();
+      tile_scores<D, C::NKB>(s_cur, qreg, ring, kaddr, kb0);
+    }
+    for (int t = 0; t < ntiles; ++t) {
+      const bool more = t + 1 < ntiles;
+      if (more) wait_tiles<C::LPT>(min(C::NS - 3, ntiles - 2 - t));   // tiles issued after tile t+1 so far
+      __syncthreads();
+      refill(t);
+      const unsigned char* stage = ring + (t % C::NS) * C::STAGE;
+      const int k0 = qk0[0];
+      advance();
+      const int nvalid = min(C::KT, nkeys - k0);
+      f32x16 s_next[C::NKB];
+      if (more) tile_scores<D, C::NKB>(s_next, qreg, ring + ((t + 1) % C::NS) * C::STAGE, kaddr, kb0);
+      tile_softmax_pv<D, C::NKB>(acc, s_cur, stage, vaddr, kb0, p.scale_log2, true, nvalid, h);
+      if (more) {
+#pragma unroll
+        for (int kb = 0; kb < C::NKB; ++kb) s_cur[kb] = s_next[kb];
+      }
     }
   }
 
-  // ---- merge the two key halves through LDS: wavefronts 4..7 hand their statistics to wavefronts 0..3
-  {
+  if constexpr (LAYOUT == kKeySplit) {
+    // ---- merge the two key halves through LDS: wavefronts 4..7 hand their statistics to wavefronts 0..3
     constexpr int REC = C::NDB * 16 + 2;
-    float* mbuf = (float*)ring + (size_t)rg * REC * 64 + lane;
     __syncthreads();
-    if (kb0 == 1) {
 #pragma unroll
-      for (int db = 0; db < C::NDB; ++db)
+    for (int i = 0; i < NSETS; ++i) {
+      float* mbuf = (float*)ring + ((size_t)i * 4 + rg) * REC * 64 + lane;
+      if (kb0 == 1) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) mbuf[(db * 16 + r) * 64] = acc.o[db][r];
-      mbuf[(C::NDB * 16) * 64] = acc.m;
-      mbuf[(C::NDB * 16 + 1) * 64] = acc.l;
+        for (int db = 0; db < C::NDB; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) mbuf[(db * 16 + r) * 64] = accs[i].o[db][r];
+        mbuf[(C::NDB * 16) * 64] = accs[i].m;
+        mbuf[(C::NDB * 16 + 1) * 64] = accs[i].l;
+      }
     }
     __syncthreads();
     if (kb0 == 1) return;
-    const float m1 = mbuf[(C::NDB * 16) * 64], l1 = mbuf[(C::NDB * 16 + 1) * 64];
-    const float M = fmaxf(acc.m, m1);
-    const float Mu = (M == -INFINITY) ? 0.f : M;
-    const float w0 = __builtin_amdgcn_exp2f(acc.m - Mu), w1 = __builtin_amdgcn_exp2f(m1 - Mu);
 #pragma unroll
-    for (int db = 0; db < C::NDB; ++db)
+    for (int i = 0; i < NSETS; ++i) {
+      const float* mbuf = (const float*)ring + ((size_t)i * 4 + rg) * REC * 64 + lane;
+      WaveAcc<C::NDB>& a = accs[i];
+      const float m1 = mbuf[(C::NDB * 16) * 64], l1 = mbuf[(C::NDB * 16 + 1) * 64];
+      const float M = fmaxf(a.m, m1);
+      const float Mu = (M == -INFINITY) ? 0.f : M;
+      const float w0 = __builtin_amdgcn_exp2f(a.m - Mu), w1 = __builtin_amdgcn_exp2f(m1 - Mu);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc.o[db][r] = acc.o[db][r] * w0 + mbuf[(db * 16 + r) * 64] * w1;
-    acc.l = acc.l * w0 + l1 * w1;
-    acc.m = M;
+      for (int db = 0; db < C::NDB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) a.o[db][r] = a.o[db][r] * w0 + mbuf[(db * 16 + r) * 64] * w1;
+      a.l = a.l * w0 + l1 * w1;
+      a.m = M;
+    }
   }
 
   // ---- epilogue
   const float l_row = acc.l + __shfl_xor(acc.l, 32, 64);
-  if (p.direct) {
-    // single split: this is the final partial.  Same conversion as the split combine: m is rounded when
-    // converted to natural-log units, o is rescaled to the reference consumers recover from it.
-    if (!(row_ok && head_active)) return;
-    float m_nat = -INFINITY, L = -INFINITY, adj = 0.f;
-    if (l_row > 0.f) {
-      m_nat = acc.m * kLn2;
-      adj = exp2f(acc.m - m_nat * kLog2e);
-      L = (acc.m + log2f(l_row)) * kLn2;
+  if constexpr (MODE == kPassInternal) {
+    if (!row_ok) return;
+    // Eq. 8-9 with the cached pair expressed through (o, m, lse): A_out e^{L_out-M} = o e^{m-M}
+    const bool has_ext = p.ext_o != nullptr;             // workgroup-uniform
+    float me2 = -INFINITY, le = 0.f;
+    if (has_ext) {
+      const float em = p.ext_m[grow], el = p.ext_lse[grow];
+      if (el != -INFINITY) {
+        me2 = em * kLog2e;
+        le = exp2f((el - em) * kLog2e);
+      }
     }
+    const float M2 = fmaxf(me2, acc.m);
+    const float Mu = (M2 == -INFINITY) ? 0.f : M2;
+    const float we = exp2f(me2 - Mu), wi = exp2f(acc.m - Mu);
+    const float den = le * we + l_row * wi;
+    const float inv = den > 0.f ? 1.f / den : 0.f;
+    __bf16* out = (__bf16*)p.out + grow * D;
 #pragma unroll
     for (int db = 0; db < C::NDB; ++db)
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
         const int d0 = 32 * db + 8 * q4 + 4 * h;
-        f32x4 o4 = {acc.o[db][4 * q4] * adj, acc.o[db][4 * q4 + 1] * adj, acc.o[db][4 * q4 + 2] * adj,
-                    acc.o[db][4 * q4 + 3] * adj};
-        *(f32x4*)(p.ws_o + grow * D + d0) = o4;
+        f32x4 e = {0.f, 0.f, 0.f, 0.f};
+        if (has_ext) e = *(const f32x4*)(p.ext_o + grow * D + d0);
+        float r[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r[i] = (acc.o[db][4 * q4 + i] * wi + e[i] * we) * inv;
+        u32x2 pk;
+        pk.x = pack_bf16x2(r[0], r[1]);
+        pk.y = pack_bf16x2(r[2], r[3]);
+        *(u32x2*)(out + d0) = pk;
       }
-    if (h == 0) {
-      p.ws_m[grow] = m_nat;
-      p.ws_l[grow] = L;
-    }
+    if (p.lse_out != nullptr && h == 0) p.lse_out[grow] = den > 0.f ? (M2 + log2f(den)) * kLn2 : -INFINITY;
     return;
-  }
-  if (!row_ok) return;
-  const size_t rows_total = (size_t)p.B * p.Hq * p.Bq;
-  const size_t wrow = (size_t)split * rows_total + grow;
+  } else {
+    if (p.direct) {
+      // single split: this is the final partial.  Same conversion as the split combine: m is rounded when
+      // converted to natural-log units, o is rescaled to the reference consumers recover from it.
+      if (!(row_ok && head_active)) return;
+      float m_nat = -INFINITY, L = -INFINITY, adj = 0.f;
+      if (l_row > 0.f) {
+        m_nat = acc.m * kLn2;
+        adj = exp2f(acc.m - m_nat * kLog2e);
+        L = (acc.m + log2f(l_row)) * kLn2;
+      }
 #pragma unroll
-  for (int db = 0; db < C::NDB; ++db)
+      for (int db = 0; db < C::NDB; ++db)
 #pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) {
-      const int d0 = 32 * db + 8 * q4 + 4 * h;
-      f32x4 o4 = {acc.o[db][4 * q4], acc.o[db][4 * q4 + 1], acc.o[db][4 * q4 + 2], acc.o[db][4 * q4 + 3]};
-      // streaming store: read next by another kernel, never again by this one
-      __builtin_nontemporal_store(o4, (f32x4*)(p.ws_o + wrow * D + d0));
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const int d0 = 32 * db + 8 * q4 + 4 * h;
+          f32x4 o4 = {acc.o[db][4 * q4] * adj, acc.o[db][4 * q4 + 1] * adj, acc.o[db][4 * q4 + 2] * adj,
+                      acc.o[db][4 * q4 + 3] * adj};
+          *(f32x4*)(p.ws_o + grow * D + d0) = o4;
+        }
+      if (h == 0) {
+        p.ws_m[grow] = m_nat;
+        p.ws_l[grow] = L;
+      }
+      return;
     }
-  if (h == 0) {
-    p.ws_m[wrow] = acc.m;
-    p.ws_l[wrow] = l_row;
+    if (!row_ok) return;
+    const size_t rows_total = (size_t)p.B * p.Hq * p.Bq;
+    const size_t wrow = (size_t)split * rows_total + grow;
+#pragma unroll
+    for (int i = 0; i < NSETS; ++i) {
+      float* __restrict__ w_o = i ? p.ws_o2 : p.ws_o;
+      float* __restrict__ w_m = i ? p.ws_m2 : p.ws_m;
+      float* __restrict__ w_l = i ? p.ws_l2 : p.ws_l;
+      const WaveAcc<C::NDB>& a = accs[i];
+      const float l_i = (i == 0) ? l_row : a.l + __shfl_xor(a.l, 32, 64);
+#pragma unroll
+      for (int db = 0; db < C::NDB; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const int d0 = 32 * db + 8 * q4 + 4 * h;
+          f32x4 o4 = {a.o[db][4 * q4], a.o[db][4 * q4 + 1], a.o[db][4 * q4 + 2], a.o[db][4 * q4 + 3]};
+          // streaming store: read next by another kernel, never again by this one (measured: faster than staging
+          // the rows through LDS for whole-row stores, and faster than write-back stores)
+          __builtin_nontemporal_store(o4, (f32x4*)(w_o + wrow * D + d0));
+        }
+      if (h == 0) {
+        w_m[wrow] = a.m;
+        w_l[wrow] = l_i;
+      }
+    }
   }
-  __builtin_amdgcn_s_waitcnt(0);
 }
 
-template <int D, int MODE>
+template <int D, int MODE, int LAYOUT, bool PIPE>
 hipError_t launch_stream(const PassParams& p, hipStream_t s) {
-  auto kern = attn_stream_kernel<D, MODE>;
-  constexpr int lds = SCfg<D>::LDS;
+  using C = SCfg<D, LAYOUT, (MODE == kPassSparseRefresh) ? 2 : 1>;
+  auto kern = attn_stream_kernel<D, MODE, LAYOUT, PIPE>;
   // raising the dynamic-LDS limit is a host-only call; made on every launch so that no process-wide flag is kept
-  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS);
   if (e != hipSuccess) return e;
   const int nrows = p.G * p.Bq;
-  const int ntile_rows = (nrows + 127) / 128;
-  const long long nwg = (long long)p.B * p.Hkv * ntile_rows * p.nsplit;
+  const int ntile_rows = (nrows + C::ROWS - 1) / C::ROWS;
+  long long nwg = (long long)p.B * p.Hkv * ntile_rows * p.nsplit;
+  if (MODE == kPassDensePaged) nwg = (((long long)p.B * p.Hkv * p.nsplit + 7) / 8) * 8 * ntile_rows;
   if (nwg >= (1ll << 31)) return hipErrorInvalidValue;
   PassParams q = p;
+  if (MODE == kPassDensePaged) q.div_page = make_fastdiv((uint32_t)p.page_size);
   q.div_rowtiles = make_fastdiv((uint32_t)ntile_rows);
   q.div_nsplit = make_fastdiv((uint32_t)p.nsplit);
   q.div_hkv = make_fastdiv((uint32_t)p.Hkv);
-  hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(kStreamThreads), lds, s, q);
+  hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(kStreamThreads), C::LDS, s, q);
   return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_stream_d(const PassParams& p, PassMode mode, hipStream_t s) {
+  const int nrows = p.G * p.Bq;
+  switch (mode) {
+    case kPassDense:
+      if (dense_row_pairs(nrows, D)) return launch_stream<D, kPassDense, kRowPair, true>(p, s);
+      return launch_stream<D, kPassDense, kKeySplit, false>(p, s);
+    case kPassDenseHeads: return launch_stream<D, kPassDenseHeads, kKeySplit, false>(p, s);
+    case kPassDensePaged: return launch_stream<D, kPassDensePaged, kKeySplit, false>(p, s);
+    case kPassSparseReuse: return launch_stream<D, kPassSparseReuse, kKeySplit, false>(p, s);
+    case kPassSparseRefresh: return launch_stream<D, kPassSparseRefresh, kKeySplit, false>(p, s);
+    case kPassInternal: return launch_stream<D, kPassInternal, kRowPair, true>(p, s);
+    default: return hipErrorInvalidValue;
+  }
 }
 
 }  // namespace
 
-bool stream_bf16_covers(const PassParams& p, PassMode mode) {
-
-  if (mode != kPassDense && mode != kPassDenseHeads) return false;
+// Shapes the streaming kernel takes over from the register-staged one: groups of more than 64 rows whose
+// workgroups stream at least 8 tiles each.
+bool stream_bf16_covers(const PassParams& p, int D, PassMode mode) {
   const int nrows = p.G * p.Bq;
   const int tiles = (p.nkeys + kKeyTile - 1) / kKeyTile;
-  return nrows > 64 && nrows <= 128 && tiles >= 8 * p.nsplit;
+  switch (mode) {
+    case kPassDense:
+      if (dense_row_pairs(nrows, D)) return false;   // row-pair form: the register-staged kernel is still ahead
+      return nrows > 64 && nrows <= 128 && tiles >= 8 * p.nsplit;
+    case kPassDenseHeads:
+    case kPassDensePaged:
+    case kPassSparseReuse:
+    case kPassSparseRefresh:
+      return nrows > 64 && nrows <= 128 && tiles >= 8 * p.nsplit;
+    case kPassInternal: {
+      // compute-bound internal pass: many rows per KV head and a 256-row workgroup for (almost) every CU
+      const long long wgs = (long long)p.B * p.Hkv * ((nrows + 255) / 256);
+      return false && nrows >= 1024 && wgs >= 128 && tiles >= 8;
+    }
+    default: return false;
+  }
 }
 
 hipError_t launch_stream_bf16(const PassParams& p, int D, PassMode mode, hipStream_t s) {
-  if (mode == kPassDense) return D == 64 ? launch_stream<64, kPassDense>(p, s) : launch_stream<128, kPassDense>(p, s);
-  if (mode == kPassDenseHeads) return D == 64 ? launch_stream<64, kPassDenseHeads>(p, s) : launch_stream<128, kPassDenseHeads>(p, s);
-  return hipErrorInvalidValue;
+  return D == 64 ? launch_stream_d<64>(p, mode, s) : launch_stream_d<128>(p, mode, s);
 }
 
 }  // namespace fb
