@@ -3,16 +3,27 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llm_32k] [--no-long] [--no-cpu]
 
-A "step" is one diffusion step of one block: fb_internal_merge on every step plus
-fb_external_partial on refresh steps (t mod R == 0).  The headline value is the mean attention
-time per diffusion step on the LLM-shaped 32K-context workload with the prefix K/V resident in
-HBM; consecutive blocks rotate through distinct K/V buffer sets so that the 128 MiB of one set
-cannot be served from the last-level cache.  One JSON line is printed, with
-  roofline      the external-pass kernel against the HBM roofline (HIP events around that
-                kernel, recorded on the stream it runs on, in a second pass over the same loop),
+A "step" is one diffusion step of one block: fb_internal_merge on every step plus the external
+pass on refresh steps (t mod R == 0; both in one call, fb_refresh_step).  The headline value is the
+attention time per diffusion step on the LLM-shaped 32K-context workload with the prefix K/V
+resident in HBM; consecutive blocks rotate through distinct K/V buffer sets so that the 128 MiB of
+one set cannot be served from the last-level cache.
+
+Timing protocol.  After W warm-up steps (and at least 150 ms of the same work: the clock governor of
+the part needs that long to settle after an idle period, and the first ~50 ms of a load run up to
+40 % slower), exactly K steps are launched between two events recorded on the stream; when K steps
+are short the K-step sequence is repeated back to back and the value is the median over the
+repeats, so that it does not depend on K.  Every kernel-level number is the median (and minimum) of
+at least 30 event-bracketed launches after the same kind of warm-up.
+
+One JSON line is printed, with
+  roofline      the external-pass kernel against the HBM roofline: HIP events recorded on the
+                stream around that kernel inside the refresh-step call, plus the read ceiling of this
+                GPU measured in the same process by a kernel that only reads (measured_peak),
   cpu_baseline  the numpy float64 oracle timed on the host cores on whole blocks of the same shape,
-and extra objects for the full-recomputation comparison (R = 1 with the same kernels) and
-the 128K-context external pass.
+  parity        max |gpu - oracle| of this run on the tiny fp32 configuration and on a 32K block,
+and extra objects for the full-recomputation comparison (R = 1 with the same kernels), the
+128K-context external pass, the video-shaped (MFMA-bound), sparse and paged passes.
 """
 from __future__ import annotations
 
@@ -106,9 +117,12 @@ class DeviceBlock:
         fb = self.fb
         q, kb, vb = self.steps[t]
         if t % R == 0 and self.fused:
-            ev = prof if prof is not None else (None, None, None)
-            fb.fb_refresh_step_prof(self.shape, q, self.K[kv_set], self.V[kv_set], kb, vb, self.o, self.m, self.lse,
-                                    self.out, None, self.ws, ev[0], ev[1], ev[2])
+            if prof is None:
+                fb.fb_refresh_step(self.shape, q, self.K[kv_set], self.V[kv_set], kb, vb, self.o, self.m, self.lse,
+                                   self.out, None, self.ws)
+            else:
+                fb.fb_refresh_step_prof(self.shape, q, self.K[kv_set], self.V[kv_set], kb, vb, self.o, self.m,
+                                        self.lse, self.out, None, self.ws, prof[0], prof[1], prof[2])
             return
         if t % R == 0:
             if prof is None:
@@ -137,9 +151,20 @@ class DeviceBlock:
         return graphs
 
 
-def time_steps(dev, n_steps, warmup, R, use_graph):
-    """Wall-clock of exactly n_steps diffusion steps (whole blocks replayed as graphs, any
-    remainder eagerly), after `warmup` untimed steps.  Returns seconds."""
+WARM_SECONDS = 0.15      # same work, untimed, before any timed region (clock governor settling)
+
+
+def _median(xs):
+    xs = sorted(xs)
+    return xs[len(xs) // 2]
+
+
+def time_steps(dev, n_steps, warmup, R, use_graph, target_s=0.12, max_reps=400):
+    """Exactly n_steps diffusion steps (whole blocks replayed as graphs, any remainder eagerly) between two
+    events on the stream, after `warmup` untimed steps and at least WARM_SECONDS of the same work.  The
+    n_steps sequence is repeated back to back (about target_s of GPU time in all) and every repeat is timed.
+    Returns a dict: median / min us per step over the repeats, number of repeats, wall-clock us per step over
+    all repeats (host clock around the whole timed region, for cross-checking)."""
     torch = dev.torch
     S = dev.w.steps
     dev.run_eager(S, R)            # first launches (one-time kernel attribute calls) stay outside any capture
@@ -160,41 +185,72 @@ def time_steps(dev, n_steps, warmup, R, use_graph):
     run(warmup, 0)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    run(n_steps, 0)
+    done = 0
+    while time.perf_counter() - t0 < WARM_SECONDS:
+        run(max(n_steps, 10 * S), 0)
+        done += max(n_steps, 10 * S)
+        torch.cuda.synchronize()
+    est = (time.perf_counter() - t0) / max(done, 1)            # seconds per step, host clock, upper bound
+    reps = int(min(max_reps, max(5, math.ceil(target_s / max(est * n_steps, 1e-9)))))
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
     torch.cuda.synchronize()
-    return time.perf_counter() - t0
+    w0 = time.perf_counter()
+    for a, b in evs:
+        a.record()
+        run(n_steps, 0)
+        b.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - w0
+    us = [a.elapsed_time(b) * 1e3 / n_steps for a, b in evs]
+    return {"us": _median(us), "us_min": min(us), "repeats": reps, "wall_us": wall / (reps * n_steps) * 1e6}
 
 
-def profile_external(dev, n_blocks, R):
-    """Second pass over the same loop with HIP events around the external pass's kernels.
-    Returns mean ms of (attention kernel, combine kernel, whole external call) and of a whole
-    refresh step and reuse step."""
+def profile_external(dev, n_blocks, R, batch=8):
+    """The same loop with HIP events around the kernels of the external pass (recorded by the library between
+    its launches, on the stream they run on) and around every step.  Blocks are launched in batches of `batch`
+    with a synchronisation between batches (bounded number of events in flight), after WARM_SECONDS of the same
+    loop.  Returns us statistics of the attention kernel, the fold/combine kernel, a refresh step and a reuse step."""
     torch = dev.torch
     hev = HipEvents()
     S = dev.w.steps
-    recs = []
-    for b in range(n_blocks):
-        evs = [hev.create() for _ in range(3)]
-        step_ev = [torch.cuda.Event(enable_timing=True) for _ in range(S + 1)]
-        step_ev[0].record()
-        for t in range(S):
-            dev.step(t, b % dev.nsets, R, prof=evs if t == 0 else None)
-            step_ev[t + 1].record()
-        recs.append((evs, step_ev))
-    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    blk = 0
+    while time.perf_counter() - t0 < WARM_SECONDS:
+        for _ in range(4):
+            for t in range(S):
+                dev.step(t, blk % dev.nsets, R)
+            blk += 1
+        torch.cuda.synchronize()
+    pool = [[hev.create() for _ in range(3)] for _ in range(batch)]
     attn, comb, refresh, reuse = [], [], [], []
-    for evs, step_ev in recs[1:] if len(recs) > 1 else recs:     # first block is warm-up
-        attn.append(hev.elapsed_ms(evs[0], evs[1]))
-        comb.append(hev.elapsed_ms(evs[1], evs[2]))
-        for t in range(S):
-            (refresh if t % R == 0 else reuse).append(step_ev[t].elapsed_time(step_ev[t + 1]))
-    for evs, _ in recs:
+    left = n_blocks
+    while left > 0:
+        nb = min(batch, left)
+        step_evs = []
+        for i in range(nb):
+            sev = [torch.cuda.Event(enable_timing=True) for _ in range(S + 1)]
+            sev[0].record()
+            for t in range(S):
+                dev.step(t, blk % dev.nsets, R, prof=pool[i] if t == 0 else None)
+                sev[t + 1].record()
+            step_evs.append(sev)
+            blk += 1
+        torch.cuda.synchronize()
+        for i in range(nb):
+            attn.append(hev.elapsed_ms(pool[i][0], pool[i][1]) * 1e3)
+            comb.append(hev.elapsed_ms(pool[i][1], pool[i][2]) * 1e3)
+            for t in range(S):
+                (refresh if t % R == 0 else reuse).append(step_evs[i][t].elapsed_time(step_evs[i][t + 1]) * 1e3)
+        left -= nb
+    for evs in pool:
         for e in evs:
             hev.destroy(e)
     mean = lambda x: sum(x) / max(1, len(x))
-    med = lambda x: sorted(x)[len(x) // 2] if x else 0.0
-    return {"attn_ms": mean(attn), "attn_ms_min": min(attn), "combine_ms": mean(comb),
-            "refresh_step_ms": med(refresh), "reuse_step_ms": med(reuse), "launches": len(attn)}
+    if os.environ.get("FB_BENCH_DEBUG"):
+        print("attn us:", " ".join(f"{x:.0f}" for x in attn), file=sys.stderr)
+    return {"attn_us": mean(attn), "attn_us_median": _median(attn), "attn_us_min": min(attn),
+            "combine_us": _median(comb), "refresh_step_us": _median(refresh),
+            "reuse_step_us": _median(reuse) if reuse else 0.0, "launches": len(attn)}
 
 
 def read_traffic(workload_name):
@@ -208,22 +264,141 @@ def read_traffic(workload_name):
     return None
 
 
-def roofline_obj(w, attn_ms, traffic=None, fused=False):
+def roofline_obj(w, prof, traffic=None, fused=False, ceilings=None):
+    """HBM roofline of the streaming attention kernel of the external pass.  achieved = algorithmic bytes per
+    launch / mean launch duration (HIP events on the stream, this run); peak = the published 8 TB/s;
+    measured_peak = what a kernel that only reads the same number of bytes reached in this process."""
+    from paper_2602_05305_amd import flashblock as fb
     # fb_refresh_step streams the block's own keys in the attention kernel only for blocks above 64 rows;
     # at the LLM shapes its streaming kernel is the plain external pass
     streams_block = fused and (w.block_len > 64 or w.block_len % 4 != 0)
     alg = external_algorithmic_bytes(w, streams_block)
-    ach = alg / (attn_ms * 1e-3) / 1e9
-    # last template argument of the external pass: 2 = tiles fetched two ahead (>= 48 tiles per workgroup), else 0
-    from paper_2602_05305_amd import flashblock as fb
-    ns = fb.fb_external_splits(fb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.block_len, w.prefix_len, w.dtype))
-    var = 2 if -(-w.prefix_len // 64) >= 48 * max(ns, 1) else 0
-    kern = ("fb::attn_bf16_kernel<128, 6, 64, 1, 2, 0> (refresh step: prefix splits + the block's own keys, one streaming launch)"
-            if streams_block else f"fb::attn_bf16_kernel<128, 0, 64, 1, 2, {var}> (external pass, streaming attention kernel)")
-    return {"bound": "hbm", "kernel": kern,
-            "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": traffic,
-            "algorithmic_bytes_per_launch": alg, "avg_launch_us": round(attn_ms * 1e3, 2)}
+    us = prof["attn_us"]
+    ach = alg / us / 1e3
+    shape = fb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.block_len, w.prefix_len, w.dtype)
+    kern = ("fb::attn_bf16_kernel<.., 6, ..> (refresh step: prefix splits + the block's own keys, one streaming launch)"
+            if streams_block else "fb::" + fb.fb_external_kernel_name(shape) + " (external pass, streaming attention kernel)")
+    r = {"bound": "hbm", "kernel": kern,
+         "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+         "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": traffic,
+         "traffic_source": ("profiles/attn_bf16_external_%s_hbm_traffic.txt (rocprofv3 FETCH_SIZE / WRITE_SIZE of an "
+                            "earlier run of the same kernel and workload, not measured in this run)" % w.name)
+                           if traffic is not None else None,
+         "algorithmic_bytes_per_launch": alg, "avg_launch_us": round(us, 2),
+         "median_launch_us": round(prof["attn_us_median"], 2), "min_launch_us": round(prof["attn_us_min"], 2),
+         "launches_timed": prof["launches"]}
+    if ceilings is not None:
+        r["measured_peak"] = ceilings["read_GBps"]
+        r["frac_of_measured"] = round(ach / ceilings["read_GBps"], 4)
+        r["measured_peak_kernel"] = ceilings["read_kernel"]
+    return r
+
+
+class Calib:
+    """libfbcalib.so: kernels that do nothing but read, copy, or issue MFMAs (bench-only, not the product library)."""
+
+    def __init__(self):
+        path = os.path.join(ROOT, "paper_2602_05305_amd", "libfbcalib.so")
+        if not os.path.exists(path):
+            raise RuntimeError(f"{path} is missing: build it with `python -m paper_2602_05305_amd.build`")
+        lib = ctypes.CDLL(path)
+        vp = ctypes.c_void_p
+        lib.fbc_read_vgpr.argtypes = [vp, ctypes.c_size_t, ctypes.c_int, vp, vp]
+        lib.fbc_read_lds.argtypes = [vp, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, vp, vp]
+        lib.fbc_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+        lib.fbc_mfma.argtypes = [ctypes.c_int, ctypes.c_int, vp, vp]
+        self.lib = lib
+
+
+def measure_ceilings(torch, reps=30):
+    """What this GPU sustains, measured in this process with the calibration kernels: a pure read of 512 MiB
+    (three buffers rotated, so it comes from HBM) through registers and through direct-to-LDS loads into a ring
+    (the data path of the streaming attention kernel), a plain copy, and back-to-back bf16 MFMAs."""
+    lib = Calib().lib
+    st = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    nbytes = 512 * 1024 * 1024
+    bufs = [torch.full((nbytes,), 3, dtype=torch.uint8, device="cuda") for _ in range(3)]
+    sink = torch.zeros(64, dtype=torch.int32, device="cuda")
+    i = [0]
+
+    def check(rc):
+        if rc != 0:
+            raise RuntimeError(f"calibration launch failed: hipError {rc}")
+
+    def read_vgpr():
+        check(lib.fbc_read_vgpr(bufs[i[0] % 3].data_ptr(), nbytes, 512, sink.data_ptr(), st)); i[0] += 1
+
+    def read_lds():
+        check(lib.fbc_read_lds(bufs[i[0] % 3].data_ptr(), nbytes, 256, 4, sink.data_ptr(), st)); i[0] += 1
+
+    def copy():
+        check(lib.fbc_copy(bufs[(i[0] + 1) % 3].data_ptr(), bufs[i[0] % 3].data_ptr(), nbytes, st)); i[0] += 1
+
+    iters, wgs = 4000, 2048
+    flops = wgs * 4 * iters * 4 * 32768.0
+
+    def mfma():
+        check(lib.fbc_mfma(iters, wgs, sink.data_ptr(), st))
+
+    t_v, t_vmin = _ev_median_us(torch, read_vgpr, reps, 3, warm_s=0.1)
+    t_l, t_lmin = _ev_median_us(torch, read_lds, reps, 3, warm_s=0.1)
+    t_c, _ = _ev_median_us(torch, copy, reps, 3, warm_s=0.05)
+    t_m, t_mmin = _ev_median_us(torch, mfma, 10, 2, warm_s=0.05)
+    del bufs
+    torch.cuda.empty_cache()
+    best, kern = (t_v, "fbc_read_vgpr (16-byte loads into registers, 512 workgroups)") if t_v <= t_l else \
+                 (t_l, "fbc_read_lds (direct-to-LDS loads into a 4-stage ring, 256 workgroups)")
+    return {"read_GBps": round(nbytes / best / 1e3, 1), "read_kernel": kern,
+            "read_bytes": nbytes, "read_vgpr_us": round(t_v, 1), "read_vgpr_min_us": round(t_vmin, 1),
+            "read_lds_ring_us": round(t_l, 1), "read_lds_ring_min_us": round(t_lmin, 1),
+            "copy_GBps_read_plus_write": round(2 * nbytes / t_c / 1e3, 1),
+            "mfma_bf16_TFLOPs": round(flops / t_m / 1e6, 1), "mfma_us": round(t_m, 1),
+            "note": "medians of event-timed launches in this process; source paper_2602_05305_amd/csrc/fb_calib.hip"}
+
+
+def parity_obj(torch, fb, wl):
+    """max |gpu - oracle| of this run: the tiny fp32 configuration (all steps) and one whole block of the
+    LLM-shaped 32K workload (refresh step through fb_refresh_step, reuse steps through fb_internal_merge),
+    on the final output, on the normalised external attention A = o exp(m - lse) and on the log-normalisers."""
+    import numpy as np
+    from oracle import flashblock_oracle as orc
+    res = {}
+    for name in ("tiny_f32", "llm_32k"):
+        w = wl.CONFIGS[name]
+        tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
+        up = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to("cuda").to(tdt).contiguous()
+        Kp, Vp = wl.make_prefix(w, 7)
+        steps = wl.make_block_steps(w, 7)
+        want = orc.run_block_dense(Kp, Vp, steps, w.refresh)
+        shape = fb.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.block_len, w.prefix_len, w.dtype)
+        rows = (w.batch, w.n_q_heads, w.block_len)
+        o = torch.empty(rows + (w.head_dim,), device="cuda")
+        m, lse = torch.empty(rows, device="cuda"), torch.empty(rows, device="cuda")
+        lse_out = torch.empty(rows, device="cuda")
+        ws = torch.empty(fb.fb_workspace_bytes(shape), device="cuda", dtype=torch.uint8)
+        kp, vp = up(Kp), up(Vp)
+        e_out = e_A = e_L = e_Lf = 0.0
+        for t, (Q, Kb, Vb) in enumerate(steps):
+            q, kb, vb = up(Q), up(Kb), up(Vb)
+            out = torch.empty_like(q)
+            if t % w.refresh == 0:
+                fb.fb_refresh_step(shape, q, kp, vp, kb, vb, o, m, lse, out, lse_out, ws)
+            else:
+                fb.fb_internal_merge(shape, q, kb, vb, o, m, lse, out, lse_out)
+            torch.cuda.synchronize()
+            e_out = max(e_out, float(np.abs(out.double().cpu().numpy() - want[t]["out"]).max()))
+            e_Lf = max(e_Lf, float(np.abs(lse_out.double().cpu().numpy() - want[t]["lse"]).max()))
+            if t % w.refresh == 0:
+                got = {"o": o.double().cpu().numpy(), "m": m.double().cpu().numpy(), "lse": lse.double().cpu().numpy()}
+                e_A = max(e_A, float(np.abs(orc.normalized(got) - orc.normalized(want[t]["ext"])).max()))
+                e_L = max(e_L, float(np.abs(got["lse"] - want[t]["ext"]["lse"]).max()))
+        res[name] = {"steps": len(steps), "max_abs_err_out": e_out, "max_abs_err_A_ext": e_A,
+                     "max_abs_err_L_ext": e_L, "max_abs_err_L_full": e_Lf,
+                     "tolerance": "1e-5 max-abs" if w.dtype == "f32" else "1e-2 abs + 1e-2 rel"}
+        del kp, vp
+        torch.cuda.empty_cache()
+    res["note"] = "float64 numpy oracle on the same seeded inputs (bf16 inputs rounded before both sides)"
+    return res
 
 
 def cpu_baseline(w, budget_s=12.0):
@@ -252,16 +427,17 @@ def cpu_baseline(w, budget_s=12.0):
             "host_cores_visible": len(os.sched_getaffinity(0))}
 
 
-def _ev_median_us(torch, fn, reps=15, warm=3):
-    """Median event-timed duration of fn.  Clocks take a while to settle on a freshly idle GPU (the
-    first ~10 ms of a compute-bound kernel run measurably slower), so warm up for at least 20 ms."""
+def _ev_median_us(torch, fn, reps=30, warm=3, warm_s=0.05):
+    """(median, min) event-timed duration of fn in us over `reps` launches.  Clocks take a while to settle on a
+    freshly idle GPU, so fn is first run untimed for at least warm_s seconds."""
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     n = 0
-    while n < warm or time.perf_counter() - t0 < 0.02:
+    while n < warm or time.perf_counter() - t0 < warm_s:
         fn()
-        torch.cuda.synchronize()
         n += 1
+        if n % 8 == 0:
+            torch.cuda.synchronize()
     torch.cuda.synchronize()
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
     for a, b in evs:
@@ -270,7 +446,7 @@ def _ev_median_us(torch, fn, reps=15, warm=3):
         b.record()
     torch.cuda.synchronize()
     ts = sorted(a.elapsed_time(b) for a, b in evs)
-    return ts[len(ts) // 2] * 1e3
+    return ts[len(ts) // 2] * 1e3, ts[0] * 1e3
 
 
 def video_extra(torch, fb, wl):
@@ -278,29 +454,32 @@ def video_extra(torch, fb, wl):
     w = wl.CONFIGS["video"]
     d = DeviceBlock(w, 1)
     q, kb, vb = d.steps[0]
-    t_ext = _ev_median_us(torch, lambda: fb.fb_external_partial(d.shape, q, d.K[0], d.V[0], d.o, d.m, d.lse, d.ws), 7, 2)
-    t_int = _ev_median_us(torch, lambda: fb.fb_internal_merge(d.shape, q, kb, vb, d.o, d.m, d.lse, d.out, None), 7, 2)
+    t_ext, t_ext_min = _ev_median_us(torch, lambda: fb.fb_external_partial(d.shape, q, d.K[0], d.V[0], d.o, d.m, d.lse, d.ws))
+    t_int, t_int_min = _ev_median_us(torch, lambda: fb.fb_internal_merge(d.shape, q, kb, vb, d.o, d.m, d.lse, d.out, None))
     hm = torch.zeros((w.batch, w.n_q_heads), device="cuda", dtype=torch.uint8)
     hm[:, ::2] = 1                       # head-wise selective refresh: every other head recomputed
     ns_h = max(fb.fb_external_heads_splits(d.shape, w.n_q_heads // 2), fb.fb_external_heads_splits(d.shape, 1), 1)
     ws_h = torch.empty(fb.fb_workspace_bytes(d.shape, 0, 0, ns_h), device="cuda", dtype=torch.uint8)
-    t_half = _ev_median_us(torch, lambda: fb.fb_external_partial_heads(d.shape, q, d.K[0], d.V[0], hm, d.o, d.m, d.lse,
-                                                                       ws_h, w.n_q_heads // 2), 7, 2)
+    t_half, _ = _ev_median_us(torch, lambda: fb.fb_external_partial_heads(d.shape, q, d.K[0], d.V[0], hm, d.o, d.m, d.lse,
+                                                                          ws_h, w.n_q_heads // 2))
     hm1 = torch.zeros((w.batch, w.n_q_heads), device="cuda", dtype=torch.uint8)
     hm1[:, 3] = 1                        # a single unstable head
-    t_one = _ev_median_us(torch, lambda: fb.fb_external_partial_heads(d.shape, q, d.K[0], d.V[0], hm1, d.o, d.m, d.lse,
-                                                                      ws_h, 1), 7, 2)
+    t_one, _ = _ev_median_us(torch, lambda: fb.fb_external_partial_heads(d.shape, q, d.K[0], d.V[0], hm1, d.o, d.m, d.lse,
+                                                                         ws_h, 1))
     f_ext = 4.0 * w.batch * w.n_q_heads * w.block_len * w.prefix_len * w.head_dim
     f_int = 4.0 * w.batch * w.n_q_heads * w.block_len * w.block_len * w.head_dim
     peak = 2500.0
     S, R = w.steps, w.refresh
     return {"workload": describe(w), "bound": "mfma", "peak": peak, "unit": "TFLOP/s",
-            "external_us": round(t_ext, 1), "external_tflops": round(f_ext / t_ext / 1e6, 1),
+            "external_us": round(t_ext, 1), "external_min_us": round(t_ext_min, 1),
+            "external_tflops": round(f_ext / t_ext / 1e6, 1),
             "external_frac": round(f_ext / t_ext / 1e6 / peak, 4),
             "external_half_of_heads_us": round(t_half, 1), "external_one_head_us": round(t_one, 1),
-            "internal_us": round(t_int, 1), "internal_tflops": round(f_int / t_int / 1e6, 1),
+            "internal_us": round(t_int, 1), "internal_min_us": round(t_int_min, 1),
+            "internal_tflops": round(f_int / t_int / 1e6, 1),
             "internal_frac": round(f_int / t_int / 1e6 / peak, 4),
-            "block_speedup_cached_vs_full": round(S * (t_ext + t_int) / (-(-S // R) * t_ext + S * t_int), 3)}
+            "block_speedup_cached_vs_full": round(S * (t_ext + t_int) / (-(-S // R) * t_ext + S * t_int), 3),
+            "timing": "median (and min) of 30 event-timed calls after 50 ms of the same call"}
 
 
 def sparse_extra(torch, fb, wl):
@@ -316,15 +495,15 @@ def sparse_extra(torch, fb, wl):
     rm, rl = torch.empty(rows, device="cuda"), torch.empty(rows, device="cuda")
     q = d.steps[0][0]
     i = [0]
-    t_pool = _ev_median_us(torch, lambda: fb.fb_pool_keys(d.shape, d.K[0], w.key_block, pooled[0]))
+    t_pool, t_pool_min = _ev_median_us(torch, lambda: fb.fb_pool_keys(d.shape, d.K[0], w.key_block, pooled[0]))
     fb.fb_pool_keys(d.shape, d.K[1], w.key_block, pooled[1])
-    t_sel1 = _ev_median_us(torch, lambda: fb.fb_select_topk(d.shape, q, pooled[0], w.key_block, w.topk, idx))
+    t_sel1, t_sel1_min = _ev_median_us(torch, lambda: fb.fb_select_topk(d.shape, q, pooled[0], w.key_block, w.topk, idx))
     sws = torch.empty(fb.fb_select_workspace_bytes(d.shape, w.key_block), device="cuda", dtype=torch.uint8)
-    t_sel = _ev_median_us(torch, lambda: fb.fb_select_topk(d.shape, q, pooled[0], w.key_block, w.topk, idx, sws))
+    t_sel, t_sel_min = _ev_median_us(torch, lambda: fb.fb_select_topk(d.shape, q, pooled[0], w.key_block, w.topk, idx, sws))
     wsm = torch.empty(fb.fb_select_mass_workspace_bytes(d.shape, w.key_block), device="cuda", dtype=torch.uint8)
     fb.fb_external_partial(d.shape, q, d.K[0], d.V[0], d.o, d.m, d.lse, ws)
     idx_m = torch.empty_like(idx)
-    t_mass = _ev_median_us(torch, lambda: fb.fb_select_topk_mass(d.shape, q, d.K[i[0] % 2], d.lse, w.key_block, w.topk,
+    t_mass, t_mass_min = _ev_median_us(torch, lambda: fb.fb_select_topk_mass(d.shape, q, d.K[i[0] % 2], d.lse, w.key_block, w.topk,
                                                                    idx_m, None, wsm))
 
     def call(mode):
@@ -332,11 +511,11 @@ def sparse_extra(torch, fb, wl):
         i[0] += 1
         fb.fb_sparse_external_residual(d.shape, mode, q, d.K[s], d.V[s], w.key_block, w.topk, idx, ro, rm, rl,
                                        d.o, d.m, d.lse, ws)
-    t_refresh = _ev_median_us(torch, lambda: call(fb.FB_SPARSE_REFRESH))
-    t_reuse_rebuild = _ev_median_us(torch, lambda: call(fb.FB_SPARSE_REUSE))
+    t_refresh, t_refresh_min = _ev_median_us(torch, lambda: call(fb.FB_SPARSE_REFRESH))
+    t_reuse_rebuild, t_reuse_rebuild_min = _ev_median_us(torch, lambda: call(fb.FB_SPARSE_REUSE))
     # reuse steps of a block keep the refresh step's selection: no mask rebuild
-    t_reuse = _ev_median_us(torch, lambda: call(fb.FB_SPARSE_REUSE_SAME_SELECTION))
-    t_dense = _ev_median_us(torch, lambda: fb.fb_external_partial(d.shape, q, d.K[i[0] % 2], d.V[i[0] % 2], d.o, d.m, d.lse, ws))
+    t_reuse, t_reuse_min = _ev_median_us(torch, lambda: call(fb.FB_SPARSE_REUSE_SAME_SELECTION))
+    t_dense, t_dense_min = _ev_median_us(torch, lambda: fb.fb_external_partial(d.shape, q, d.K[i[0] % 2], d.V[i[0] % 2], d.o, d.m, d.lse, ws))
     sel = idx.cpu().numpy()
     G = w.n_q_heads // w.n_kv_heads
     union = sum(len(set(sel[0, kv * G:(kv + 1) * G].ravel().tolist())) for kv in range(w.n_kv_heads))
@@ -348,9 +527,14 @@ def sparse_extra(torch, fb, wl):
             "sparse_refresh_call_us": round(t_refresh, 1), "sparse_reuse_call_us": round(t_reuse, 1),
             "sparse_reuse_call_rebuilding_masks_us": round(t_reuse_rebuild, 1),
             "dense_external_call_us": round(t_dense, 1),
+            "sparse_refresh_call_min_us": round(t_refresh_min, 1), "sparse_reuse_call_min_us": round(t_reuse_min, 1),
+            "dense_external_call_min_us": round(t_dense_min, 1),
             "union_fraction_of_prefix": round(union / (nblk * w.n_kv_heads), 3),
             "reuse_union_bytes": union_bytes, "reuse_GBps_vs_union_bytes": round(union_bytes / t_reuse / 1e3, 1),
-            "refresh_GBps_vs_kv_bytes": round(w.kv_bytes / t_refresh / 1e3, 1)}
+            "reuse_frac_of_8TBps_vs_union_bytes": round(union_bytes / t_reuse / 1e3 / HBM_PEAK_GBS, 4),
+            "refresh_GBps_vs_kv_bytes": round(w.kv_bytes / t_refresh / 1e3, 1),
+            "refresh_frac_of_8TBps_vs_kv_bytes": round(w.kv_bytes / t_refresh / 1e3 / HBM_PEAK_GBS, 4),
+            "timing": "median (and min) of 30 event-timed calls after 50 ms of the same call"}
 
 
 def paged_setup(torch, fb, wl):
@@ -399,8 +583,9 @@ def paged_extra(torch, fb, wl):
     """Bandwidth of the paged external pass, priced against the K/V bytes of the tokens that exist
     (not of the padded maximum)."""
     call, info = paged_setup(torch, fb, wl)
-    t = _ev_median_us(torch, call)
-    info.update({"external_call_us": round(t, 1), "GBps_vs_kv_bytes": round(info["kv_bytes"] / t / 1e3, 1),
+    t, tmin = _ev_median_us(torch, call)
+    info.update({"external_call_us": round(t, 1), "external_call_min_us": round(tmin, 1),
+                 "GBps_vs_kv_bytes": round(info["kv_bytes"] / t / 1e3, 1),
                  "frac_of_8TBps": round(info["kv_bytes"] / t / 1e3 / 8000.0, 4)})
     return info
 
@@ -477,8 +662,8 @@ def gamma_calibration(torch, fb, wl, gamma=0.85):
     err = torch.stack(err).mean(dim=0)
     err_stale = torch.stack(err_stale).mean(dim=0)
     q = steps[1][0]
-    t_full = _ev_median_us(torch, lambda: fb.fb_external_partial(shape, q, K, V, *full, ws), 9, 3)
-    t_sel = (_ev_median_us(torch, lambda: fb.fb_external_partial_heads(shape, q, K, V, mask, *part, wsh, n_refresh), 9, 3)
+    t_full = _ev_median_us(torch, lambda: fb.fb_external_partial(shape, q, K, V, *full, ws), 9, 3)[0]
+    t_sel = (_ev_median_us(torch, lambda: fb.fb_external_partial_heads(shape, q, K, V, mask, *part, wsh, n_refresh), 9, 3)[0]
              if n_refresh > 0 else 0.0)
     ref_scale = float(out_full.float().abs().mean())
     return {"workload": describe(w), "gamma": gamma,
@@ -657,6 +842,11 @@ def main():
                          "fb_refresh_step (2 launches)")
     ap.add_argument("--no-long", action="store_true", help="skip the 128K-context external-pass measurement")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-parity", action="store_true", help="skip the gpu-vs-oracle error report")
+    ap.add_argument("--no-calibration", action="store_true", help="skip the read / MFMA ceiling measurement")
+    ap.add_argument("--calibration-only", action="store_true",
+                    help="only print the measured ceilings (pure read, copy, MFMA-only kernels); also what the "
+                         "rocprofv3 summaries under profiles/ of those kernels run")
     ap.add_argument("--no-extras", action="store_true", help="skip the video-shaped (MFMA), sparse and paged measurements")
     ap.add_argument("--profile-external", type=int, default=0, metavar="N",
                     help="only run N whole blocks of the workload, eagerly (for rocprofv3), print nothing else")
@@ -671,7 +861,7 @@ def main():
     ap.add_argument("--profile-paged", type=int, default=0, metavar="N",
                     help="only run N paged external passes of the batch-32 serving shape (for rocprofv3)")
     ap.add_argument("--profile-copy", type=int, default=0, metavar="N",
-                    help="only run N plain device copies of 256 MiB (calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE)")
+                    help="only run N launches of the plain copy kernel on 256 MiB (calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (the path has no multi-GPU part); use --gpus 1",
@@ -687,13 +877,19 @@ def main():
         sys.exit(3)
     torch.cuda.set_device(0)
     w = wl.CONFIGS[args.workload]
+    if args.calibration_only:
+        print(json.dumps(measure_ceilings(torch)))
+        return
     if args.profile_copy > 0:
         x = torch.full((256 * 1024 * 1024,), 3, dtype=torch.uint8, device="cuda")
         y = torch.empty_like(x)
+        lib = Calib().lib
+        st = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
         for _ in range(args.profile_copy):
-            y.copy_(x)
+            if lib.fbc_copy(y.data_ptr(), x.data_ptr(), x.numel(), st) != 0:
+                raise RuntimeError("fbc_copy launch failed")
         torch.cuda.synchronize()
-        print(f"ran {args.profile_copy} device copies of {x.numel()} bytes (read {x.numel()} + write {x.numel()} per copy)")
+        print(f"ran {args.profile_copy} copy kernels of {x.numel()} bytes (read {x.numel()} + write {x.numel()} per launch)")
         return
     if args.profile_paged > 0:
         call, info = paged_setup(torch, fb, wl)
@@ -745,17 +941,19 @@ def main():
     K, W = args.steps, args.warmup
     nsets = max(2, min(4, int(-(-600e6 // w.kv_bytes))))     # working set well beyond the last-level cache
     fused = not args.split_refresh
+    ceilings = None if args.no_calibration else measure_ceilings(torch)
     dev = DeviceBlock(w, nsets, fused=fused)
 
-    # Exactly K steps after W warm-up steps, in both launch modes unless one is forced; the faster one
+    # Exactly K steps per repeat after W warm-up steps, in both launch modes unless one is forced; the faster one
     # is the reported value (the other is listed in steps_detail).
     modes = {"graph": [True], "eager": [False], "auto": [True, False]}["eager" if args.no_graph else args.launch]
-    timed = {g: time_steps(dev, K, W, w.refresh, g) / K * 1e6 for g in modes}
-    use_graph = min(timed, key=timed.get)
-    us_step = timed[use_graph]
-    sec_full = time_steps(dev, K, W, 1, use_graph)           # full recomputation: refresh on every step
-    us_full = sec_full / K * 1e6
-    prof = profile_external(dev, 41, w.refresh)
+    timed = {g: time_steps(dev, K, W, w.refresh, g) for g in modes}
+    use_graph = min(timed, key=lambda g: timed[g]["us"])
+    tm = timed[use_graph]
+    us_step = tm["us"]
+    full = time_steps(dev, K, W, 1, use_graph)               # full recomputation: refresh on every step
+    us_full = full["us"]
+    prof = profile_external(dev, 40, w.refresh)
 
     traffic = read_traffic(w.name)
     line = {
@@ -768,40 +966,43 @@ def main():
                    "launch": "one HIP graph per block" if use_graph else "eager",
                    "refresh_step": "fb_refresh_step (2 launches)" if fused else "fb_external_partial + fb_internal_merge (3 launches)",
                    "external_splits": fb.fb_external_splits(dev.shape)},
-        "roofline": roofline_obj(w, prof["attn_ms"], traffic, fused),
-        "steps_detail": {"refresh_step_us": round(prof["refresh_step_ms"] * 1e3, 2),
-                         "reuse_step_us": round(prof["reuse_step_ms"] * 1e3, 2),
-                         "external_attn_kernel_us": round(prof["attn_ms"] * 1e3, 2),
+        "timing": {"protocol": f"{W} warm-up steps and >= {WARM_SECONDS} s of the same work, then {tm['repeats']} back-to-back "
+                               f"repeats of exactly {K} steps, each between two events on the stream; value = median over repeats",
+                   "repeats": tm["repeats"], "us_per_step_min_over_repeats": round(tm["us_min"], 3),
+                   "wall_clock_us_per_step_over_all_repeats": round(tm["wall_us"], 3)},
+        "roofline": roofline_obj(w, prof, traffic, fused, ceilings),
+        "steps_detail": {"refresh_step_us": round(prof["refresh_step_us"], 2),
+                         "reuse_step_us": round(prof["reuse_step_us"], 2),
+                         "external_attn_kernel_us": round(prof["attn_us"], 2),
                          ("refresh_fold_kernel_us (split fold + block-internal attention + merge)" if fused
-                          else "external_combine_kernel_us"): round(prof["combine_ms"] * 1e3, 2),
-                         "us_per_step_by_launch_mode": {("hip_graph_per_block" if g else "eager"): round(t, 3)
+                          else "external_combine_kernel_us"): round(prof["combine_us"], 2),
+                         "us_per_step_by_launch_mode": {("hip_graph_per_block" if g else "eager"): round(t["us"], 3)
                                                         for g, t in timed.items()}},
         "full_recompute": {"us_per_step": round(us_full, 3), "speedup_cached_vs_full": round(us_full / us_step, 3),
                            "note": "same kernels with refresh interval 1"},
     }
+    if ceilings is not None:
+        line["calibration"] = ceilings
     # the same external pass with the prefix resident in the last-level cache (one K/V set, never rotated)
     dev_warm = DeviceBlock(w, 1, fused=fused)
-    pw = profile_external(dev_warm, 31, w.refresh)
-    line["steps_detail"]["external_attn_kernel_us_prefix_in_llc"] = round(pw["attn_ms"] * 1e3, 2)
+    pw = profile_external(dev_warm, 32, w.refresh)
+    line["steps_detail"]["external_attn_kernel_us_prefix_in_llc"] = round(pw["attn_us"], 2)
     del dev_warm, dev
     torch.cuda.empty_cache()
 
     if not args.no_long:
         wl128 = wl.CONFIGS["long_128k"]
         d2 = DeviceBlock(wl128, 2, fused=fused)
-        for _ in range(3):
-            d2.step(0, 0, wl128.refresh)
-        p2 = profile_external(d2, 21, wl128.refresh)
-        r2 = roofline_obj(wl128, p2["attn_ms"], read_traffic(wl128.name), fused)
+        p2 = profile_external(d2, 32, wl128.refresh)
+        r2 = roofline_obj(wl128, p2, read_traffic(wl128.name), fused, ceilings)
         r2["workload"] = describe(wl128)
-        r2["external_call_us"] = round((p2["attn_ms"] + p2["combine_ms"]) * 1e3, 2)
-        r2["refresh_step_us"] = round(p2["refresh_step_ms"] * 1e3, 2)
-        r2["reuse_step_us"] = round(p2["reuse_step_ms"] * 1e3, 2)
+        r2["external_call_us"] = round(p2["attn_us_median"] + p2["combine_us"], 2)
+        r2["refresh_step_us"] = round(p2["refresh_step_us"], 2)
+        r2["reuse_step_us"] = round(p2["reuse_step_us"], 2)
         # refresh-interval sweep (speedup of caching against full recomputation = R 1), eager launches
         sweep = {}
         for R in (1, 2, 4, 8):
-            n = 40 * wl128.steps
-            sweep[f"R={R}"] = round(time_steps(d2, n, wl128.steps, R, False) / n * 1e6, 2)
+            sweep[f"R={R}"] = round(time_steps(d2, 5 * wl128.steps, wl128.steps, R, False, target_s=0.04)["us"], 2)
         r2["us_per_step_by_refresh_interval"] = sweep
         r2["speedup_R8_vs_R1"] = round(sweep["R=1"] / sweep["R=8"], 3)
         line["external_128k"] = r2
@@ -810,12 +1011,10 @@ def main():
         # batch 4 at the same context length (2.1 GB of K/V per pass)
         w4 = wl.CONFIGS["long_128k_b4"]
         d4 = DeviceBlock(w4, 2, fused=fused)
-        for _ in range(3):
-            d4.step(0, 0, w4.refresh)
-        p4 = profile_external(d4, 11, w4.refresh)
-        r4 = roofline_obj(w4, p4["attn_ms"], None, fused)
+        p4 = profile_external(d4, 32, w4.refresh)
+        r4 = roofline_obj(w4, p4, None, fused, ceilings)
         r4["workload"] = describe(w4)
-        r4["refresh_step_us"] = round(p4["refresh_step_ms"] * 1e3, 2)
+        r4["refresh_step_us"] = round(p4["refresh_step_us"], 2)
         line["external_128k_batch4"] = r4
         del d4
         torch.cuda.empty_cache()
@@ -833,10 +1032,12 @@ def main():
         wt = wl.CONFIGS["tiny_f32"]
         dt_ = DeviceBlock(wt, 2, fused=fused)
         nt = 50 * wt.steps
-        line["tiny_f32"] = {"workload": describe(wt), "us_per_step": round(time_steps(dt_, nt, wt.steps, wt.refresh, False) / nt * 1e6, 2),
+        line["tiny_f32"] = {"workload": describe(wt), "us_per_step": round(time_steps(dt_, nt, wt.steps, wt.refresh, False, target_s=0.03)["us"], 2),
                             "note": "launch-bound: a roofline fraction is not meaningful at this size"}
         del dt_
 
+    if not args.no_parity:
+        line["parity"] = parity_obj(torch, fb, wl)
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(line))

@@ -31,9 +31,12 @@
  *     The normalised pair of Eq. 6 is A_i = o_i * exp(m_i - lse_i), L_i = lse_i.
  *     An empty key set gives o = 0, m = lse = -inf.
  *   - Ownership: the caller allocates and frees every buffer, including the workspace.  The
- *     library allocates no device memory, keeps no state between calls, never synchronises the
- *     device and launches only on the HIP stream passed in (hipStream_t cast to void*; NULL is
- *     the default stream).  Calls are asynchronous; buffers must stay valid until the stream
+ *     library allocates no device memory, never synchronises the device and launches only on the
+ *     HIP stream passed in (hipStream_t cast to void*; NULL is the default stream).  The only
+ *     state it keeps between calls is, per kernel, the set of devices on which the kernel's
+ *     dynamic-LDS limit has been raised (a one-time hipFuncSetAttribute per kernel and device,
+ *     remembered in an atomic word, safe to race from several host threads) and the text of the
+ *     last HIP error per thread.  Calls are asynchronous; buffers must stay valid until the stream
  *     has passed the call.  Two calls that share a workspace must be ordered on one stream.
  *   - Alignment: every tensor pointer must be 16-byte aligned (FB_ERR_ALIGN otherwise).
  *   - Errors: every entry point returns an fb_status; nothing throws or aborts.  Arguments are
@@ -101,6 +104,12 @@ fb_status fb_check_shape(const fb_shape* shape);
  * uses for this shape when the caller passes n_splits = 0.  Host only.  0 on invalid shape. */
 int32_t fb_external_splits(const fb_shape* shape);
 
+/* Name (as a profiler's kernel trace prints it, without the namespace) of the streaming attention
+ * kernel fb_external_partial launches for this shape with the library's own split count: the
+ * kernel whose duration the roofline of the external pass is about.  Host only.  Host string owned
+ * by the library, valid until the next call on the same thread; "" on an invalid shape. */
+const char* fb_external_kernel_name(const fb_shape* shape);
+
 /* Bytes of device workspace one call needs on this shape.  n_splits = 0 sizes for the
  * library's own split choice (what fb_external_partial and fb_sparse_external_residual use),
  * otherwise for fb_external_partial_ex with that split count.  key_block = 0 sizes the dense
@@ -127,16 +136,6 @@ fb_status fb_external_partial_ex(const fb_shape* shape, const void* q, const voi
                                  const void* v_prefix, float* o_part, float* m_part,
                                  float* lse_part, int32_t n_splits, void* workspace,
                                  size_t workspace_bytes, void* hip_stream);
-
-/* Profiling aid: fb_external_partial_ex that also records three caller-created HIP events
- * (hipEvent_t cast to void*, created with timing enabled) on hip_stream: ev_begin before the
- * streaming attention kernel, ev_attn_end between it and the split combine, ev_end after the
- * combine.  Any of the three may be NULL.  Results are identical to fb_external_partial_ex. */
-fb_status fb_external_partial_prof(const fb_shape* shape, const void* q, const void* k_prefix,
-                                   const void* v_prefix, float* o_part, float* m_part,
-                                   float* lse_part, int32_t n_splits, void* workspace,
-                                   size_t workspace_bytes, void* ev_begin, void* ev_attn_end,
-                                   void* ev_end, void* hip_stream);
 
 /*
  * Head-wise selective refresh (Section 4.2, "Selective reuse": for video models only heads whose
@@ -241,15 +240,6 @@ fb_status fb_refresh_step(const fb_shape* shape, const void* q, const void* k_pr
                           const void* v_prefix, const void* k_block, const void* v_block,
                           float* o_part, float* m_part, float* lse_part, void* out, float* lse_out,
                           void* workspace, size_t workspace_bytes, void* hip_stream);
-
-/* Profiling aid: fb_refresh_step that also records three caller-created HIP events, as
- * fb_external_partial_prof does (before the streaming kernel, between it and the combine, after
- * the combine).  Any of the three may be NULL.  Results are identical to fb_refresh_step. */
-fb_status fb_refresh_step_prof(const fb_shape* shape, const void* q, const void* k_prefix,
-                               const void* v_prefix, const void* k_block, const void* v_block,
-                               float* o_part, float* m_part, float* lse_part, void* out,
-                               float* lse_out, void* workspace, size_t workspace_bytes,
-                               void* ev_begin, void* ev_attn_end, void* ev_end, void* hip_stream);
 
 /*
  * Sparse variant, key-block selection (this library's workload rule; the paper leaves the

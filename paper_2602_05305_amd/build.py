@@ -1,8 +1,9 @@
-"""Build libflashblock.so (hand-written HIP for gfx950) in-tree with hipcc.
+"""Build libflashblock.so (hand-written HIP for gfx950) and libfbcalib.so (the benchmark's calibration
+kernels: read and MFMA ceilings, a plain copy) in-tree with hipcc.
 
     python -m paper_2602_05305_amd.build [--force]
 
-The library is written next to this file so that it travels with the source tree; nothing is
+The libraries are written next to this file so that they travel with the source tree; nothing is
 installed.  Objects go to paper_2602_05305_amd/_build/ (ignored by git).
 """
 from __future__ import annotations
@@ -16,6 +17,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libflashblock.so")
+CALIB_LIB = os.path.join(HERE, "libfbcalib.so")
+CALIB_SOURCES = ["fb_calib.hip"]
 SOURCES = ["fb_api.hip", "fb_attn_f32.hip", "fb_attn_bf16.hip", "fb_stream_bf16.hip", "fb_aux.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
@@ -41,17 +44,18 @@ def _compile(src: str) -> str:
 def build(force: bool = True) -> str:
     """Compile every HIP source for gfx950 and link the shared library.  Returns its path."""
     os.makedirs(OBJ, exist_ok=True)
-    if not force and os.path.exists(LIB):
+    if not force and os.path.exists(LIB) and os.path.exists(CALIB_LIB):
         newest = max(os.path.getmtime(os.path.join(CSRC, f)) for f in os.listdir(CSRC))
         newest = max(newest, os.path.getmtime(os.path.join(HERE, "..", "include", "flashblock.h")))
-        if os.path.getmtime(LIB) >= newest:
+        if min(os.path.getmtime(LIB), os.path.getmtime(CALIB_LIB)) >= newest:
             return LIB
-    with ThreadPoolExecutor(max_workers=4) as ex:
-        objs = list(ex.map(_compile, SOURCES))
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
+    with ThreadPoolExecutor(max_workers=6) as ex:
+        objs = list(ex.map(_compile, SOURCES + CALIB_SOURCES))
+    for lib, lobjs in ((LIB, objs[:len(SOURCES)]), (CALIB_LIB, objs[len(SOURCES):])):
+        cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *lobjs]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
     return LIB
 
 

@@ -1,12 +1,13 @@
 // C-ABI layer of libflashblock.so: argument validation (host only, no GPU touched), split
 // heuristics, workspace carving and kernel dispatch.  Contract: include/flashblock.h.
 #include <math.h>
+#include <stdio.h>
 #include <string.h>
 
 #include <algorithm>
 #include <string>
 
-#include "../../include/flashblock.h"
+#include "../../include/flashblock_prof.h"
 #include "fb_kernels.h"
 
 namespace {
@@ -221,6 +222,19 @@ fb_status fb_check_shape(const fb_shape* shape) { return check_shape(shape); }
 int32_t fb_external_splits(const fb_shape* shape) {
   if (check_shape(shape) != FB_OK) return 0;
   return dense_splits(shape);
+}
+
+const char* fb_external_kernel_name(const fb_shape* shape) {
+  thread_local char name[96];
+  name[0] = 0;
+  if (check_shape(shape) != FB_OK) return name;
+  if (shape->dtype != FB_BF16) {
+    snprintf(name, sizeof(name), "attn_f32_kernel<%d, %d>", shape->head_dim, (int)fb::kPassDense);
+    return name;
+  }
+  const fb::PassParams p = base_pass(shape, nullptr, nullptr, nullptr, shape->prefix_len, dense_splits(shape));
+  fb::attn_bf16_dense_name(p, shape->head_dim, name, sizeof(name));
+  return name;
 }
 
 int32_t fb_paged_splits(const fb_shape* shape) {

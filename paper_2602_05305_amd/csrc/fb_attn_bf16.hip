@@ -32,6 +32,8 @@
 //   tile t is computed from LDS; one barrier per tile.
 // Precision: bf16 operands, fp32 MFMA accumulation, fp32 max / sum / rescale, probabilities
 // rounded to bf16 for the PV product; scores live in the log2 domain (scale*log2(e) folded).
+#include <stdio.h>
+
 #include "fb_kernels.h"
 
 namespace fb {
@@ -893,14 +895,13 @@ __global__ __launch_bounds__(256) void block_mass_bf16_kernel(const MassParams p
 
 template <int D, int MODE, int KT, int WS, int NG, int VAR = 0>
 hipError_t launch_one(const PassParams& p, hipStream_t s) {
-  static bool attr_set = false;   // raising the dynamic-LDS limit is idempotent; the flag only saves calls
+  static LdsLimit lim;
   constexpr bool RP = (VAR & 1) != 0;
   auto kern = attn_bf16_kernel<D, MODE, KT, WS, NG, VAR>;
   constexpr int lds = Cfg<D, KT>::LDS * ((MODE == kPassSparseRefresh || RP) ? 1 : NG);
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  {
+    hipError_t e = raise_lds_limit(kern, lds, lim, lds);
     if (e != hipSuccess) return e;
-    attr_set = true;
   }
   constexpr int rows_per_wg = RP ? 2 * kRowsPerWgBf16 : kRowsPerWgBf16 / WS;
   const int nrows = p.G * p.Bq;
@@ -926,33 +927,50 @@ inline bool use_row_pairs(const PassParams& p) {
   return nrows >= 1024 && wgs >= 128;
 }
 
+// Template arguments <column split, wavefront groups, variant> of the dense external pass for a shape: the one
+// place that decides them, for the launcher and for the name the benchmark reports.
+struct DenseVariant {
+  int ws, ng, var;
+};
+
+template <int D>
+DenseVariant dense_variant(const PassParams& p) {
+  constexpr int WSMAX = (D / 32 >= 4) ? 4 : 2;
+  // 8-wave workgroups for split-KV streaming when every wavefront group gets >= 4 tiles; the
+  // split heuristic (fb_api) then asks for one such workgroup per CU.
+  // Small blocks (the paper's 4- and 8-token blocks: G*Bq <= 32 or 64 rows per KV group) would
+  // leave three of the four row groups of a workgroup computing padding rows; there the
+  // wavefronts share one or two 32-row groups and split the output columns instead.
+  // (row pair + two tiles ahead, VAR = 3, measured: 0.6 % faster with 9 spilled registers; not used)
+  if (dense_row_pairs(p.G * p.Bq, D)) return {1, 2, 1};
+  const int tiles = (p.nkeys + kKeyTile - 1) / kKeyTile;
+  const bool groups2 = p.nsplit > 1 && tiles >= 8 * p.nsplit;
+  const int nrows = p.G * p.Bq;
+  if (nrows <= 32) return {WSMAX, groups2 ? 2 : 1, 0};
+  if (nrows <= 64) return {2, groups2 ? 2 : 1, 0};
+  // long streams (>= 48 tiles per workgroup): tiles fetched two ahead; measured 4-6 % faster at 64 tiles
+  // per workgroup (128K prefix), neutral at 32, and 1 us slower at 16 (32K prefix: longer start-up)
+  if (groups2) return {1, 2, tiles >= 48 * p.nsplit ? 2 : 0};
+  return {1, 1, 0};
+}
+
 template <int D>
 hipError_t launch_d(const PassParams& p, PassMode mode, hipStream_t s) {
   constexpr int WSMAX = (D / 32 >= 4) ? 4 : 2;
   switch (mode) {
     case kPassDense: {
-      // 8-wave workgroups for split-KV streaming when every wavefront group gets >= 4 tiles; the
-      // split heuristic (fb_api) then asks for one such workgroup per CU.
-      // Small blocks (the paper's 4- and 8-token blocks: G*Bq <= 32 or 64 rows per KV group) would
-      // leave three of the four row groups of a workgroup computing padding rows; there the
-      // wavefronts share one or two 32-row groups and split the output columns instead.
-      // (row pair + two tiles ahead, VAR = 3, measured: 0.6 % faster with 9 spilled registers; not used)
-      if (dense_row_pairs(p.G * p.Bq, D)) return launch_one<D, kPassDense, kKeyTile, 1, 2, 1>(p, s);
-      const int tiles = (p.nkeys + kKeyTile - 1) / kKeyTile;
-      const bool groups2 = p.nsplit > 1 && tiles >= 8 * p.nsplit;
-      const int nrows = p.G * p.Bq;
-      if (nrows <= 32) {
-        if (groups2) return launch_one<D, kPassDense, kKeyTile, WSMAX, 2>(p, s);
+      const DenseVariant v = dense_variant<D>(p);
+      if (v.var == 1) return launch_one<D, kPassDense, kKeyTile, 1, 2, 1>(p, s);
+      if (v.ws == WSMAX && WSMAX > 2) {
+        if (v.ng == 2) return launch_one<D, kPassDense, kKeyTile, WSMAX, 2>(p, s);
         return launch_one<D, kPassDense, kKeyTile, WSMAX, 1>(p, s);
       }
-      if (nrows <= 64) {
-        if (groups2) return launch_one<D, kPassDense, kKeyTile, 2, 2>(p, s);
+      if (v.ws == 2) {
+        if (v.ng == 2) return launch_one<D, kPassDense, kKeyTile, 2, 2>(p, s);
         return launch_one<D, kPassDense, kKeyTile, 2, 1>(p, s);
       }
-      if (groups2) {
-        // long streams (>= 48 tiles per workgroup): tiles fetched two ahead; measured 4-6 % faster at 64 tiles
-        // per workgroup (128K prefix), neutral at 32, and 1 us slower at 16 (32K prefix: longer start-up)
-        if (tiles >= 48 * p.nsplit) return launch_one<D, kPassDense, kKeyTile, 1, 2, 2>(p, s);
+      if (v.ng == 2) {
+        if (v.var == 2) return launch_one<D, kPassDense, kKeyTile, 1, 2, 2>(p, s);
         return launch_one<D, kPassDense, kKeyTile, 1, 2>(p, s);
       }
       return launch_one<D, kPassDense, kKeyTile, 1, 1>(p, s);
@@ -1010,6 +1028,12 @@ hipError_t launch_block_mass_bf16(const MassParams& p, int D, hipStream_t s) {
   if (D == 64) hipLaunchKernelGGL(block_mass_bf16_kernel<64>, grid, dim3(256), 0, s, p);
   else hipLaunchKernelGGL(block_mass_bf16_kernel<128>, grid, dim3(256), 0, s, p);
   return hipGetLastError();
+}
+
+int attn_bf16_dense_name(const PassParams& p, int D, char* buf, size_t n) {
+  if (stream_bf16_covers(p, D, kPassDense)) return stream_bf16_name(p, D, kPassDense, buf, n);
+  const DenseVariant v = D == 64 ? dense_variant<64>(p) : dense_variant<128>(p);
+  return snprintf(buf, n, "attn_bf16_kernel<%d, %d, %d, %d, %d, %d>", D, (int)kPassDense, kKeyTile, v.ws, v.ng, v.var);
 }
 
 hipError_t launch_attn_bf16(const PassParams& p, int D, PassMode mode, hipStream_t s) {

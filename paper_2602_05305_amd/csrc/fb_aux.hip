@@ -861,22 +861,13 @@ hipError_t launch_pool_keys(const PoolParams& p, hipStream_t s) {
   return hipGetLastError();
 }
 
-// Dynamic LDS above the 64 KiB default needs the per-kernel limit raised once.
-template <typename K>
-hipError_t ensure_lds(K kern, size_t bytes, bool& done) {
-  if (bytes <= 48 * 1024 || done) return hipSuccess;
-  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 2048);
-  if (e == hipSuccess) done = true;
-  return e;
-}
-
 hipError_t launch_refresh_fold(const CombineParams& p, hipStream_t s) {
   if (p.rows == 0) return hipSuccess;
   if (p.Bq > kMaxInlineBlock || p.Bq % kFoldRows != 0 || p.blk_q == nullptr || p.nsplit < 1) return hipErrorInvalidValue;
   const size_t lds = ((size_t)2 * p.Bq * (p.D + 4) + kFoldRows * p.D + kFoldRows * (p.D + 4)) * sizeof(float) +
                      (size_t)kFoldRows * 256 * sizeof(Folded);
-  static bool raised64 = false, raised128 = false;
-  hipError_t e = p.D == 64 ? ensure_lds(refresh_fold_kernel<64>, lds, raised64) : ensure_lds(refresh_fold_kernel<128>, lds, raised128);
+  static LdsLimit lim64, lim128;
+  hipError_t e = p.D == 64 ? raise_lds_limit(refresh_fold_kernel<64>, lds, lim64, kLdsLimitMax) : raise_lds_limit(refresh_fold_kernel<128>, lds, lim128, kLdsLimitMax);
   if (e != hipSuccess) return e;
   const dim3 grid((unsigned)(p.rows / kFoldRows));
   if (p.D == 64) hipLaunchKernelGGL(refresh_fold_kernel<64>, grid, dim3(256), lds, s, p);
@@ -885,9 +876,9 @@ hipError_t launch_refresh_fold(const CombineParams& p, hipStream_t s) {
 }
 
 hipError_t launch_select_topk(const SelectParams& p, hipStream_t s) {
-  static bool raised = false;
+  static LdsLimit lim;
   const size_t lds = (size_t)(p.D + 256 * 8 + 2 * p.nblk) * 4;
-  hipError_t e = ensure_lds(select_topk_kernel, lds, raised);
+  hipError_t e = raise_lds_limit(select_topk_kernel, lds, lim, kLdsLimitMax);
   if (e != hipSuccess) return e;
   if (p.scores_ws != nullptr && p.rowmass == nullptr && p.nblk > 0) {
     // three kernels: mean queries, block scores spread over the whole chip, then the selection proper
@@ -901,9 +892,9 @@ hipError_t launch_select_topk(const SelectParams& p, hipStream_t s) {
 }
 
 hipError_t launch_build_masks(const MaskParams& p, hipStream_t s) {
-  static bool raised = false;
+  static LdsLimit lim;
   const size_t lds = (size_t)p.nblk * 4;
-  hipError_t e = ensure_lds(build_masks_kernel, lds, raised);
+  hipError_t e = raise_lds_limit(build_masks_kernel, lds, lim, kLdsLimitMax);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(build_masks_kernel, dim3(p.B * p.Hkv), dim3(256), lds, s, p);
   return hipGetLastError();

@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace fb {
 
 constexpr int kKeyTile = 64;  // keys per main-loop iteration in every attention kernel
@@ -33,6 +35,31 @@ __host__ __device__ __forceinline__ uint32_t fastdiv(uint32_t n, const FastDiv& 
   const uint64_t t = (((uint64_t)n * f.magic) >> 32) + n;
 #endif
   return (uint32_t)(t >> f.shift);
+}
+
+// Kernels with more than 64 KiB of dynamic LDS need their per-kernel limit raised before the first launch on a
+// device.  One flag word per kernel remembers the devices on which that was done (bit d = device d): the only
+// state the library keeps between calls.  It is an atomic, so concurrent first calls from several host threads are
+// safe (the attribute call is idempotent), and it is per device, so a second GPU gets its own call.
+struct LdsLimit {
+  std::atomic<uint32_t> devices{0};
+};
+
+// bytes: what this launch needs; limit: what to ask for (the kernel's fixed size, or, for kernels whose size
+// varies from call to call, kLdsLimitMax, which leaves room for their small static arrays).
+constexpr size_t kLdsLimitMax = 160 * 1024 - 2048;
+
+template <typename K>
+hipError_t raise_lds_limit(K kern, size_t bytes, LdsLimit& st, size_t limit) {
+  if (bytes <= 48 * 1024) return hipSuccess;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const uint32_t bit = (dev >= 0 && dev < 32) ? (1u << dev) : 0u;
+  if (bit != 0u && (st.devices.load(std::memory_order_acquire) & bit) != 0u) return hipSuccess;
+  e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)limit);
+  if (e == hipSuccess && bit != 0u) st.devices.fetch_or(bit, std::memory_order_release);
+  return e;
 }
 
 // What a pass iterates over and what it emits.
@@ -138,6 +165,9 @@ hipError_t launch_attn_bf16(const PassParams& p, int D, PassMode mode, hipStream
 // Streaming form of the bf16 pass (direct-to-LDS tile ring); covers a subset of (shape, mode) combinations.
 bool stream_bf16_covers(const PassParams& p, int D, PassMode mode);
 hipError_t launch_stream_bf16(const PassParams& p, int D, PassMode mode, hipStream_t s);
+int stream_bf16_name(const PassParams& p, int D, PassMode mode, char* buf, size_t n);
+// Name of the kernel launch_attn_bf16 runs for the dense external pass of p (profiler spelling, no namespace).
+int attn_bf16_dense_name(const PassParams& p, int D, char* buf, size_t n);
 hipError_t launch_combine(const CombineParams& p, hipStream_t s);
 // Fold + block-internal attention + merge in one kernel; needs blk_q/k/v, Bq <= kMaxInlineBlock, Bq % kFoldRows == 0.
 hipError_t launch_refresh_fold(const CombineParams& p, hipStream_t s);

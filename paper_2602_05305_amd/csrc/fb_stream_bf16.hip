@@ -29,6 +29,8 @@
 //   wavefront waits for its own loads of a tile with an explicit s_waitcnt vmcnt(n), then the workgroup
 //   barrier makes the tile visible to all.  The stage refilled after barrier t is the one last read in
 //   iteration t-1, which every wavefront has left by then.
+#include <stdio.h>
+
 #include "fb_kernels.h"
 
 namespace fb {
@@ -733,8 +735,8 @@ template <int D, int MODE, int LAYOUT, bool PIPE>
 hipError_t launch_stream(const PassParams& p, hipStream_t s) {
   using C = SCfg<D, LAYOUT, (MODE == kPassSparseRefresh) ? 2 : 1>;
   auto kern = attn_stream_kernel<D, MODE, LAYOUT, PIPE>;
-  // raising the dynamic-LDS limit is a host-only call; made on every launch so that no process-wide flag is kept
-  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS);
+  static LdsLimit lim;
+  hipError_t e = raise_lds_limit(kern, C::LDS, lim, C::LDS);
   if (e != hipSuccess) return e;
   const int nrows = p.G * p.Bq;
   const int ntile_rows = (nrows + C::ROWS - 1) / C::ROWS;
@@ -789,6 +791,13 @@ bool stream_bf16_covers(const PassParams& p, int D, PassMode mode) {
     }
     default: return false;
   }
+}
+
+// Name of the instantiation launch_stream_bf16 picks, as a kernel trace prints it (without the namespaces).
+int stream_bf16_name(const PassParams& p, int D, PassMode mode, char* buf, size_t n) {
+  const bool rp = (mode == kPassDense && dense_row_pairs(p.G * p.Bq, D)) || mode == kPassInternal;
+  return snprintf(buf, n, "attn_stream_kernel<%d, %d, %d, %s>", D, (int)mode, rp ? (int)kRowPair : (int)kKeySplit,
+                  rp ? "true" : "false");
 }
 
 hipError_t launch_stream_bf16(const PassParams& p, int D, PassMode mode, hipStream_t s) {

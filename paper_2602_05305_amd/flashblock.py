@@ -1,4 +1,5 @@
-"""Thin ctypes binding over libflashblock.so (contract: include/flashblock.h).
+"""Thin ctypes binding over libflashblock.so (contract: include/flashblock.h, measurement hooks:
+include/flashblock_prof.h).
 
 Argument marshalling only: every function here has the name of the C entry point it calls,
 takes torch tensors for device buffers (PyTorch is used for device memory and streams, nothing
@@ -45,6 +46,7 @@ _SIGNATURES = {
     "fb_last_hip_error": (c_char_p, []),
     "fb_check_shape": (c_int, [POINTER(fb_shape)]),
     "fb_external_splits": (c_int32, [POINTER(fb_shape)]),
+    "fb_external_kernel_name": (c_char_p, [POINTER(fb_shape)]),
     "fb_workspace_bytes": (c_size_t, [POINTER(fb_shape), c_int32, c_int32, c_int32]),
     "fb_external_partial": (c_int, [POINTER(fb_shape)] + [c_void_p] * 7 + [c_size_t, c_void_p]),
     "fb_external_partial_ex": (c_int, [POINTER(fb_shape)] + [c_void_p] * 6 + [c_int32, c_void_p, c_size_t, c_void_p]),
@@ -126,6 +128,10 @@ def fb_check_shape(shape: fb_shape) -> int:
 
 def fb_external_splits(shape: fb_shape) -> int:
     return load_library().fb_external_splits(ctypes.byref(shape))
+
+
+def fb_external_kernel_name(shape: fb_shape) -> str:
+    return load_library().fb_external_kernel_name(ctypes.byref(shape)).decode()
 
 
 def fb_workspace_bytes(shape: fb_shape, key_block: int = 0, topk: int = 0, n_splits: int = 0) -> int:

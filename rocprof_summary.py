@@ -1,6 +1,6 @@
 """Condense rocprofv3 CSV output into the short text summaries kept under profiles/.
 
-    python3 -m paper_2602_05305_amd.rocprof_summary <rocprofv3 output dir> [--all-kernels]
+    python3 rocprof_summary.py <rocprofv3 output dir> [--all-kernels]
 
 Reads every *kernel_trace.csv (per-kernel call count and duration statistics) and every
 *counter_collection.csv (per-kernel mean of each counter) found below the directory.  Only this
