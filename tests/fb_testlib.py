@@ -2,6 +2,8 @@
 the C ABI binding, and compare with the numpy float64 oracle."""
 from __future__ import annotations
 
+import os
+
 import numpy as np
 import torch
 
@@ -52,7 +54,24 @@ def tolerances(dtype):
     return (1e-5, 0.0) if dtype == "f32" else (1e-2, 1e-2)
 
 
+# Achieved errors, collected over the session and printed at its end (tests/conftest.py): a precision regression
+# that stays inside the tolerances still shows up as a jump in this table.
+ACHIEVED = {}
+
+
+def _record(kind, dtype, err, mag):
+    key = (kind, dtype)
+    e, m, n = ACHIEVED.get(key, (0.0, 0.0, 0))
+    ACHIEVED[key] = (max(e, err), max(m, mag), n + 1)
+
+
 def assert_close(got, want, dtype, what, lse=False):
+    """|gpu - oracle| within the tolerance of the storage type; returns the achieved max error.
+    Log-normalisers (lse=True) are held to tighter absolute bounds than the general rule:
+      fp32: 1e-5 absolute while |L| <= 16 (every benchmark configuration; the tiny fp32 config has |L| ~ 6);
+            beyond that 1e-5 |L| / 16 (fp32 spacing at |L| = 64 is already 7.6e-6: the large-score stress cases)
+      bf16: the 1e-2 + 1e-2 |L| rule AND 1e-3 absolute: L is computed in fp32 from exact products, so a
+            precision regression must not hide in the relative term."""
     got, want = np.asarray(got, dtype=np.float64), np.asarray(want, dtype=np.float64)
     assert got.shape == want.shape, (what, got.shape, want.shape)
     a, r = tolerances(dtype)
@@ -61,7 +80,9 @@ def assert_close(got, want, dtype, what, lse=False):
     assert not np.isnan(got).any(), f"{what}: NaN"
     g, wv = got[~inf], want[~inf]
     if dtype == "f32" and lse:
-        bound = 1e-5 * np.maximum(1.0, np.abs(wv))     # log-normaliser: relative to its magnitude
+        bound = 1e-5 * np.maximum(1.0, np.abs(wv) / 16.0)
+    elif lse:
+        bound = np.minimum(a + r * np.abs(wv), 1e-3)
     else:
         bound = a + r * np.abs(wv)
     err = np.abs(g - wv)
@@ -69,7 +90,11 @@ def assert_close(got, want, dtype, what, lse=False):
         i = int(np.argmax(err - bound))
         raise AssertionError(f"{what}: |gpu-oracle| = {err.flat[i]:.3e} > {bound.flat[i]:.3e} "
                              f"(max err {err.max():.3e}, {int((err > bound).sum())} of {err.size} elements)")
-    return float(err.max()) if err.size else 0.0
+    emax = float(err.max()) if err.size else 0.0
+    _record("L" if lse else "value", dtype, emax, float(np.abs(wv).max()) if wv.size else 0.0)
+    if os.environ.get("FB_TEST_VERBOSE"):
+        print(f"[err] {what}: max |gpu-oracle| = {emax:.3e}", flush=True)
+    return emax
 
 
 def check_partial(gpu_part, ora_part, dtype, what):

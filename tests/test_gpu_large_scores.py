@@ -1,0 +1,147 @@
+"""bf16 parity with scores spread over many log2 units, so that the kernels' lazily moved running reference
+(it moves only when a tile's maximum exceeds it by more than 8 log2 units) is driven through its interesting
+branches: rescaling of non-zero accumulators in mid-stream, and weights up to 2^8 rounded to bf16 while the
+reference lags.  N(0,1) inputs with an explicit score scale of 0.5 or 1.0 give the scores a standard deviation of
+8 to 16 log2 units at head_dim 64 / 128; planted keys that are multiples of single query rows give those rows a
+score far above everything before them, wherever in the stream the planted key's tile is visited.
+Every kernel variant that streams keys is covered: the streaming (direct-to-LDS) kernel in split, unsplit, per-head,
+sparse refresh / reuse and paged form, the register-staged kernel's column-split, row-pair and two-tiles-ahead
+variants, and the one-call refresh step."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import flashblock_oracle as orc
+from paper_2602_05305_amd import flashblock as fb
+from paper_2602_05305_amd import workloads as wl
+
+import fb_testlib as T
+
+pytestmark = pytest.mark.gpu
+
+
+def _inputs(w, seed, plant=True):
+    Kp, Vp = wl.make_prefix(w, seed)
+    steps = wl.make_block_steps(w, seed)
+    if plant and w.prefix_len >= 512:
+        # key j of KV head kvh := 2 x query row (head kvh*G+g, row g % Bq): that row scores 2 |q|^2 scale there
+        G = w.n_q_heads // w.n_kv_heads
+        Q0 = steps[0][0]
+        for b in range(w.batch):
+            for kvh in range(w.n_kv_heads):
+                for g in range(G):
+                    for frac in (0.12, 0.55, 0.97):
+                        j = min(w.prefix_len - 1, int(frac * w.prefix_len) + 67 * g)
+                        Kp[b, kvh, j] = wl.round_storage(2.0 * Q0[b, kvh * G + g, g % w.block_len], w.dtype)
+    return Kp, Vp, steps
+
+
+def _dense(w, seed, scale, n_splits=0):
+    print(f"[case] large scores {w.name} seed={seed} scale={scale} n_splits={n_splits}", flush=True)
+    Kp, Vp, steps = _inputs(w, seed)
+    ora = orc.run_block_dense(Kp, Vp, steps, w.refresh, scale=scale)
+    gpu = T.run_dense_block_gpu(w, Kp, Vp, steps, n_splits=n_splits, scale=scale)
+    spread = orc.scores(steps[0][0], Kp, scale).std() / np.log(2.0)
+    assert spread >= 5.0, spread        # the inputs do what the test is for
+    for t, (g, o) in enumerate(zip(gpu, ora)):
+        T.assert_close(g["out"], o["out"], w.dtype, f"{w.name} step {t} out")
+        T.assert_close(g["lse"], o["lse"], w.dtype, f"{w.name} step {t} lse", lse=True)
+        T.check_partial(g["ext"], o["ext"], w.dtype, f"{w.name} step {t} ext")
+
+
+def _w(Hq, Hkv, d, P, Bq, S=2, R=2, B=1):
+    return wl.Workload(f"big_{B}_{Hq}_{Hkv}_{d}_{P}_{Bq}", B, Hq, Hkv, d, P, Bq, S, R, "bf16", 1.0)
+
+
+@pytest.mark.parametrize("d,scale", [(128, 1.0), (128, 0.5), (64, 1.0)])
+@pytest.mark.parametrize("n_splits", [1, 4, 0])
+def test_streaming_kernel_split_and_unsplit(d, scale, n_splits):
+    """128 rows per KV group, 65+ tiles: the streaming kernel (key-split layout), one split (final partial written
+    by the kernel), four splits, and the library's choice."""
+    _dense(_w(8, 2, d, 4096 + 37, 32), 11, scale, n_splits)
+
+
+@pytest.mark.parametrize("Hq,Hkv,d,P,Bq,n_splits", [
+    (8, 2, 128, 1024 + 9, 8, 0),      # 32 rows per group: column split over four wavefronts
+    (8, 2, 128, 1536, 16, 2),         # 64 rows per group: column split over two wavefronts
+    (2, 2, 128, 2048 + 5, 300, 0),    # 300 rows per head: row-pair workgroups
+    (2, 2, 64, 3200, 256, 1),         # head_dim 64, 256 rows, 50 tiles per workgroup, unsplit
+    (2, 1, 64, 6400, 130, 2),         # head_dim 64, two wavefront groups, tiles fetched two ahead
+])
+def test_register_staged_variants(Hq, Hkv, d, P, Bq, n_splits):
+    _dense(_w(Hq, Hkv, d, P, Bq), 12, 1.0, n_splits)
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_refresh_step_and_heads(d):
+    """fb_refresh_step (streaming pass + fold kernel) and the per-head refresh on large-score inputs."""
+    scale = 1.0
+    w = _w(8, 2, d, 2048 + 64, 32)
+    print(f"[case] large scores refresh_step {w.name}", flush=True)
+    Kp, Vp, steps = _inputs(w, 13)
+    Q, Kb, Vb = steps[0]
+    shape = T.shape_of(w, scale=scale)
+    q, kb, vb = T.to_dev(Q, "bf16"), T.to_dev(Kb, "bf16"), T.to_dev(Vb, "bf16")
+    kp, vp = T.to_dev(Kp, "bf16"), T.to_dev(Vp, "bf16")
+    ext = T.Partial(w)
+    out = torch.empty_like(q)
+    lse = torch.empty(q.shape[:3], device=T.DEV, dtype=torch.float32)
+    fb.fb_refresh_step(shape, q, kp, vp, kb, vb, ext.o, ext.m, ext.lse, out, lse, T.workspace(shape))
+    torch.cuda.synchronize()
+    ora_ext = orc.partial(Q, Kp, Vp, scale)
+    T.check_partial(ext.numpy(), ora_ext, "bf16", "refresh_step ext")
+    ora_out, ora_lse = orc.merge(ora_ext, orc.partial(Q, Kb, Vb, scale))
+    T.assert_close(out.double().cpu().numpy(), ora_out, "bf16", "refresh_step out")
+    T.assert_close(lse.double().cpu().numpy(), ora_lse, "bf16", "refresh_step lse", lse=True)
+    # per-head refresh of heads 1, 2, 6 with a later query: those heads' rows follow the new query
+    Q2 = steps[1][0]
+    hm = torch.zeros((1, w.n_q_heads), device=T.DEV, dtype=torch.uint8)
+    hm[0, [1, 2, 6]] = 1
+    ns = max(fb.fb_external_heads_splits(shape, 3), 1)
+    fb.fb_external_partial_heads(shape, T.to_dev(Q2, "bf16"), kp, vp, hm, ext.o, ext.m, ext.lse,
+                                 T.workspace(shape, n_splits=ns), 3)
+    torch.cuda.synchronize()
+    new = orc.partial(Q2, Kp, Vp, scale)
+    got = ext.numpy()
+    for hd in range(w.n_q_heads):
+        ref = new if hd in (1, 2, 6) else ora_ext
+        T.check_partial({k: v[:, hd:hd + 1] for k, v in got.items()}, {k: v[:, hd:hd + 1] for k, v in ref.items()},
+                        "bf16", f"heads refresh head {hd}")
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_sparse_refresh_and_reuse(d):
+    """Sparse refresh (two accumulator sets) and reuse passes on large-score inputs, oracle's selection."""
+    scale = 0.5 if d == 128 else 1.0
+    w = _w(8, 2, d, 4096, 32, S=3, R=3).with_(key_block=64, topk=16)
+    print(f"[case] large scores sparse {w.name}", flush=True)
+    Kp, Vp, steps = _inputs(w, 14)
+    idx = orc.select_topk(steps[0][0], Kp, w.key_block, w.topk)
+    gpu = T.run_sparse_block_gpu(w, Kp, Vp, steps, idx_per_refresh={0: idx}, scale=scale)
+    kmask = orc.selection_key_mask(idx, w.prefix_len, w.key_block)
+    res = orc.partial(steps[0][0], Kp, Vp, scale, key_mask=~kmask)
+    T.check_partial(gpu[0]["residual"], res, "bf16", "sparse residual")
+    for t, (Q, Kb, Vb) in enumerate(steps):
+        ext = orc.merge_partials(orc.partial(Q, Kp, Vp, scale, key_mask=kmask), res)
+        T.check_partial(gpu[t]["ext"], ext, "bf16", f"sparse step {t} sel(+)res")
+        out, _ = orc.merge(ext, orc.partial(Q, Kb, Vb, scale))
+        T.assert_close(gpu[t]["out"], out, "bf16", f"sparse step {t} out")
+
+
+def test_paged_large_scores():
+    w = _w(8, 2, 128, 2048, 32, B=3)
+    print(f"[case] large scores paged {w.name}", flush=True)
+    scale = 1.0
+    seqs, pool_k, pool_v, table, lens = wl.make_paged_prefix(w, 15, 128, [2048, 700, 1293])
+    Q = wl.make_block_steps(w, 15, steps=1)[0][0]
+    shape = T.shape_of(w, scale=scale)
+    kv = fb.make_paged_kv(T.to_dev(pool_k, "bf16"), T.to_dev(pool_v, "bf16"),
+                          torch.from_numpy(table).to(T.DEV), torch.from_numpy(lens).to(T.DEV))
+    part = T.Partial(w)
+    ns = fb.fb_paged_splits(shape)
+    fb.fb_external_partial_paged(shape, T.to_dev(Q, "bf16"), kv, part.o, part.m, part.lse, T.workspace(shape, n_splits=ns))
+    torch.cuda.synchronize()
+    got = part.numpy()
+    for b, (Kb_, Vb_) in enumerate(seqs):
+        ora = orc.partial(Q[b:b + 1], Kb_[None], Vb_[None], scale)
+        T.check_partial({k: v[b:b + 1] for k, v in got.items()}, ora, "bf16", f"paged seq {b}")
