@@ -138,6 +138,24 @@ fb_status fb_external_partial_ex(const fb_shape* shape, const void* q, const voi
                                  size_t workspace_bytes, void* hip_stream);
 
 /*
+ * fb_external_partial for callers that cannot allocate device memory at all, not even a workspace: code
+ * running under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * operation, arguments and results as fb_external_partial (library's own split count); the split
+ * partials go through a scratch array built into the library (device memory of
+ * fb_builtin_workspace_bytes() = 20 MiB per GPU, held until the process ends) instead of a caller
+ * workspace.  The call allocates and frees nothing.  Shapes whose fb_workspace_bytes(shape, 0, 0, 0)
+ * exceeds that size are rejected with FB_ERR_WORKSPACE before anything is launched (every batch-1
+ * LLM-shaped configuration up to 128K context fits; batch 4 at 128K and the video shape do not).
+ * All calls on one GPU share the one array: calls that may overlap in time (different streams, or
+ * different threads) race on it and must be ordered by the caller; nothing in it has to be cleared
+ * between calls.  More than 16 GPUs per process: FB_ERR_UNSUPPORTED.
+ */
+size_t fb_builtin_workspace_bytes(void);
+fb_status fb_external_partial_builtin_ws(const fb_shape* shape, const void* q, const void* k_prefix,
+                                         const void* v_prefix, float* o_part, float* m_part,
+                                         float* lse_part, void* hip_stream);
+
+/*
  * Head-wise selective refresh (Section 4.2, "Selective reuse": for video models only heads whose
  * block-external attention is not stable enough across steps are recomputed): fb_external_partial
  * restricted to the query heads with head_mask[b * n_q_heads + h] != 0.  The (o, m, lse) rows of

@@ -5,6 +5,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <atomic>
 #include <string>
 
 #include "../../include/flashblock_prof.h"
@@ -378,6 +379,57 @@ fb_status fb_external_partial(const fb_shape* shape, const void* q, const void* 
                               void* workspace, size_t workspace_bytes, void* hip_stream) {
   return fb_external_partial_ex(shape, q, k_prefix, v_prefix, o_part, m_part, lse_part, 0, workspace,
                                 workspace_bytes, hip_stream);
+}
+
+}  // extern "C"
+
+namespace {
+
+// Scratch memory of fb_external_partial_builtin_ws: the split partials of one call.  One copy per GPU the
+// library runs on, held until the process ends.
+constexpr size_t kBuiltinWsBytes = (size_t)20 * 1024 * 1024;
+static __device__ __align__(256) unsigned char scratch[kBuiltinWsBytes];
+
+constexpr int kMaxDevices = 16;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];   // device address of `scratch` per device, looked up on first use
+
+// The array's name is only a host-side handle: its device address comes from hipGetSymbolAddress, asked once
+// per device with that device current, and that address is what kernels and copies get.
+fb_status builtin_ws(void** out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e);
+  if (dev < 0 || dev >= kMaxDevices) return FB_ERR_UNSUPPORTED;
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (ptr == nullptr) {
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_fail(e);
+    if (ptr == nullptr) return FB_ERR_HIP;
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);   // racing first calls store the same address
+  }
+  *out = ptr;
+  return FB_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t fb_builtin_workspace_bytes(void) { return kBuiltinWsBytes; }
+
+fb_status fb_external_partial_builtin_ws(const fb_shape* shape, const void* q, const void* k_prefix,
+                                         const void* v_prefix, float* o_part, float* m_part, float* lse_part,
+                                         void* hip_stream) {
+  fb_status st = check_shape(shape);
+  if (st != FB_OK) return st;
+  if (fb_workspace_bytes(shape, 0, 0, 0) > kBuiltinWsBytes) return FB_ERR_WORKSPACE;   // too large for the built-in scratch
+  if (!q || !o_part || !m_part || !lse_part) return FB_ERR_NULL;      // host-side checks before any HIP call
+  if (shape->prefix_len > 0 && (!k_prefix || !v_prefix)) return FB_ERR_NULL;
+  void* ws = nullptr;
+  st = builtin_ws(&ws);
+  if (st != FB_OK) return st;
+  return external_partial_impl(shape, q, k_prefix, v_prefix, nullptr, nullptr, false, 0, o_part, m_part, lse_part, 0,
+                               ws, kBuiltinWsBytes, nullptr, nullptr, nullptr, hip_stream);
 }
 
 fb_status fb_head_similarity(const fb_shape* shape, const float* o_a, const float* o_b, float* sim,

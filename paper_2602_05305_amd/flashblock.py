@@ -51,6 +51,8 @@ _SIGNATURES = {
     "fb_external_partial": (c_int, [POINTER(fb_shape)] + [c_void_p] * 7 + [c_size_t, c_void_p]),
     "fb_external_partial_ex": (c_int, [POINTER(fb_shape)] + [c_void_p] * 6 + [c_int32, c_void_p, c_size_t, c_void_p]),
     "fb_external_partial_prof": (c_int, [POINTER(fb_shape)] + [c_void_p] * 6 + [c_int32, c_void_p, c_size_t] + [c_void_p] * 4),
+    "fb_builtin_workspace_bytes": (c_size_t, []),
+    "fb_external_partial_builtin_ws": (c_int, [POINTER(fb_shape)] + [c_void_p] * 7),
     "fb_external_heads_splits": (c_int32, [POINTER(fb_shape), c_int32]),
     "fb_external_partial_heads": (c_int, [POINTER(fb_shape)] + [c_void_p] * 4 + [c_int32] + [c_void_p] * 4
                                   + [c_size_t, c_void_p]),
@@ -160,6 +162,16 @@ def fb_external_partial_prof(shape, q, k_prefix, v_prefix, o_part, m_part, lse_p
                                                  workspace.numel() * workspace.element_size(), ev_begin, ev_attn_end,
                                                  ev_end, _stream(stream))
     _check(st, "fb_external_partial_prof")
+
+
+def fb_builtin_workspace_bytes() -> int:
+    return int(load_library().fb_builtin_workspace_bytes())
+
+
+def fb_external_partial_builtin_ws(shape, q, k_prefix, v_prefix, o_part, m_part, lse_part, stream=None):
+    st = load_library().fb_external_partial_builtin_ws(ctypes.byref(shape), _ptr(q), _ptr(k_prefix), _ptr(v_prefix),
+                                                       _ptr(o_part), _ptr(m_part), _ptr(lse_part), _stream(stream))
+    _check(st, "fb_external_partial_builtin_ws")
 
 
 def fb_external_heads_splits(shape, n_active_heads) -> int:

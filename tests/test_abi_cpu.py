@@ -299,3 +299,16 @@ def test_header_is_plain_c_and_links(tmp_path):
     assert out.returncode == 0, out.stderr
     ver, ok, splits, ws = out.stdout.split()
     assert int(ver) == 100 and int(ok) == fb.FB_OK and int(splits) >= 1 and int(ws) >= 256
+
+
+def test_builtin_workspace_entry_rejects_on_the_host():
+    """The entry point for callers that cannot allocate: size and argument checks come before any HIP call."""
+    assert fb.fb_builtin_workspace_bytes() == 20 * 1024 * 1024
+    lib = fb.load_library()
+    video = fb.make_shape(1, 12, 12, 128, 4680, 37440, "bf16")
+    one = ctypes.c_void_p(16)
+    assert lib.fb_external_partial_builtin_ws(ctypes.byref(video), one, one, one, one, one, one, None) == fb.FB_ERR_WORKSPACE
+    small = fb.make_shape(1, 4, 4, 64, 16, 256, "f32")
+    assert lib.fb_external_partial_builtin_ws(ctypes.byref(small), None, one, one, one, one, one, None) == fb.FB_ERR_NULL
+    bad = fb.make_shape(1, 4, 3, 64, 16, 256, "f32")
+    assert lib.fb_external_partial_builtin_ws(ctypes.byref(bad), one, one, one, one, one, one, None) == fb.FB_ERR_SHAPE
