@@ -15,8 +15,8 @@
 //              residual key blocks); a tile's scores are computed once and go to the set the row's head routes
 //              the tile's key block to, so the eight wavefronts stay evenly loaded whatever the selection.
 //   kRowPair   256 rows, wavefront w owns rows [32 w, +32) and whole tiles (many rows per KV head: a staged
-//              tile serves twice the rows).  PIPE: the score MFMAs of tile t+1 are issued ahead of the softmax
-//              of tile t, so that the matrix pipe has independent work during the exp chain.
+//              tile serves twice the rows).  Run with LATE: the second wavefront of every SIMD defers the value
+//              product of a tile by one iteration, so that the two wavefronts of a SIMD are in different phases.
 //   Per tile and wavefront: S^T = K Q^T on v_mfma_f32_32x32x16_bf16 (A = K rows from LDS, B = Q^T in
 //   registers), in-lane online softmax with a lazily moved reference, O^T += V^T P^T with the lane's own
 //   probabilities as the B operand (register layout reasoning: fb_attn_bf16.hip, which is the same).
@@ -30,6 +30,8 @@
 //   barrier makes the tile visible to all.  The stage refilled after barrier t is the one last read in
 //   iteration t-1, which every wavefront has left by then.
 #include <stdio.h>
+
+#include <type_traits>
 
 #include "fb_kernels.h"
 
@@ -167,16 +169,13 @@ __device__ __forceinline__ void tile_scores(f32x16 (&s)[NKB], const bf16x8 (&qre
   }
 }
 
-// Online softmax update with the tile's scores and value accumulation.
+// Online softmax update with the tile's scores: moves the running reference if needed (rescaling the accumulators),
+// adds the row sums, and leaves the tile's probabilities, rounded to bf16, in pb (B operands of the value product).
 //   s[kb][r] = raw dot product of query row lane%32 with key 32 (kb0 + kb) + 8 (r/4) + 4 h + r%4
-//   vaddr[db] = per-lane byte address (within a stage) of the lane's share of the transposing V read of
-//               column block db, key offset 0; the 4-key groups are reached through immediate offsets
 template <int D, int NKB>
-__device__ __forceinline__ void tile_softmax_pv(WaveAcc<D / 32>& st, f32x16 (&s)[NKB],
-                                                const unsigned char* __restrict__ stage,
-                                                const uint32_t (&vaddr)[D / 32], int kb0, float scale_log2,
-                                                bool lane_on, int nvalid, int h) {
-  constexpr int NDB = D / 32, ROWB = D * 2, OPB = 64 * ROWB;
+__device__ __forceinline__ void tile_softmax(WaveAcc<D / 32>& st, f32x16 (&s)[NKB], bf16x8 (&pb)[2 * NKB], int kb0,
+                                             float scale_log2, bool lane_on, int nvalid, int h) {
+  constexpr int NDB = D / 32;
   if (nvalid < 64) {
     // the empty asm keeps this a real (wavefront-uniform) branch instead of per-score selects on every tile
     asm volatile("" ::: "memory");
@@ -202,7 +201,6 @@ __device__ __forceinline__ void tile_softmax_pv(WaveAcc<D / 32>& st, f32x16 (&s)
   const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
   const float alpha = __builtin_amdgcn_exp2f(st.m - m_use);
   float lsum = 0.f;
-  bf16x8 pb[2 * NKB];
 #pragma unroll
   for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
@@ -220,9 +218,17 @@ __device__ __forceinline__ void tile_softmax_pv(WaveAcc<D / 32>& st, f32x16 (&s)
 #pragma unroll
       for (int r = 0; r < 16; ++r) st.o[db][r] *= alpha;
   }
-  // O^T[db] += V^T P^T over 16-key steps: A operand element e of lane half h is key 16u + 8(e/4) + 4h + e%4 of
-  // the key block, i.e. two transposing reads of 4 consecutive keys each (the lane's own 4h + i/4 row offset
-  // is inside vaddr).
+}
+
+// Value accumulation O^T[db] += V^T P^T over 16-key steps: A operand element e of lane half h is key
+// 16u + 8(e/4) + 4h + e%4 of the key block, i.e. two transposing reads of 4 consecutive keys each.
+//   vaddr[db] = per-lane byte address (within a stage) of the lane's share of the transposing V read of column block
+//               db, key offset 0 (the lane's own 4h + i/4 row offset is inside); the 4-key groups are reached
+//               through immediate offsets
+template <int D, int NKB>
+__device__ __forceinline__ void tile_pv(WaveAcc<D / 32>& st, const bf16x8 (&pb)[2 * NKB],
+                                        const unsigned char* __restrict__ stage, const uint32_t (&vaddr)[D / 32], int kb0) {
+  constexpr int NDB = D / 32, ROWB = D * 2, OPB = 64 * ROWB;
 #pragma unroll
   for (int t = 0; t < 2 * NKB; ++t) {
     const int krow = (kb0 + t / 2) * 32 + 16 * (t % 2);
@@ -241,6 +247,16 @@ __device__ __forceinline__ void tile_softmax_pv(WaveAcc<D / 32>& st, f32x16 (&s)
   }
 }
 
+template <int D, int NKB>
+__device__ __forceinline__ void tile_softmax_pv(WaveAcc<D / 32>& st, f32x16 (&s)[NKB],
+                                                const unsigned char* __restrict__ stage,
+                                                const uint32_t (&vaddr)[D / 32], int kb0, float scale_log2,
+                                                bool lane_on, int nvalid, int h) {
+  bf16x8 pb[2 * NKB];
+  tile_softmax<D, NKB>(st, s, pb, kb0, scale_log2, lane_on, nvalid, h);
+  tile_pv<D, NKB>(st, pb, stage, vaddr, kb0);
+}
+
 // A tile of the stream (all wavefront-uniform).  TileRaw is what the table lookups deliver (fetched one iteration
 // before the tile is issued, with no arithmetic on the loaded words, so that the wait for them falls into the
 // next iteration); TileDesc adds the addresses.
@@ -256,15 +272,21 @@ struct TileDesc {
   const unsigned char* vt;
 };
 
-template <int D, int MODE, int LAYOUT, bool PIPE>
+template <int D, int MODE, int LAYOUT, bool LATE>
 __global__ __launch_bounds__(kStreamThreads, 1) void attn_stream_kernel(const PassParams p) {
   constexpr int NSETS = (MODE == kPassSparseRefresh) ? 2 : 1;
   using C = SCfg<D, LAYOUT, NSETS>;
   static_assert(MODE == kPassDense || MODE == kPassDenseHeads || MODE == kPassDensePaged || MODE == kPassSparseReuse ||
                     MODE == kPassSparseRefresh || MODE == kPassInternal, "modes of the streaming kernel");
   static_assert(MODE != kPassSparseRefresh || LAYOUT == kKeySplit, "two accumulator sets: key-split layout");
-  static_assert(!PIPE || (LAYOUT == kRowPair && (MODE == kPassDense || MODE == kPassInternal)), "pipelined form");
   static_assert(MODE != kPassInternal || LAYOUT == kRowPair, "internal pass: row-pair layout");
+  static_assert(!LATE || NSETS == 1, "deferred value product: one accumulator set");
+  // LATE: the second wavefront of every SIMD (wavefronts 4..7) defers the value product of a tile to the next
+  // iteration, in front of that tile's scores.  The two wavefronts of a SIMD otherwise run the same phases at the
+  // same time (the barrier keeps them in step): matrix phases would queue on the one matrix pipe while it idles
+  // during both softmax phases.  With one of them shifted, one wavefront's softmax runs under the other's MFMAs.
+  // A tile then stays in the ring one iteration longer, so tiles are fetched AHEAD = NS - 2 ahead instead of NS - 1.
+  constexpr int AHEAD = LATE ? C::NS - 2 : C::NS - 1;
   // passes whose tiles come from a table (paged, sparse): the lookups are made one iteration ahead of the tile's
   // issue, and (first key, mask) travel to the tile's compute in a register queue
   extern __shared__ __align__(16) unsigned char ring[];
@@ -461,12 +483,12 @@ __global__ __launch_bounds__(kStreamThreads, 1) void attn_stream_kernel(const Pa
         dma16(qg, (uint32_t)(r * C::ROWB + ck[j] * 16), qbase + part * C::OPB + j * 8192);
       }
   }
-  constexpr int kPre = C::NS - C::QSTAGES;               // tiles that can be issued while the queries sit in the ring
+  constexpr int kPre = (AHEAD < C::NS - C::QSTAGES) ? AHEAD : C::NS - C::QSTAGES;   // tiles issued while the queries sit in the ring
   {
     int pre = 0;
 #pragma unroll
     for (int i = 0; i < kPre; ++i)
-      if (i < ntiles && i < C::NS - 1) {
+      if (i < ntiles) {
         const TileDesc d = tile_desc(tile_raw(i));
         issue_tile(i, d);
         qk0[i] = d.k0;
@@ -484,11 +506,11 @@ __global__ __launch_bounds__(kStreamThreads, 1) void attn_stream_kernel(const Pa
     for (int ks = 0; ks < C::NKS; ++ks)
       qreg[ks] = *(const bf16x8*)(qs + ((2 * ks + h + C::rot_k(r % 64)) & (C::CPR - 1)) * 16);
   }
-  if constexpr (kPre < C::NS - 1) {
+  if constexpr (kPre < AHEAD) {
     // the queries took more than the last stage: the remaining start-up tiles go out once everyone has read them
     __syncthreads();
 #pragma unroll
-    for (int i = kPre; i < C::NS - 1; ++i)
+    for (int i = kPre; i < AHEAD; ++i)
       if (i < ntiles) {
         const TileDesc d = tile_desc(tile_raw(i));
         issue_tile(i, d);
@@ -499,7 +521,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void attn_stream_kernel(const Pa
   // table words of the next tile to be issued, fetched one iteration ahead (lookups off the critical path)
   TileRaw rnext;
   rnext.e = 0; rnext.word = 0; rnext.mask = 0u;
-  if (C::NS - 1 < ntiles) rnext = tile_raw(C::NS - 1);
+  if (AHEAD < ntiles) rnext = tile_raw(AHEAD);
 
   // per-lane LDS read addresses inside a stage
   uint32_t kaddr[C::NKS], vaddr[C::NDB];
@@ -530,15 +552,15 @@ __global__ __launch_bounds__(kStreamThreads, 1) void attn_stream_kernel(const Pa
     else return true;
   };
   constexpr bool kMasked = (MODE == kPassDenseHeads || MODE == kPassSparseReuse || MODE == kPassSparseRefresh);
-  // issue of tile t + NS - 1 (into the stage every wavefront left at the last barrier), then the lookups of the
-  // tile after it; the queue then holds tiles t .. t + NS - 1
+  // issue of tile t + AHEAD (into a stage every wavefront has left for good), then the lookups of the tile after it;
+  // the queue then holds tiles t .. t + AHEAD
   auto refill = [&](int t) {
-    if (t + C::NS - 1 < ntiles) {
+    if (t + AHEAD < ntiles) {
       const TileDesc d = tile_desc(rnext);
-      issue_tile(t + C::NS - 1, d);
-      qk0[C::NS - 1] = d.k0;
-      qmask[C::NS - 1] = d.mask;
-      if (t + C::NS < ntiles) rnext = tile_raw(t + C::NS);
+      issue_tile(t + AHEAD, d);
+      qk0[AHEAD] = d.k0;
+      qmask[AHEAD] = d.mask;
+      if (t + AHEAD + 1 < ntiles) rnext = tile_raw(t + AHEAD + 1);
     }
   };
   auto advance = [&]() {
@@ -549,60 +571,60 @@ __global__ __launch_bounds__(kStreamThreads, 1) void attn_stream_kernel(const Pa
     }
   };
 
-  if constexpr (!PIPE) {
-    for (int t = 0; t < ntiles; ++t) {
-      wait_tiles<C::LPT>(min(C::NS - 2, ntiles - 1 - t));     // tiles issued after tile t so far
-      __syncthreads();
-      refill(t);
-      const unsigned char* stage = ring + (t % C::NS) * C::STAGE;
-      const int k0 = qk0[0];
-      const uint32_t mask = qmask[0];
-      advance();
-      const int nvalid = min(C::KT, nkeys - k0);
-      if constexpr (MODE == kPassSparseReuse) {
-        if (nvalid <= 0) continue;                             // a list entry past the end of the keys
-      }
-      bool on[NSETS];
-      bool any_on = false;
+  {
+    // The loop exists in two forms, chosen once per wavefront: value product of a tile right after its softmax, or
+    // (LATE, wavefronts 4..7) deferred to the next iteration.  Both run the same barriers.
+    auto tile_loop = [&](auto late_tag) __attribute__((always_inline)) {
+      constexpr bool kLateLoop = decltype(late_tag)::value;
+      bf16x8 pb_prev[2 * C::NKB];                              // probabilities of the tile whose value product is due
+      const unsigned char* stage_prev = ring;
+      bool have_prev = false;
+      for (int t = 0; t < ntiles; ++t) {
+        wait_tiles<C::LPT>(min(AHEAD - 1, ntiles - 1 - t));    // tiles issued after tile t so far
+        __syncthreads();
+        refill(t);
+        const unsigned char* stage = ring + (t % C::NS) * C::STAGE;
+        const int k0 = qk0[0];
+        const uint32_t mask = qmask[0];
+        advance();
+        if constexpr (kLateLoop) {
+          if (have_prev) {
+            tile_pv<D, C::NKB>(acc, pb_prev, stage_prev, vaddr, kb0);
+            have_prev = false;
+          }
+        }
+        const int nvalid = min(C::KT, nkeys - k0);
+        if constexpr (MODE == kPassSparseReuse) {
+          if (nvalid <= 0) continue;                           // a list entry past the end of the keys
+        }
+        bool on[NSETS];
+        bool any_on = false;
 #pragma unroll
-      for (int i = 0; i < NSETS; ++i) {
-        on[i] = lane_on_of(mask, i);
-        any_on = any_on || on[i];
-      }
-      if (kMasked && !__any(any_on)) continue;
-      f32x16 s[C::NKB];
-      tile_scores<D, C::NKB>(s, qreg, stage, kaddr, kb0);
+        for (int i = 0; i < NSETS; ++i) {
+          on[i] = lane_on_of(mask, i);
+          any_on = any_on || on[i];
+        }
+        if (kMasked && !__any(any_on)) continue;
+        f32x16 s[C::NKB];
+        tile_scores<D, C::NKB>(s, qreg, stage, kaddr, kb0);
+        if constexpr (kLateLoop) {
+          tile_softmax<D, C::NKB>(acc, s, pb_prev, kb0, p.scale_log2, on[0], nvalid, h);
+          stage_prev = stage;
+          have_prev = true;
+        } else {
 #pragma unroll
-      for (int i = 0; i < NSETS; ++i) {
-        if (NSETS > 1 && !__any(on[i])) continue;
-        tile_softmax_pv<D, C::NKB>(accs[i], s, stage, vaddr, kb0, p.scale_log2, on[i], nvalid, h);
+          for (int i = 0; i < NSETS; ++i) {
+            if (NSETS > 1 && !__any(on[i])) continue;
+            tile_softmax_pv<D, C::NKB>(accs[i], s, stage, vaddr, kb0, p.scale_log2, on[i], nvalid, h);
+          }
+        }
       }
-    }
-  } else {
-    // scores of tile t+1 are issued before the softmax of tile t: two score register sets
-    f32x16 s_cur[C::NKB];
-    if (ntiles > 0) {
-      wait_tiles<C::LPT>(min(C::NS - 2, ntiles - 1));
-      __syncthreads();
-      tile_scores<D, C::NKB>(s_cur, qreg, ring, kaddr, kb0);
-    }
-    for (int t = 0; t < ntiles; ++t) {
-      const bool more = t + 1 < ntiles;
-      if (more) wait_tiles<C::LPT>(min(C::NS - 3, ntiles - 2 - t));   // tiles issued after tile t+1 so far
-      __syncthreads();
-      refill(t);
-      const unsigned char* stage = ring + (t % C::NS) * C::STAGE;
-      const int k0 = qk0[0];
-      advance();
-      const int nvalid = min(C::KT, nkeys - k0);
-      f32x16 s_next[C::NKB];
-      if (more) tile_scores<D, C::NKB>(s_next, qreg, ring + ((t + 1) % C::NS) * C::STAGE, kaddr, kb0);
-      tile_softmax_pv<D, C::NKB>(acc, s_cur, stage, vaddr, kb0, p.scale_log2, true, nvalid, h);
-      if (more) {
-#pragma unroll
-        for (int kb = 0; kb < C::NKB; ++kb) s_cur[kb] = s_next[kb];
+      if constexpr (kLateLoop) {
+        if (have_prev) tile_pv<D, C::NKB>(acc, pb_prev, stage_prev, vaddr, kb0);
       }
-    }
+    };
+    if (LATE && wave >= 4) tile_loop(std::true_type{});
+    else tile_loop(std::false_type{});
   }
 
   if constexpr (LAYOUT == kKeySplit) {
@@ -731,10 +753,10 @@ __global__ __launch_bounds__(kStreamThreads, 1) void attn_stream_kernel(const Pa
   }
 }
 
-template <int D, int MODE, int LAYOUT, bool PIPE>
+template <int D, int MODE, int LAYOUT, bool LATE>
 hipError_t launch_stream(const PassParams& p, hipStream_t s) {
   using C = SCfg<D, LAYOUT, (MODE == kPassSparseRefresh) ? 2 : 1>;
-  auto kern = attn_stream_kernel<D, MODE, LAYOUT, PIPE>;
+  auto kern = attn_stream_kernel<D, MODE, LAYOUT, LATE>;
   static LdsLimit lim;
   hipError_t e = raise_lds_limit(kern, C::LDS, lim, C::LDS);
   if (e != hipSuccess) return e;
@@ -777,7 +799,7 @@ bool stream_bf16_covers(const PassParams& p, int D, PassMode mode) {
   const int tiles = (p.nkeys + kKeyTile - 1) / kKeyTile;
   switch (mode) {
     case kPassDense:
-      if (dense_row_pairs(nrows, D)) return false;   // row-pair form: the register-staged kernel is still ahead
+      if (dense_row_pairs(nrows, D)) return tiles >= 8 * p.nsplit;
       return nrows > 64 && nrows <= 128 && tiles >= 8 * p.nsplit;
     case kPassDenseHeads:
     case kPassDensePaged:
@@ -787,7 +809,7 @@ bool stream_bf16_covers(const PassParams& p, int D, PassMode mode) {
     case kPassInternal: {
       // compute-bound internal pass: many rows per KV head and a 256-row workgroup for (almost) every CU
       const long long wgs = (long long)p.B * p.Hkv * ((nrows + 255) / 256);
-      return false && nrows >= 1024 && wgs >= 128 && tiles >= 8;
+      return nrows >= 1024 && wgs >= 128 && tiles >= 8;
     }
     default: return false;
   }
