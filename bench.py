@@ -537,15 +537,14 @@ def sparse_extra(torch, fb, wl):
             "timing": "median (and min) of 30 event-timed calls after 50 ms of the same call"}
 
 
-def paged_setup(torch, fb, wl):
-    """Paged prefix cache with ragged per-sequence lengths (the serving shape): batch 32, prefix
-    lengths uniform in [512, 8192], 256-token pages handed out in random order.  Returns the
-    call closure and a description."""
+def paged_setup(torch, fb, wl, B=32, block_len=32, lo=512, pmax=8192, page=256, seed=5305):
+    """Paged prefix cache with ragged per-sequence lengths (the serving shape): batch B, prefix lengths uniform in
+    [lo, pmax] (one at the maximum), 256-token pages handed out in random order, block of block_len tokens.
+    Returns the call closure and a description."""
     import numpy as np
     base = wl.CONFIGS["llm_32k"]
-    B, pmax, page = 32, 8192, 256
-    rng = np.random.default_rng([2602, 5305])
-    lens = rng.integers(512, pmax + 1, size=B).astype(np.int32)
+    rng = np.random.default_rng([2602, seed])
+    lens = rng.integers(lo, pmax + 1, size=B).astype(np.int32)
     lens[0] = pmax
     need = [-(-int(n) // page) for n in lens]
     npages = sum(need) + 3
@@ -554,14 +553,16 @@ def paged_setup(torch, fb, wl):
     for b in range(B):
         table[b, :need[b]] = order[nxt:nxt + need[b]]
         nxt += need[b]
-    shape = fb.make_shape(B, base.n_q_heads, base.n_kv_heads, base.head_dim, base.block_len, pmax, "bf16")
+    shape = fb.make_shape(B, base.n_q_heads, base.n_kv_heads, base.head_dim, block_len, pmax, "bf16")
     sc = float(base.input_scale)
+    # pools above ~1 GB are not doubled: they exceed the last-level cache several times over on their own
+    npools = 2 if npages * base.n_kv_heads * page * base.head_dim * 4 < (1 << 30) else 1
     pools = [tuple((torch.randn((npages, base.n_kv_heads, page, base.head_dim), device="cuda") * sc).to(torch.bfloat16)
-                   for _ in range(2)) for _ in range(2)]
+                   for _ in range(2)) for _ in range(npools)]
     tbl, ln = torch.from_numpy(table).cuda(), torch.from_numpy(lens).cuda()
     kvs = [fb.make_paged_kv(k, v, tbl, ln) for k, v in pools]
-    q = (torch.randn((B, base.n_q_heads, base.block_len, base.head_dim), device="cuda") * sc).to(torch.bfloat16)
-    rows = (B, base.n_q_heads, base.block_len)
+    q = (torch.randn((B, base.n_q_heads, block_len, base.head_dim), device="cuda") * sc).to(torch.bfloat16)
+    rows = (B, base.n_q_heads, block_len)
     o = torch.empty(rows + (base.head_dim,), device="cuda")
     m, l = torch.empty(rows, device="cuda"), torch.empty(rows, device="cuda")
     ns = fb.fb_paged_splits(shape)
@@ -569,25 +570,43 @@ def paged_setup(torch, fb, wl):
     i = [0]
 
     def call():
-        fb.fb_external_partial_paged(shape, q, kvs[i[0] % 2], o, m, l, ws)
+        fb.fb_external_partial_paged(shape, q, kvs[i[0] % npools], o, m, l, ws)
         i[0] += 1
+    kb = (torch.randn((B, base.n_kv_heads, block_len, base.head_dim), device="cuda") * sc).to(torch.bfloat16)
+    vb = (torch.randn((B, base.n_kv_heads, block_len, base.head_dim), device="cuda") * sc).to(torch.bfloat16)
+    out = torch.empty_like(q)
+
+    def refresh_step():
+        fb.fb_refresh_step_paged(shape, q, kvs[i[0] % npools], kb, vb, o, m, l, out, None, ws)
+        i[0] += 1
+    call.refresh_step = refresh_step
+    call.keep = (pools, tbl, ln, q, o, m, l, ws)        # the closure's buffers live as long as it does
     kv_bytes = int(lens.sum()) * base.n_kv_heads * base.head_dim * 2 * 2
-    info = {"workload": f"paged external pass: batch {B}, prefix lengths uniform 512..{pmax} ({int(lens.sum())} tokens), "
+    info = {"workload": f"paged external pass: batch {B}, prefix lengths uniform {lo}..{pmax} ({int(lens.sum())} tokens), "
                         f"{page}-token pages in random order, {base.n_q_heads} q / {base.n_kv_heads} kv heads, "
-                        f"head_dim {base.head_dim}, block {base.block_len}, bf16",
+                        f"head_dim {base.head_dim}, block {block_len}, bf16",
             "splits": ns, "kv_bytes": kv_bytes}
     return call, info
 
 
-def paged_extra(torch, fb, wl):
+def paged_extra(torch, fb, wl, **kw):
     """Bandwidth of the paged external pass, priced against the K/V bytes of the tokens that exist
     (not of the padded maximum)."""
-    call, info = paged_setup(torch, fb, wl)
+    call, info = paged_setup(torch, fb, wl, **kw)
     t, tmin = _ev_median_us(torch, call)
+    t_step, t_step_min = _ev_median_us(torch, call.refresh_step)
     info.update({"external_call_us": round(t, 1), "external_call_min_us": round(tmin, 1),
                  "GBps_vs_kv_bytes": round(info["kv_bytes"] / t / 1e3, 1),
-                 "frac_of_8TBps": round(info["kv_bytes"] / t / 1e3 / 8000.0, 4)})
+                 "frac_of_8TBps": round(info["kv_bytes"] / t / 1e3 / 8000.0, 4),
+                 "refresh_step_paged_us": round(t_step, 1), "refresh_step_paged_min_us": round(t_step_min, 1)})
+    del call
+    torch.cuda.empty_cache()
     return info
+
+
+# the paper's language-model deployment shape (Section 5 implementation details, Table 1): 128 sequences under one
+# token budget of about 800k tokens, blocks of 4 or 8 tokens
+PAGED_DEPLOY = dict(B=128, lo=512, pmax=12288, page=256)
 
 
 def gamma_calibration(torch, fb, wl, gamma=0.85):
@@ -860,6 +879,8 @@ def main():
                     help="only run N sparse refresh + reuse call pairs of the sparse_64k workload (for rocprofv3)")
     ap.add_argument("--profile-paged", type=int, default=0, metavar="N",
                     help="only run N paged external passes of the batch-32 serving shape (for rocprofv3)")
+    ap.add_argument("--paged-block", type=int, default=0, metavar="BQ",
+                    help="with --profile-paged: the batch-128 deployment shape with blocks of BQ tokens instead of batch 32")
     ap.add_argument("--profile-copy", type=int, default=0, metavar="N",
                     help="only run N launches of the plain copy kernel on 256 MiB (calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -892,7 +913,10 @@ def main():
         print(f"ran {args.profile_copy} copy kernels of {x.numel()} bytes (read {x.numel()} + write {x.numel()} per launch)")
         return
     if args.profile_paged > 0:
-        call, info = paged_setup(torch, fb, wl)
+        if args.paged_block:
+            call, info = paged_setup(torch, fb, wl, block_len=args.paged_block, **PAGED_DEPLOY)
+        else:
+            call, info = paged_setup(torch, fb, wl)
         for _ in range(args.profile_paged):
             call()
         torch.cuda.synchronize()
@@ -1025,6 +1049,8 @@ def main():
         line["sparse_64k"] = sparse_extra(torch, fb, wl)
         torch.cuda.empty_cache()
         line["paged_b32"] = paged_extra(torch, fb, wl)
+        line["paged_b128_block4"] = paged_extra(torch, fb, wl, block_len=4, **PAGED_DEPLOY)
+        line["paged_b128_block8"] = paged_extra(torch, fb, wl, block_len=8, **PAGED_DEPLOY)
         torch.cuda.empty_cache()
 
     if not args.no_extras:

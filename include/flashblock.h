@@ -219,6 +219,20 @@ fb_status fb_external_partial_paged(const fb_shape* shape, const void* q, const 
                                     void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * A whole refresh step on the paged cache: fb_external_partial_paged followed by the step's block-internal
+ * attention and Eq. 8-9 merge (what fb_internal_merge would return), in two launches where the shape allows it:
+ * with one split the paged pass writes the partial itself and the internal pass follows; with several
+ * splits and a block of at most 64 rows (a multiple of 4) one kernel folds the splits, computes the rows'
+ * block-internal attention and merges; otherwise split combine + internal pass (three launches).
+ * Arguments as in fb_external_partial_paged and fb_internal_merge; lse_out may be NULL.  Workspace as for
+ * fb_external_partial_paged.  (Batches above 128 sequences add the sequence-ordering launch.)
+ */
+fb_status fb_refresh_step_paged(const fb_shape* shape, const void* q, const fb_paged_kv* kv,
+                                const void* k_block, const void* v_block, float* o_part, float* m_part,
+                                float* lse_part, void* out, float* lse_out, int32_t n_splits,
+                                void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Cross-step similarity of block-external attention per head (Section 3 / Figure 1, used to
  * calibrate the head-wise reuse threshold of Section 4.2): sim[b,h] = mean over the block's rows
  * of the cosine similarity between the external attention outputs A_out of two partials, e.g.

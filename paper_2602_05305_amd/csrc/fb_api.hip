@@ -265,7 +265,11 @@ fb_status external_partial_impl(const fb_shape* shape, const void* q, const void
                                 const void* v_prefix, const fb_paged_kv* paged, const uint8_t* head_mask,
                                 bool use_head_mask, int n_active_heads, float* o_part, float* m_part, float* lse_part,
                                 int32_t n_splits, void* workspace, size_t workspace_bytes,
-                                void* ev_begin, void* ev_attn_end, void* ev_end, void* hip_stream) {
+                                void* ev_begin, void* ev_attn_end, void* ev_end, void* hip_stream,
+                                fb::CombineParams* fold_out = nullptr) {
+  // fold_out: the caller folds the split partials itself (with a kernel that does more than the plain combine); it
+  // gets the combine's parameters instead of the combine launch.  Left with nsplit = 0 when there was one split
+  // and the attention kernel wrote the final partial itself.
   fb_status st = check_shape(shape);
   if (st != FB_OK) return st;
   if (!q || !o_part || !m_part || !lse_part) return FB_ERR_NULL;
@@ -319,6 +323,7 @@ fb_status external_partial_impl(const fb_shape* shape, const void* q, const void
   if (e != hipSuccess) return hip_fail(e);
   if (ev_attn_end && (e = hipEventRecord((hipEvent_t)ev_attn_end, stream)) != hipSuccess) return hip_fail(e);
 
+  if (fold_out) memset(fold_out, 0, sizeof(*fold_out));
   if (!p.direct) {
     fb::CombineParams c;
     memset(&c, 0, sizeof(c));
@@ -326,8 +331,12 @@ fb_status external_partial_impl(const fb_shape* shape, const void* q, const void
     c.ws_o = p.ws_o; c.ws_m = p.ws_m; c.ws_l = p.ws_l;
     c.o = o_part; c.m = m_part; c.lse = lse_part;
     c.head_on = p.head_on; c.Bq = shape->block_len;
-    e = fb::launch_combine(c, stream);
-    if (e != hipSuccess) return hip_fail(e);
+    if (fold_out) {
+      *fold_out = c;
+    } else {
+      e = fb::launch_combine(c, stream);
+      if (e != hipSuccess) return hip_fail(e);
+    }
   }
   if (ev_end && (e = hipEventRecord((hipEvent_t)ev_end, stream)) != hipSuccess) return hip_fail(e);
   return FB_OK;
@@ -523,6 +532,35 @@ fb_status fb_refresh_step_prof(const fb_shape* shape, const void* q, const void*
   if (e != hipSuccess) return hip_fail(e);
   if (ev_end && (e = hipEventRecord((hipEvent_t)ev_end, stream)) != hipSuccess) return hip_fail(e);
   return FB_OK;
+}
+
+fb_status fb_refresh_step_paged(const fb_shape* shape, const void* q, const fb_paged_kv* kv, const void* k_block,
+                                const void* v_block, float* o_part, float* m_part, float* lse_part, void* out,
+                                float* lse_out, int32_t n_splits, void* workspace, size_t workspace_bytes,
+                                void* hip_stream) {
+  if (!kv) return FB_ERR_NULL;
+  fb_status st = check_shape(shape);
+  if (st != FB_OK) return st;
+  if (!k_block || !v_block || !out) return FB_ERR_NULL;
+  if (!aligned16(k_block) || !aligned16(v_block) || !aligned16(out) || !aligned16(lse_out)) return FB_ERR_ALIGN;
+  // With several splits and a small block the split fold, the block-internal attention and the merge are one
+  // kernel (as in fb_refresh_step); with one split the paged pass writes the partial itself and the internal pass
+  // follows; otherwise combine + internal pass.
+  const bool fold_kernel = shape->block_len <= fb::kMaxInlineBlock && shape->block_len % fb::kFoldRows == 0;
+  fb::CombineParams c;
+  st = external_partial_impl(shape, q, nullptr, nullptr, kv, nullptr, false, 0, o_part, m_part, lse_part, n_splits,
+                             workspace, workspace_bytes, nullptr, nullptr, nullptr, hip_stream, fold_kernel ? &c : nullptr);
+  if (st != FB_OK) return st;
+  if (fold_kernel && c.nsplit > 0) {
+    c.fin_out = out; c.fin_lse = lse_out; c.fin_bf16 = shape->dtype == FB_BF16;
+    c.blk_q = q; c.blk_k = k_block; c.blk_v = v_block;
+    c.Hq = shape->n_q_heads; c.Hkv = shape->n_kv_heads; c.G = shape->n_q_heads / shape->n_kv_heads;
+    c.scale_log2 = eff_scale(shape) * kLog2e;
+    hipError_t e = fb::launch_refresh_fold(c, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return hip_fail(e);
+    return FB_OK;
+  }
+  return fb_internal_merge(shape, q, k_block, v_block, o_part, m_part, lse_part, out, lse_out, hip_stream);
 }
 
 fb_status fb_refresh_step(const fb_shape* shape, const void* q, const void* k_prefix, const void* v_prefix,

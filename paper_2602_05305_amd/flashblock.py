@@ -59,6 +59,8 @@ _SIGNATURES = {
     "fb_paged_splits": (c_int32, [POINTER(fb_shape)]),
     "fb_external_partial_paged": (c_int, [POINTER(fb_shape), c_void_p, POINTER(fb_paged_kv)] + [c_void_p] * 3
                                   + [c_int32, c_void_p, c_size_t, c_void_p]),
+    "fb_refresh_step_paged": (c_int, [POINTER(fb_shape), c_void_p, POINTER(fb_paged_kv)] + [c_void_p] * 7
+                              + [c_int32, c_void_p, c_size_t, c_void_p]),
     "fb_head_similarity": (c_int, [POINTER(fb_shape)] + [c_void_p] * 4),
     "fb_internal_merge": (c_int, [POINTER(fb_shape)] + [c_void_p] * 9),
     "fb_refresh_step": (c_int, [POINTER(fb_shape)] + [c_void_p] * 11 + [c_size_t, c_void_p]),
@@ -189,7 +191,8 @@ def fb_external_partial_heads(shape, q, k_prefix, v_prefix, head_mask, o_part, m
 
 
 def make_paged_kv(k_pool, v_pool, block_table, prefix_lens) -> fb_paged_kv:
-    """k_pool / v_pool: [num_pages, Hkv, page_size, d]; block_table int32 [B, max_pages]; prefix_lens int32 [B]."""
+    """k_pool / v_pool: [num_pages, Hkv, page_size, d]; block_table int32 [B, max_pages]; prefix_lens int32 [B].
+    The struct holds raw device addresses only: the caller keeps the four tensors alive while it is in use."""
     return fb_paged_kv(ctypes.sizeof(fb_paged_kv), k_pool.shape[0], k_pool.shape[2], block_table.shape[1],
                        k_pool.data_ptr(), v_pool.data_ptr(), block_table.data_ptr(), prefix_lens.data_ptr())
 
@@ -203,6 +206,15 @@ def fb_external_partial_paged(shape, q, kv, o_part, m_part, lse_part, workspace,
                                                   _ptr(m_part), _ptr(lse_part), n_splits, _ptr(workspace),
                                                   workspace.numel() * workspace.element_size(), _stream(stream))
     _check(st, "fb_external_partial_paged")
+
+
+def fb_refresh_step_paged(shape, q, kv, k_block, v_block, o_part, m_part, lse_part, out, lse_out, workspace,
+                          n_splits=0, stream=None):
+    st = load_library().fb_refresh_step_paged(ctypes.byref(shape), _ptr(q), ctypes.byref(kv), _ptr(k_block),
+                                              _ptr(v_block), _ptr(o_part), _ptr(m_part), _ptr(lse_part), _ptr(out),
+                                              _ptr(lse_out), n_splits, _ptr(workspace),
+                                              workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(st, "fb_refresh_step_paged")
 
 
 def fb_head_similarity(shape, o_a, o_b, sim, stream=None):

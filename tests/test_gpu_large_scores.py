@@ -135,8 +135,10 @@ def test_paged_large_scores():
     seqs, pool_k, pool_v, table, lens = wl.make_paged_prefix(w, 15, 128, [2048, 700, 1293])
     Q = wl.make_block_steps(w, 15, steps=1)[0][0]
     shape = T.shape_of(w, scale=scale)
-    kv = fb.make_paged_kv(T.to_dev(pool_k, "bf16"), T.to_dev(pool_v, "bf16"),
-                          torch.from_numpy(table).to(T.DEV), torch.from_numpy(lens).to(T.DEV))
+    # the descriptor holds raw device addresses: the tensors behind them stay referenced until the call has run
+    kpool, vpool = T.to_dev(pool_k, "bf16"), T.to_dev(pool_v, "bf16")
+    tbl, ln = torch.from_numpy(table).to(T.DEV), torch.from_numpy(lens).to(T.DEV)
+    kv = fb.make_paged_kv(kpool, vpool, tbl, ln)
     part = T.Partial(w)
     ns = fb.fb_paged_splits(shape)
     fb.fb_external_partial_paged(shape, T.to_dev(Q, "bf16"), kv, part.o, part.m, part.lse, T.workspace(shape, n_splits=ns))

@@ -139,3 +139,67 @@ def test_paged_head_dim_64_and_wide_grouping():
     """head_dim 64 (other tile geometry) and G = 8 with a block that spans two row tiles."""
     _run_paged(_wl("bf16", 3, 8, 1, 64, 1536, 40), seed=45, page_size=128, lens=[1536, 700, 64])
     _run_paged(_wl("f32", 2, 8, 1, 128, 384, 3), seed=46, page_size=64, lens=[384, 65])
+
+
+@pytest.mark.parametrize("block_len", [4, 8])
+def test_paged_deployment_shape_batch128_small_blocks(block_len):
+    """The paper's language-model deployment shape (Section 5 implementation details, Table 1): 128 sequences under
+    one token budget, blocks of 4 or 8 tokens, 32 q / 8 kv heads, d128, 256-token pages, library-chosen split count.
+    Lengths are uniform in [512, 12288] with the extremes planted (maximum, one ragged tile, a single key, empty).
+    The oracle recomputes 24 of the 128 sequences, among them every planted one."""
+    w = wl.Workload(f"paged_b128_blk{block_len}", 128, 32, 8, 128, 12288, block_len, 1, 1, "bf16", 1.0 / np.sqrt(128.0))
+    print(f"[case] {w.name}", flush=True)
+    rng = np.random.default_rng(4200 + block_len)
+    lens = rng.integers(512, 12289, size=128).astype(np.int32)
+    lens[0], lens[7], lens[64], lens[127] = 12288, 37, 1, 0
+    seqs, Kpool, Vpool, table, lens = wl.make_paged_prefix(w, 4200 + block_len, 256, lens)
+    Q = wl.make_block_steps(w, 4200 + block_len, 1)[0][0]
+    shape = T.shape_of(w)
+    # the descriptor holds raw device addresses: the tensors behind them stay referenced until the call has run
+    kpool, vpool = T.to_dev(Kpool, "bf16"), T.to_dev(Vpool, "bf16")
+    tbl, ln = torch.from_numpy(table).to(T.DEV), torch.from_numpy(lens).to(T.DEV)
+    kv = fb.make_paged_kv(kpool, vpool, tbl, ln)
+    del Kpool, Vpool
+    ext = T.Partial(w)
+    fb.fb_external_partial_paged(shape, T.to_dev(Q, "bf16"), kv, ext.o, ext.m, ext.lse,
+                                 T.workspace(shape, n_splits=fb.fb_paged_splits(shape)))
+    torch.cuda.synchronize()
+    got = ext.numpy()
+    check = sorted(set([0, 7, 64, 127] + rng.choice(128, 20, replace=False).tolist()))
+    for b in check:
+        Kb, Vb = seqs[b]
+        ora = (orc.partial(Q[b:b + 1], Kb[None], Vb[None]) if Kb.shape[1] > 0
+               else orc.empty_partial(1, w.n_q_heads, w.block_len, w.head_dim))
+        T.check_partial({k: v[b:b + 1] for k, v in got.items()}, ora, "bf16", f"{w.name} seq {b}")
+
+
+@pytest.mark.parametrize("dtype,B,Hq,Hkv,d,P,Bq,page,lens,n_splits", [
+    ("bf16", 4, 8, 2, 128, 2048, 32, 128, [1617, 64, 0, 1000], 0),     # library split count
+    ("bf16", 3, 8, 2, 128, 4096, 8, 256, [4096, 300, 2222], 4),        # several splits, small block: fold kernel
+    ("bf16", 2, 8, 2, 64, 1024, 16, 64, [1024, 65], 1),                # one split: paged pass writes the partial
+    ("bf16", 2, 4, 4, 128, 1024, 70, 128, [1000, 512], 3),             # block above 64 rows: combine + internal pass
+    ("f32", 3, 4, 2, 64, 576, 8, 64, [200, 0, 513], 2),
+    ("f32", 2, 4, 4, 64, 640, 5, 128, [640, 129], 2),                  # block not a multiple of 4
+])
+def test_paged_refresh_step(dtype, B, Hq, Hkv, d, P, Bq, page, lens, n_splits):
+    """fb_refresh_step_paged: cached partial, output and log-normaliser of a whole refresh step on the paged cache."""
+    w = _wl(dtype, B, Hq, Hkv, d, P, Bq)
+    print(f"[case] paged refresh step {w.name} lens={lens} n_splits={n_splits}", flush=True)
+    seqs, Kpool, Vpool, table, lens = wl.make_paged_prefix(w, 51, page, lens)
+    Q, Kb, Vb = wl.make_block_steps(w, 51, 1)[0]
+    shape = T.shape_of(w)
+    q, kb, vb = T.to_dev(Q, dtype), T.to_dev(Kb, dtype), T.to_dev(Vb, dtype)
+    kpool, vpool = T.to_dev(Kpool, dtype), T.to_dev(Vpool, dtype)
+    tbl, ln = torch.from_numpy(table).to(T.DEV), torch.from_numpy(lens).to(T.DEV)
+    kv = fb.make_paged_kv(kpool, vpool, tbl, ln)
+    ext = T.Partial(w)
+    out = torch.empty_like(q)
+    lse = torch.empty(q.shape[:3], device=T.DEV, dtype=torch.float32)
+    ws = T.workspace(shape, n_splits=n_splits or fb.fb_paged_splits(shape))
+    fb.fb_refresh_step_paged(shape, q, kv, kb, vb, ext.o, ext.m, ext.lse, out, lse, ws, n_splits)
+    torch.cuda.synchronize()
+    ora_ext = _oracle_partial(w, Q, seqs)
+    T.check_partial(ext.numpy(), ora_ext, dtype, f"{w.name} paged refresh ext")
+    ora_out, ora_lse = orc.merge(ora_ext, orc.partial(Q, Kb, Vb))
+    T.assert_close(out.double().cpu().numpy(), ora_out, dtype, f"{w.name} paged refresh out")
+    T.assert_close(lse.double().cpu().numpy(), ora_lse, dtype, f"{w.name} paged refresh lse", lse=True)
