@@ -256,7 +256,7 @@ def profile_external(dev, n_blocks, R, batch=8):
 def read_traffic(workload_name):
     """HBM bytes per launch of the external-pass kernel as measured with rocprofv3 --pmc FETCH_SIZE /
     WRITE_SIZE and recorded (with the commands) in profiles/; None if no such record exists."""
-    tpath = os.path.join(ROOT, "profiles", f"attn_bf16_external_{workload_name}_hbm_traffic.txt")
+    tpath = os.path.join(ROOT, "profiles", f"attn_stream_external_{workload_name}_hbm_traffic.txt")
     if os.path.exists(tpath):
         for ln in open(tpath):
             if ln.startswith("hbm_bytes_per_launch"):
@@ -281,7 +281,7 @@ def roofline_obj(w, prof, traffic=None, fused=False, ceilings=None):
     r = {"bound": "hbm", "kernel": kern,
          "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
          "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": traffic,
-         "traffic_source": ("profiles/attn_bf16_external_%s_hbm_traffic.txt (rocprofv3 FETCH_SIZE / WRITE_SIZE of an "
+         "traffic_source": ("profiles/attn_stream_external_%s_hbm_traffic.txt (rocprofv3 FETCH_SIZE / WRITE_SIZE of an "
                             "earlier run of the same kernel and workload, not measured in this run)" % w.name)
                            if traffic is not None else None,
          "algorithmic_bytes_per_launch": alg, "avg_launch_us": round(us, 2),
