@@ -108,6 +108,9 @@ struct PassParams {
   // dense / heads / paged pass with nsplit == 1: ws_o / ws_m / ws_l are the caller's final (o, m, lse)
   // arrays and the kernel emits natural-log units itself (no combine pass)
   int direct;
+  // streaming bf16 pass: 1 = splits alternate between the even and the odd XCD of a pair and the odd XCDs' splits are a
+  // little shorter (see biased_range)
+  int xcd_bias;
   FastDiv div_rowtiles, div_nsplit, div_hkv;   // bf16 pass: decomposition of the linear workgroup index
   FastDiv div_page;                            // bf16 paged pass: key index -> page slot
 };
@@ -205,6 +208,22 @@ __device__ __forceinline__ TileRange split_range(int total, int nsplit, int spli
   TileRange r;
   r.begin = split * base + min(split, rem);
   r.end = r.begin + base + (split < rem ? 1 : 0);
+  return r;
+}
+
+// Cut of `total` tiles into an even number of pieces in which the even-numbered pieces are 1/64 longer and the
+// odd-numbered ones 1/64 shorter than the mean (weights 65 : 63).  Used with a workgroup mapping that puts the
+// odd-numbered splits on the odd-numbered XCDs: on the MI355X boards measured, the odd XCD of each pair streams
+// about 4 % slower than the even one whichever KV head it reads (finish times of 128K passes per XCD, in-kernel
+// clocks, with the head-to-XCD assignment rotated), and the pass ends with its slowest XCD.  A fixed, deterministic
+// cut, deliberately a little weaker than the measured asymmetry: 128K pass 99.4 -> 97.4 us, batch 4 neutral; on a
+// board without the asymmetry it would cost under 2 %.
+__device__ __forceinline__ TileRange biased_range(int total, int nsplit, int split) {
+  auto cum = [](int s) -> unsigned long long { return 64ull * (unsigned)s + (unsigned long long)(s & 1); };
+  const unsigned long long den = 64ull * (unsigned)nsplit;
+  TileRange r;
+  r.begin = (int)(((unsigned long long)(unsigned)total * cum(split)) / den);
+  r.end = (split + 1 == nsplit) ? total : (int)(((unsigned long long)(unsigned)total * cum(split + 1)) / den);
   return r;
 }
 

@@ -312,6 +312,10 @@ __global__ __launch_bounds__(kStreamThreads, 1) void attn_stream_kernel(const Pa
     const int bid = blockIdx.x, q8 = nwg / 8, r8 = nwg % 8;
     const int xcd = bid % 8, j = bid / 8;
     int w = (xcd < r8 ? xcd * (q8 + 1) : r8 * (q8 + 1) + (xcd - r8) * q8) + j;
+    // biased cut (the host sets it only for one row tile, an even split count and a grid that is a multiple of 8):
+    // the two XCDs of a pair take alternate work items of the pair's contiguous range, so that even-numbered splits
+    // run on even XCDs and odd-numbered ones on odd XCDs
+    if (p.xcd_bias) w = (xcd >> 1) * (2 * q8) + 2 * j + (xcd & 1);
     if constexpr (MODE == kPassDenseHeads) {
       if (p.div_rowtiles.d > 1) w = bid;     // whole heads drop out: deal a head's row tiles over the XCDs
     }
@@ -382,7 +386,8 @@ __global__ __launch_bounds__(kStreamThreads, 1) void attn_stream_kernel(const Pa
   } else {
     total = (nkeys + C::KT - 1) / C::KT;
   }
-  const TileRange tr = (MODE == kPassInternal) ? TileRange{0, total} : split_range(total, p.div_nsplit, split);
+  const TileRange tr = (MODE == kPassInternal) ? TileRange{0, total}
+                       : p.xcd_bias ? biased_range(total, p.nsplit, split) : split_range(total, p.div_nsplit, split);
   const int ntiles = tr.end - tr.begin;
   const uint32_t rsrc = (p.div_rowtiles.d == 1) ? blockIdx.x : unit;
   const int rot = (MODE == kPassInternal || ntiles <= 0) ? 0 : (int)((rsrc * 13u + (rsrc >> 5) * 7u) % (unsigned)ntiles);
@@ -767,6 +772,12 @@ hipError_t launch_stream(const PassParams& p, hipStream_t s) {
   if (nwg >= (1ll << 31)) return hipErrorInvalidValue;
   PassParams q = p;
   if (MODE == kPassDensePaged) q.div_page = make_fastdiv((uint32_t)p.page_size);
+  {
+    // long streams only: below 64 tiles per split a 1/64 bias rounds away
+    const int tiles = (p.nkeys + kKeyTile - 1) / kKeyTile;
+    q.xcd_bias = ((MODE == kPassDense || MODE == kPassSparseRefresh) && ntile_rows == 1 && p.nsplit % 2 == 0 &&
+                  nwg % 8 == 0 && tiles >= 64 * p.nsplit) ? 1 : 0;
+  }
   q.div_rowtiles = make_fastdiv((uint32_t)ntile_rows);
   q.div_nsplit = make_fastdiv((uint32_t)p.nsplit);
   q.div_hkv = make_fastdiv((uint32_t)p.Hkv);
