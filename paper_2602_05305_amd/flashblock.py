@@ -84,6 +84,12 @@ def load_library():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2602_05305_amd.build` "
                                "(there is no CPU fallback)")
+        # PyTorch ships its own copy of the HIP runtime; the library must bind to that same copy (device memory and
+        # streams come from torch), so torch is loaded first: whichever libamdhip64 is in the process first serves both.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         lib = ctypes.CDLL(LIB_PATH)
         for name, (res, args) in _SIGNATURES.items():
             fn = getattr(lib, name)
