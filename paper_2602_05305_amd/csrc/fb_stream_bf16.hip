@@ -15,8 +15,8 @@
 //              residual key blocks); a tile's scores are computed once and go to the set the row's head routes
 //              the tile's key block to, so the eight wavefronts stay evenly loaded whatever the selection.
 //   kRowPair   256 rows, wavefront w owns rows [32 w, +32) and whole tiles (many rows per KV head: a staged
-//              tile serves twice the rows).  Run with LATE: the second wavefront of every SIMD defers the value
-//              product of a tile by one iteration, so that the two wavefronts of a SIMD are in different phases.
+//              tile serves twice the rows).  Two tiles per barrier: inside an iteration the two wavefronts of a SIMD
+//              are free to drift apart by a tile, so that one's softmax can run under the other's MFMAs.
 //   Per tile and wavefront: S^T = K Q^T on v_mfma_f32_32x32x16_bf16 (A = K rows from LDS, B = Q^T in
 //   registers), in-lane online softmax with a lazily moved reference, O^T += V^T P^T with the lane's own
 //   probabilities as the B operand (register layout reasoning: fb_attn_bf16.hip, which is the same).
@@ -30,8 +30,6 @@
 //   barrier makes the tile visible to all.  The stage refilled after barrier t is the one last read in
 //   iteration t-1, which every wavefront has left by then.
 #include <stdio.h>
-
-#include <type_traits>
 
 #include "fb_kernels.h"
 
@@ -272,7 +270,7 @@ struct TileDesc {
   const unsigned char* vt;
 };
 
-template <int D, int MODE, int LAYOUT, bool LATE>
+template <int D, int MODE, int LAYOUT>
 __global__ __launch_bounds__(kStreamThreads, 1) void attn_stream_kernel(const PassParams p) {
   constexpr int NSETS = (MODE == kPassSparseRefresh) ? 2 : 1;
   using C = SCfg<D, LAYOUT, NSETS>;
@@ -280,15 +278,14 @@ __global__ __launch_bounds__(kStreamThreads, 1) void attn_stream_kernel(const Pa
                     MODE == kPassSparseRefresh || MODE == kPassInternal, "modes of the streaming kernel");
   static_assert(MODE != kPassSparseRefresh || LAYOUT == kKeySplit, "two accumulator sets: key-split layout");
   static_assert(MODE != kPassInternal || LAYOUT == kRowPair, "internal pass: row-pair layout");
-  static_assert(!LATE || NSETS == 1, "deferred value product: one accumulator set");
-  // LATE: the second wavefront of every SIMD (wavefronts 4..7) defers the value product of a tile to the next
-  // iteration, in front of that tile's scores.  The two wavefronts of a SIMD otherwise run the same phases at the
-  // same time (the barrier keeps them in step): matrix phases would queue on the one matrix pipe while it idles
-  // during both softmax phases.  With one of them shifted, one wavefront's softmax runs under the other's MFMAs.
-  // A tile then stays in the ring one iteration longer, so tiles are fetched AHEAD = NS - 2 ahead instead of NS - 1.
-  constexpr int AHEAD = LATE ? C::NS - 2 : C::NS - 1;
+  // Row-pair layout: two tiles per barrier (tiles t, t+1 are computed while t+2, t+3 are in flight), measured 2 % faster
+  // at the video shape than one tile per barrier; every other layout: one tile per barrier, NS - 1 tiles in flight.
+  constexpr bool kPairs = LAYOUT == kRowPair;
+  constexpr int AHEAD = kPairs ? C::NS - 2 : C::NS - 1;
+  static_assert(!kPairs || (C::NS == 4 || C::NS == 6), "pairs of tiles: an even number of stages");
   // passes whose tiles come from a table (paged, sparse): the lookups are made one iteration ahead of the tile's
   // issue, and (first key, mask) travel to the tile's compute in a register queue
+  constexpr bool kListed = (MODE == kPassDensePaged || MODE == kPassSparseReuse || MODE == kPassSparseRefresh);
   extern __shared__ __align__(16) unsigned char ring[];
   const int lane = threadIdx.x & 63, l32 = lane & 31, h = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));     // wavefront-uniform (scalar)
@@ -576,60 +573,61 @@ __global__ __launch_bounds__(kStreamThreads, 1) void attn_stream_kernel(const Pa
     }
   };
 
-  {
-    // The loop exists in two forms, chosen once per wavefront: value product of a tile right after its softmax, or
-    // (LATE, wavefronts 4..7) deferred to the next iteration.  Both run the same barriers.
-    auto tile_loop = [&](auto late_tag) __attribute__((always_inline)) {
-      constexpr bool kLateLoop = decltype(late_tag)::value;
-      bf16x8 pb_prev[2 * C::NKB];                              // probabilities of the tile whose value product is due
-      const unsigned char* stage_prev = ring;
-      bool have_prev = false;
-      for (int t = 0; t < ntiles; ++t) {
-        wait_tiles<C::LPT>(min(AHEAD - 1, ntiles - 1 - t));    // tiles issued after tile t so far
-        __syncthreads();
-        refill(t);
-        const unsigned char* stage = ring + (t % C::NS) * C::STAGE;
-        const int k0 = qk0[0];
-        const uint32_t mask = qmask[0];
-        advance();
-        if constexpr (kLateLoop) {
-          if (have_prev) {
-            tile_pv<D, C::NKB>(acc, pb_prev, stage_prev, vaddr, kb0);
-            have_prev = false;
-          }
-        }
-        const int nvalid = min(C::KT, nkeys - k0);
-        if constexpr (MODE == kPassSparseReuse) {
-          if (nvalid <= 0) continue;                           // a list entry past the end of the keys
-        }
-        bool on[NSETS];
-        bool any_on = false;
+  if constexpr (kPairs) {
+    // two tiles per barrier; the prologue put tiles 0 .. AHEAD-1 in flight, iteration t adds tiles t+AHEAD, t+AHEAD+1
+    // into the stages of tiles t-2, t-1 (or the query stages), which every wavefront left before this barrier
+    static_assert(!kListed, "row-pair layout: dense passes only");
+    for (int t = 0; t < ntiles; t += 2) {
+      wait_tiles<C::LPT>(min(AHEAD - 2, max(ntiles - 2 - t, 0)));   // tiles issued after tile t+1 so far
+      __syncthreads();
 #pragma unroll
-        for (int i = 0; i < NSETS; ++i) {
-          on[i] = lane_on_of(mask, i);
-          any_on = any_on || on[i];
+      for (int u = 0; u < 2; ++u)
+        if (t + AHEAD + u < ntiles) {
+          const TileDesc d = tile_desc(tile_raw(t + AHEAD + u));
+          issue_tile(t + AHEAD + u, d);
+          qk0[AHEAD + u] = d.k0;
         }
-        if (kMasked && !__any(any_on)) continue;
-        f32x16 s[C::NKB];
-        tile_scores<D, C::NKB>(s, qreg, stage, kaddr, kb0);
-        if constexpr (kLateLoop) {
-          tile_softmax<D, C::NKB>(acc, s, pb_prev, kb0, p.scale_log2, on[0], nvalid, h);
-          stage_prev = stage;
-          have_prev = true;
-        } else {
 #pragma unroll
-          for (int i = 0; i < NSETS; ++i) {
-            if (NSETS > 1 && !__any(on[i])) continue;
-            tile_softmax_pv<D, C::NKB>(accs[i], s, stage, vaddr, kb0, p.scale_log2, on[i], nvalid, h);
-          }
+      for (int u = 0; u < 2; ++u)
+        if (t + u < ntiles) {
+          const unsigned char* stage = ring + ((t + u) % C::NS) * C::STAGE;
+          const int nvalid = min(C::KT, nkeys - qk0[u]);
+          f32x16 s[C::NKB];
+          tile_scores<D, C::NKB>(s, qreg, stage, kaddr, kb0);
+          tile_softmax_pv<D, C::NKB>(acc, s, stage, vaddr, kb0, p.scale_log2, true, nvalid, h);
         }
+#pragma unroll
+      for (int i = 0; i + 2 < C::NS; ++i) qk0[i] = qk0[i + 2];
+    }
+  } else {
+    for (int t = 0; t < ntiles; ++t) {
+      wait_tiles<C::LPT>(min(AHEAD - 1, ntiles - 1 - t));      // tiles issued after tile t so far
+      __syncthreads();
+      refill(t);
+      const unsigned char* stage = ring + (t % C::NS) * C::STAGE;
+      const int k0 = qk0[0];
+      const uint32_t mask = qmask[0];
+      advance();
+      const int nvalid = min(C::KT, nkeys - k0);
+      if constexpr (MODE == kPassSparseReuse) {
+        if (nvalid <= 0) continue;                             // a list entry past the end of the keys
       }
-      if constexpr (kLateLoop) {
-        if (have_prev) tile_pv<D, C::NKB>(acc, pb_prev, stage_prev, vaddr, kb0);
+      bool on[NSETS];
+      bool any_on = false;
+#pragma unroll
+      for (int i = 0; i < NSETS; ++i) {
+        on[i] = lane_on_of(mask, i);
+        any_on = any_on || on[i];
       }
-    };
-    if (LATE && wave >= 4) tile_loop(std::true_type{});
-    else tile_loop(std::false_type{});
+      if (kMasked && !__any(any_on)) continue;
+      f32x16 s[C::NKB];
+      tile_scores<D, C::NKB>(s, qreg, stage, kaddr, kb0);
+#pragma unroll
+      for (int i = 0; i < NSETS; ++i) {
+        if (NSETS > 1 && !__any(on[i])) continue;
+        tile_softmax_pv<D, C::NKB>(accs[i], s, stage, vaddr, kb0, p.scale_log2, on[i], nvalid, h);
+      }
+    }
   }
 
   if constexpr (LAYOUT == kKeySplit) {
@@ -758,10 +756,10 @@ __global__ __launch_bounds__(kStreamThreads, 1) void attn_stream_kernel(const Pa
   }
 }
 
-template <int D, int MODE, int LAYOUT, bool LATE>
+template <int D, int MODE, int LAYOUT>
 hipError_t launch_stream(const PassParams& p, hipStream_t s) {
   using C = SCfg<D, LAYOUT, (MODE == kPassSparseRefresh) ? 2 : 1>;
-  auto kern = attn_stream_kernel<D, MODE, LAYOUT, LATE>;
+  auto kern = attn_stream_kernel<D, MODE, LAYOUT>;
   static LdsLimit lim;
   hipError_t e = raise_lds_limit(kern, C::LDS, lim, C::LDS);
   if (e != hipSuccess) return e;
@@ -790,13 +788,13 @@ hipError_t launch_stream_d(const PassParams& p, PassMode mode, hipStream_t s) {
   const int nrows = p.G * p.Bq;
   switch (mode) {
     case kPassDense:
-      if (dense_row_pairs(nrows, D)) return launch_stream<D, kPassDense, kRowPair, true>(p, s);
-      return launch_stream<D, kPassDense, kKeySplit, false>(p, s);
-    case kPassDenseHeads: return launch_stream<D, kPassDenseHeads, kKeySplit, false>(p, s);
-    case kPassDensePaged: return launch_stream<D, kPassDensePaged, kKeySplit, false>(p, s);
-    case kPassSparseReuse: return launch_stream<D, kPassSparseReuse, kKeySplit, false>(p, s);
-    case kPassSparseRefresh: return launch_stream<D, kPassSparseRefresh, kKeySplit, false>(p, s);
-    case kPassInternal: return launch_stream<D, kPassInternal, kRowPair, true>(p, s);
+      if (dense_row_pairs(nrows, D)) return launch_stream<D, kPassDense, kRowPair>(p, s);
+      return launch_stream<D, kPassDense, kKeySplit>(p, s);
+    case kPassDenseHeads: return launch_stream<D, kPassDenseHeads, kKeySplit>(p, s);
+    case kPassDensePaged: return launch_stream<D, kPassDensePaged, kKeySplit>(p, s);
+    case kPassSparseReuse: return launch_stream<D, kPassSparseReuse, kKeySplit>(p, s);
+    case kPassSparseRefresh: return launch_stream<D, kPassSparseRefresh, kKeySplit>(p, s);
+    case kPassInternal: return launch_stream<D, kPassInternal, kRowPair>(p, s);
     default: return hipErrorInvalidValue;
   }
 }
@@ -829,8 +827,7 @@ bool stream_bf16_covers(const PassParams& p, int D, PassMode mode) {
 // Name of the instantiation launch_stream_bf16 picks, as a kernel trace prints it (without the namespaces).
 int stream_bf16_name(const PassParams& p, int D, PassMode mode, char* buf, size_t n) {
   const bool rp = (mode == kPassDense && dense_row_pairs(p.G * p.Bq, D)) || mode == kPassInternal;
-  return snprintf(buf, n, "attn_stream_kernel<%d, %d, %d, %s>", D, (int)mode, rp ? (int)kRowPair : (int)kKeySplit,
-                  rp ? "true" : "false");
+  return snprintf(buf, n, "attn_stream_kernel<%d, %d, %d>", D, (int)mode, rp ? (int)kRowPair : (int)kKeySplit);
 }
 
 hipError_t launch_stream_bf16(const PassParams& p, int D, PassMode mode, hipStream_t s) {
