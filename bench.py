@@ -223,6 +223,20 @@ def profile_external(dev, n_blocks, R, batch=8):
         torch.cuda.synchronize()
     pool = [[hev.create() for _ in range(3)] for _ in range(batch)]
     attn, comb, refresh, reuse = [], [], [], []
+    # pass 1: only the library's three events around the kernels of the refresh step (nothing else is recorded, so
+    # that no other marker sits next to the kernel being timed); pass 2: events around every step
+    left = n_blocks
+    while left > 0:
+        nb = min(batch, left)
+        for i in range(nb):
+            for t in range(S):
+                dev.step(t, blk % dev.nsets, R, prof=pool[i] if t == 0 else None)
+            blk += 1
+        torch.cuda.synchronize()
+        for i in range(nb):
+            attn.append(hev.elapsed_ms(pool[i][0], pool[i][1]) * 1e3)
+            comb.append(hev.elapsed_ms(pool[i][1], pool[i][2]) * 1e3)
+        left -= nb
     left = n_blocks
     while left > 0:
         nb = min(batch, left)
@@ -231,14 +245,12 @@ def profile_external(dev, n_blocks, R, batch=8):
             sev = [torch.cuda.Event(enable_timing=True) for _ in range(S + 1)]
             sev[0].record()
             for t in range(S):
-                dev.step(t, blk % dev.nsets, R, prof=pool[i] if t == 0 else None)
+                dev.step(t, blk % dev.nsets, R)
                 sev[t + 1].record()
             step_evs.append(sev)
             blk += 1
         torch.cuda.synchronize()
         for i in range(nb):
-            attn.append(hev.elapsed_ms(pool[i][0], pool[i][1]) * 1e3)
-            comb.append(hev.elapsed_ms(pool[i][1], pool[i][2]) * 1e3)
             for t in range(S):
                 (refresh if t % R == 0 else reuse).append(step_evs[i][t].elapsed_time(step_evs[i][t + 1]) * 1e3)
         left -= nb

@@ -14,10 +14,12 @@
 extern "C" {
 #endif
 
-/* fb_external_partial_ex that also records three caller-created HIP events
- * (hipEvent_t cast to void*, created with timing enabled) on hip_stream: ev_begin before the
- * streaming attention kernel, ev_attn_end between it and the split combine, ev_end after the
- * combine.  Any of the three may be NULL.  Results are identical to fb_external_partial_ex. */
+/* fb_external_partial_ex that also fills three caller-created HIP events (hipEvent_t cast to void*,
+ * created with timing enabled) on hip_stream.  For bf16 shapes ev_begin and ev_attn_end are the
+ * streaming attention kernel's own start and stop events (the launch carries them: they hold the
+ * timestamps of the kernel's dispatch, the duration a profiler's kernel trace reports); for fp32
+ * shapes they are recorded immediately before and after that launch.  ev_end is recorded after the
+ * split combine.  Any of the three may be NULL.  Results are identical to fb_external_partial_ex. */
 fb_status fb_external_partial_prof(const fb_shape* shape, const void* q, const void* k_prefix,
                                    const void* v_prefix, float* o_part, float* m_part,
                                    float* lse_part, int32_t n_splits, void* workspace,

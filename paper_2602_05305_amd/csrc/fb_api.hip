@@ -197,6 +197,25 @@ hipError_t launch_attn(const fb_shape* s, const fb::PassParams& p, fb::PassMode 
                              : fb::launch_attn_f32(p, s->head_dim, mode, st);
 }
 
+// Attention launch with optional measurement events.  bf16 kernels take them as their own start / stop events
+// (the kernel's dispatch timestamps); where the launch does not (fp32 kernel), they are recorded around it.
+hipError_t timed_attn(const fb_shape* s, const fb::PassParams& p, fb::PassMode mode, hipStream_t st, void* ev_begin,
+                      void* ev_end) {
+  hipError_t e = hipSuccess;
+  const bool in_launch = s->dtype == FB_BF16 && (ev_begin || ev_end);
+  if (in_launch) {
+    fb::tl_kernel_events.start = (hipEvent_t)ev_begin;
+    fb::tl_kernel_events.stop = (hipEvent_t)ev_end;
+  } else if (ev_begin && (e = hipEventRecord((hipEvent_t)ev_begin, st)) != hipSuccess) {
+    return e;
+  }
+  e = launch_attn(s, p, mode, st);
+  fb::tl_kernel_events = fb::KernelEvents{};      // never left behind for an unrelated launch
+  if (e != hipSuccess) return e;
+  if (!in_launch && ev_end) e = hipEventRecord((hipEvent_t)ev_end, st);
+  return e;
+}
+
 }  // namespace
 
 extern "C" {
@@ -318,11 +337,8 @@ fb_status external_partial_impl(const fb_shape* shape, const void* q, const void
     p.direct = 1;
     p.ws_o = o_part; p.ws_m = m_part; p.ws_l = lse_part;
   }
-  hipError_t e = hipSuccess;
-  if (ev_begin && (e = hipEventRecord((hipEvent_t)ev_begin, stream)) != hipSuccess) return hip_fail(e);
-  e = launch_attn(shape, p, mode, stream);
+  hipError_t e = timed_attn(shape, p, mode, stream, ev_begin, ev_attn_end);
   if (e != hipSuccess) return hip_fail(e);
-  if (ev_attn_end && (e = hipEventRecord((hipEvent_t)ev_attn_end, stream)) != hipSuccess) return hip_fail(e);
 
   if (fold_out) memset(fold_out, 0, sizeof(*fold_out));
   if (!p.direct) {
@@ -508,11 +524,8 @@ fb_status fb_refresh_step_prof(const fb_shape* shape, const void* q, const void*
   }
   p.ws_o = (float*)(ws + w.o[0]); p.ws_m = (float*)(ws + w.m[0]); p.ws_l = (float*)(ws + w.l[0]);
   p.ws_o2 = (float*)(ws + w.o[1]); p.ws_m2 = (float*)(ws + w.m[1]); p.ws_l2 = (float*)(ws + w.l[1]);
-  hipError_t e = hipSuccess;
-  if (ev_begin && (e = hipEventRecord((hipEvent_t)ev_begin, stream)) != hipSuccess) return hip_fail(e);
-  e = launch_attn(shape, p, small_block ? fb::kPassDense : fb::kPassRefreshFused, stream);
+  hipError_t e = timed_attn(shape, p, small_block ? fb::kPassDense : fb::kPassRefreshFused, stream, ev_begin, ev_attn_end);
   if (e != hipSuccess) return hip_fail(e);
-  if (ev_attn_end && (e = hipEventRecord((hipEvent_t)ev_attn_end, stream)) != hipSuccess) return hip_fail(e);
 
   fb::CombineParams c;
   memset(&c, 0, sizeof(c));

@@ -914,7 +914,7 @@ hipError_t launch_one(const PassParams& p, hipStream_t s) {
   q.div_rowtiles = make_fastdiv((uint32_t)ntile_rows);
   q.div_nsplit = make_fastdiv((uint32_t)p.nsplit);
   q.div_hkv = make_fastdiv((uint32_t)p.Hkv);
-  hipLaunchKernelGGL(kern, dim3((unsigned)nwg), dim3(256 * NG), lds, s, q);
+  launch_attn_kernel(kern, dim3((unsigned)nwg), dim3(256 * NG), lds, s, q);
   return hipGetLastError();
 }
 

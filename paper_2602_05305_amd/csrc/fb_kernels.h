@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include <atomic>
@@ -60,6 +61,25 @@ hipError_t raise_lds_limit(K kern, size_t bytes, LdsLimit& st, size_t limit) {
   e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)limit);
   if (e == hipSuccess && bit != 0u) st.devices.fetch_or(bit, std::memory_order_release);
   return e;
+}
+
+// Measurement hook (include/flashblock_prof.h): events that the NEXT bf16 attention launch of this host thread is to
+// carry as its own start / stop events (hipExtLaunchKernelGGL: the timestamps of the kernel's dispatch, what a
+// profiler's kernel trace reports, instead of markers recorded around it).  Cleared by the launch that takes them.
+struct KernelEvents {
+  hipEvent_t start = nullptr, stop = nullptr;
+};
+inline thread_local KernelEvents tl_kernel_events;
+
+template <typename K, typename P>
+void launch_attn_kernel(K kern, dim3 grid, dim3 block, size_t lds, hipStream_t s, const P& params) {
+  KernelEvents& ev = tl_kernel_events;
+  if (ev.start != nullptr || ev.stop != nullptr) {
+    hipExtLaunchKernelGGL(kern, grid, block, lds, s, ev.start, ev.stop, 0, params);
+    ev = KernelEvents{};
+  } else {
+    hipLaunchKernelGGL(kern, grid, block, lds, s, params);
+  }
 }
 
 // What a pass iterates over and what it emits.
