@@ -46,30 +46,36 @@ typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
-constexpr int kStreamThreads = 512;
 
 enum StreamLayout : int { kKeySplit = 0, kRowPair = 2 };
 
-template <int D, int LAYOUT, int NSETS = 1>
+// NRG: 32-row groups of a key-split workgroup (4: 128 rows, 8 wavefronts; 2: 64 rows, 4 wavefronts; 1: 32 rows, 2
+// wavefronts: the small blocks of 4- and 8-token diffusion steps, where more row groups would compute padding rows)
+template <int D, int LAYOUT, int NSETS = 1, int NRG = 4>
 struct SCfg {
+  static constexpr int NW = (LAYOUT == kRowPair) ? 8 : 2 * NRG;   // wavefronts per workgroup
+  static constexpr int THREADS = 64 * NW;
   static constexpr int KT = 64;                       // keys per tile
   static constexpr int ROWB = D * 2;                  // bytes per key row
   static constexpr int CPR = ROWB / 16;               // 16-byte chunks per row
   static constexpr int OPB = KT * ROWB;               // bytes per operand (K or V) per tile
   static constexpr int STAGE = 2 * OPB;
-  static constexpr int NLOAD = OPB / (kStreamThreads * 16);   // direct-to-LDS loads per lane, operand and tile
+  static constexpr int NLOAD = OPB / (THREADS * 16);  // direct-to-LDS loads per lane, operand and tile
+  static constexpr int LSTEP = NW * 1024;             // LDS bytes one load of every wavefront covers
   static constexpr int LPT = 2 * NLOAD;               // loads per lane and tile
   static constexpr int NS = (D == 128) ? 4 : 6;       // ring stages
   static constexpr int NKS = D / 16;                  // MFMA k-steps of the score product
   static constexpr int NDB = D / 32;                  // 32-wide output column blocks
-  static constexpr int ROWS = (LAYOUT == kRowPair) ? 256 : 128;
+  static constexpr int ROWS = (LAYOUT == kRowPair) ? 256 : 32 * NRG;
   static constexpr int NKB = (LAYOUT == kKeySplit) ? 1 : 2;    // 32-key blocks of a tile one wavefront computes
-  static constexpr int QSTAGES = ROWS * ROWB / STAGE;          // ring stages the query rows pass through at start
-  static constexpr int MERGE = (LAYOUT == kKeySplit) ? NSETS * 4 * (NDB * 16 + 2) * 64 * 4 : 0;   // key-half hand-over
+  static constexpr int QPARTS = (ROWS + 63) / 64;             // the query rows are loaded 64 at a time, like a K operand
+  static constexpr int QSTAGES = (QPARTS * OPB + STAGE - 1) / STAGE;   // ring stages they pass through at start
+  static constexpr int MERGE = (LAYOUT == kKeySplit) ? NSETS * NRG * (NDB * 16 + 2) * 64 * 4 : 0;   // key-half hand-over
   static constexpr int RING = NS * STAGE;
   static constexpr int FIFO = RING > MERGE ? RING : MERGE;
   static constexpr int LDS = FIFO;
-  static_assert(QSTAGES >= 1 && QSTAGES < NS && ROWS * ROWB == QSTAGES * STAGE, "query rows fill whole stages");
+  static_assert(QSTAGES >= 1 && QSTAGES < NS && NLOAD >= 1, "ring geometry");
+  static_assert((NS - 1) * LPT <= 63, "the loads of NS - 1 tiles in flight must fit the 6-bit load counter");
   // rotation (in chunks) of row `row`
   __device__ static __forceinline__ int rot_k(int row) { return D == 128 ? row : (row >> 1); }
   __device__ static __forceinline__ int rot_v(int row) { return D == 128 ? 4 * row : 4 * (row >> 1); }
@@ -107,13 +113,15 @@ __device__ __forceinline__ void wait_vm() {
 }
 
 // wait until at most `tiles` tiles' worth of this lane's direct-to-LDS loads are outstanding
+// (the counter has 6 bits: counts above 63 cannot be asked for, and no ring here keeps that many loads in flight)
 template <int LPT>
 __device__ __forceinline__ void wait_tiles(int tiles) {
-  if (tiles >= 5) wait_vm<5 * LPT>();
-  else if (tiles == 4) wait_vm<4 * LPT>();
-  else if (tiles == 3) wait_vm<3 * LPT>();
-  else if (tiles == 2) wait_vm<2 * LPT>();
-  else if (tiles == 1) wait_vm<LPT>();
+  constexpr int kMax = 63 / LPT;       // largest tile count the counter can express
+  if (kMax >= 5 && tiles >= 5) wait_vm<(kMax >= 5 ? 5 : 0) * LPT>();
+  else if (kMax >= 4 && tiles >= 4) wait_vm<(kMax >= 4 ? 4 : 0) * LPT>();
+  else if (kMax >= 3 && tiles >= 3) wait_vm<(kMax >= 3 ? 3 : 0) * LPT>();
+  else if (kMax >= 2 && tiles >= 2) wait_vm<(kMax >= 2 ? 2 : 0) * LPT>();
+  else if (kMax >= 1 && tiles >= 1) wait_vm<(kMax >= 1 ? 1 : 0) * LPT>();
   else wait_vm<0>();
 }
 
@@ -270,10 +278,10 @@ struct TileDesc {
   const unsigned char* vt;
 };
 
-template <int D, int MODE, int LAYOUT>
-__global__ __launch_bounds__(kStreamThreads, 1) void attn_stream_kernel(const PassParams p) {
+template <int D, int MODE, int LAYOUT, int NRG>
+__global__ __launch_bounds__(((LAYOUT == kRowPair) ? 8 : 2 * NRG) * 64, 1) void attn_stream_kernel(const PassParams p) {
   constexpr int NSETS = (MODE == kPassSparseRefresh) ? 2 : 1;
-  using C = SCfg<D, LAYOUT, NSETS>;
+  using C = SCfg<D, LAYOUT, NSETS, NRG>;
   static_assert(MODE == kPassDense || MODE == kPassDenseHeads || MODE == kPassDensePaged || MODE == kPassSparseReuse ||
                     MODE == kPassSparseRefresh || MODE == kPassInternal, "modes of the streaming kernel");
   static_assert(MODE != kPassSparseRefresh || LAYOUT == kKeySplit, "two accumulator sets: key-split layout");
@@ -289,8 +297,8 @@ __global__ __launch_bounds__(kStreamThreads, 1) void attn_stream_kernel(const Pa
   extern __shared__ __align__(16) unsigned char ring[];
   const int lane = threadIdx.x & 63, l32 = lane & 31, h = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));     // wavefront-uniform (scalar)
-  const int rg = (LAYOUT == kRowPair) ? wave : (wave & 3);       // 32-row group
-  const int kb0 = (LAYOUT == kKeySplit) ? (wave >> 2) : 0;       // first 32-key block of every tile
+  const int rg = (LAYOUT == kRowPair) ? wave : (wave % NRG);     // 32-row group
+  const int kb0 = (LAYOUT == kKeySplit) ? (wave / NRG) : 0;      // first 32-key block of every tile
 
   // ---- workgroup -> (row tile, batch, KV head, split).  Hardware deals consecutive workgroup ids round-robin
   // to the 8 XCDs; each XCD gets a contiguous range of units so that row tiles sharing K/V share an L2.
@@ -336,9 +344,9 @@ __global__ __launch_bounds__(kStreamThreads, 1) void attn_stream_kernel(const Pa
       // first): lengths to LDS, one rank per thread, the thread whose sequence has rank b publishes it
       int* lens_s = (int*)ring;
       __shared__ int chosen;
-      for (int i = threadIdx.x; i < p.B; i += kStreamThreads) lens_s[i] = p.prefix_lens[i];
+      for (int i = threadIdx.x; i < p.B; i += C::THREADS) lens_s[i] = p.prefix_lens[i];
       __syncthreads();
-      for (int i = threadIdx.x; i < p.B; i += kStreamThreads) {
+      for (int i = threadIdx.x; i < p.B; i += C::THREADS) {
         const int li = lens_s[i];
         int rank = 0;
         for (int j = 0; j < p.B; ++j) {
@@ -437,7 +445,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void attn_stream_kernel(const Pa
   int ck[C::NLOAD], cv[C::NLOAD];
 #pragma unroll
   for (int j = 0; j < C::NLOAD; ++j) {
-    const int pidx = (j * 8 + wave) * 64 + lane;
+    const int pidx = (j * C::NW + wave) * 64 + lane;
     const int r = pidx / C::CPR, pc = pidx % C::CPR;
     ld_row[j] = r;
     ck[j] = (pc - C::rot_k(r)) & (C::CPR - 1);
@@ -455,19 +463,19 @@ __global__ __launch_bounds__(kStreamThreads, 1) void attn_stream_kernel(const Pa
     const int nvalid = nkeys - d.k0;
     if (nvalid >= C::KT) {
 #pragma unroll
-      for (int j = 0; j < C::NLOAD; ++j) dma16(d.kt, off_k[j], sbase + j * 8192);
+      for (int j = 0; j < C::NLOAD; ++j) dma16(d.kt, off_k[j], sbase + j * C::LSTEP);
 #pragma unroll
-      for (int j = 0; j < C::NLOAD; ++j) dma16(d.vt, off_v[j], sbase + C::OPB + j * 8192);
+      for (int j = 0; j < C::NLOAD; ++j) dma16(d.vt, off_v[j], sbase + C::OPB + j * C::LSTEP);
     } else {
       // ragged tile: rows past the end read the last key (in bounds; their scores are masked); an entry past the
       // end of the keys reads one row of the address tile_desc gave it
       const int last = max(nvalid, 1) - 1;
 #pragma unroll
       for (int j = 0; j < C::NLOAD; ++j)
-        dma16(d.kt, (uint32_t)(min(ld_row[j], last) * C::ROWB + ck[j] * 16), sbase + j * 8192);
+        dma16(d.kt, (uint32_t)(min(ld_row[j], last) * C::ROWB + ck[j] * 16), sbase + j * C::LSTEP);
 #pragma unroll
       for (int j = 0; j < C::NLOAD; ++j)
-        dma16(d.vt, (uint32_t)(min(ld_row[j], last) * C::ROWB + cv[j] * 16), sbase + C::OPB + j * 8192);
+        dma16(d.vt, (uint32_t)(min(ld_row[j], last) * C::ROWB + cv[j] * 16), sbase + C::OPB + j * C::LSTEP);
     }
   };
 
@@ -478,11 +486,11 @@ __global__ __launch_bounds__(kStreamThreads, 1) void attn_stream_kernel(const Pa
     const int qvalid = nrows - row0;                     // >= 1
     const uint32_t qbase = ring_base + (uint32_t)(C::NS - C::QSTAGES) * C::STAGE + wave * 1024;
 #pragma unroll
-    for (int part = 0; part < C::ROWS / 64; ++part)      // 64 rows at a time, each laid out like a K operand
+    for (int part = 0; part < C::QPARTS; ++part)         // 64 rows at a time, each laid out like a K operand
 #pragma unroll
       for (int j = 0; j < C::NLOAD; ++j) {
         const int r = min(64 * part + ld_row[j], qvalid - 1);
-        dma16(qg, (uint32_t)(r * C::ROWB + ck[j] * 16), qbase + part * C::OPB + j * 8192);
+        dma16(qg, (uint32_t)(r * C::ROWB + ck[j] * 16), qbase + part * C::OPB + j * C::LSTEP);
       }
   }
   constexpr int kPre = (AHEAD < C::NS - C::QSTAGES) ? AHEAD : C::NS - C::QSTAGES;   // tiles issued while the queries sit in the ring
@@ -636,7 +644,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void attn_stream_kernel(const Pa
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < NSETS; ++i) {
-      float* mbuf = (float*)ring + ((size_t)i * 4 + rg) * REC * 64 + lane;
+      float* mbuf = (float*)ring + ((size_t)i * NRG + rg) * REC * 64 + lane;
       if (kb0 == 1) {
 #pragma unroll
         for (int db = 0; db < C::NDB; ++db)
@@ -650,7 +658,7 @@ __global__ __launch_bounds__(kStreamThreads, 1) void attn_stream_kernel(const Pa
     if (kb0 == 1) return;
 #pragma unroll
     for (int i = 0; i < NSETS; ++i) {
-      const float* mbuf = (const float*)ring + ((size_t)i * 4 + rg) * REC * 64 + lane;
+      const float* mbuf = (const float*)ring + ((size_t)i * NRG + rg) * REC * 64 + lane;
       WaveAcc<C::NDB>& a = accs[i];
       const float m1 = mbuf[(C::NDB * 16) * 64], l1 = mbuf[(C::NDB * 16 + 1) * 64];
       const float M = fmaxf(a.m, m1);
@@ -756,10 +764,10 @@ __global__ __launch_bounds__(kStreamThreads, 1) void attn_stream_kernel(const Pa
   }
 }
 
-template <int D, int MODE, int LAYOUT>
+template <int D, int MODE, int LAYOUT, int NRG = 4>
 hipError_t launch_stream(const PassParams& p, hipStream_t s) {
-  using C = SCfg<D, LAYOUT, (MODE == kPassSparseRefresh) ? 2 : 1>;
-  auto kern = attn_stream_kernel<D, MODE, LAYOUT>;
+  using C = SCfg<D, LAYOUT, (MODE == kPassSparseRefresh) ? 2 : 1, NRG>;
+  auto kern = attn_stream_kernel<D, MODE, LAYOUT, NRG>;
   static LdsLimit lim;
   hipError_t e = raise_lds_limit(kern, C::LDS, lim, C::LDS);
   if (e != hipSuccess) return e;
@@ -779,8 +787,17 @@ hipError_t launch_stream(const PassParams& p, hipStream_t s) {
   q.div_rowtiles = make_fastdiv((uint32_t)ntile_rows);
   q.div_nsplit = make_fastdiv((uint32_t)p.nsplit);
   q.div_hkv = make_fastdiv((uint32_t)p.Hkv);
-  launch_attn_kernel(kern, dim3((unsigned)nwg), dim3(kStreamThreads), C::LDS, s, q);
+  launch_attn_kernel(kern, dim3((unsigned)nwg), dim3(C::THREADS), C::LDS, s, q);
   return hipGetLastError();
+}
+
+// key-split layout with as many 32-row groups per workgroup as the KV group has rows for
+template <int D, int MODE>
+hipError_t launch_key_split(const PassParams& p, hipStream_t s) {
+  const int nrows = p.G * p.Bq;
+  if (nrows <= 32) return launch_stream<D, MODE, kKeySplit, 1>(p, s);
+  if (nrows <= 64) return launch_stream<D, MODE, kKeySplit, 2>(p, s);
+  return launch_stream<D, MODE, kKeySplit, 4>(p, s);
 }
 
 template <int D>
@@ -789,11 +806,11 @@ hipError_t launch_stream_d(const PassParams& p, PassMode mode, hipStream_t s) {
   switch (mode) {
     case kPassDense:
       if (dense_row_pairs(nrows, D)) return launch_stream<D, kPassDense, kRowPair>(p, s);
-      return launch_stream<D, kPassDense, kKeySplit>(p, s);
-    case kPassDenseHeads: return launch_stream<D, kPassDenseHeads, kKeySplit>(p, s);
-    case kPassDensePaged: return launch_stream<D, kPassDensePaged, kKeySplit>(p, s);
-    case kPassSparseReuse: return launch_stream<D, kPassSparseReuse, kKeySplit>(p, s);
-    case kPassSparseRefresh: return launch_stream<D, kPassSparseRefresh, kKeySplit>(p, s);
+      return launch_key_split<D, kPassDense>(p, s);
+    case kPassDenseHeads: return launch_key_split<D, kPassDenseHeads>(p, s);
+    case kPassDensePaged: return launch_key_split<D, kPassDensePaged>(p, s);
+    case kPassSparseReuse: return launch_key_split<D, kPassSparseReuse>(p, s);
+    case kPassSparseRefresh: return launch_key_split<D, kPassSparseRefresh>(p, s);
     case kPassInternal: return launch_stream<D, kPassInternal, kRowPair>(p, s);
     default: return hipErrorInvalidValue;
   }
@@ -801,20 +818,20 @@ hipError_t launch_stream_d(const PassParams& p, PassMode mode, hipStream_t s) {
 
 }  // namespace
 
-// Shapes the streaming kernel takes over from the register-staged one: groups of more than 64 rows whose
-// workgroups stream at least 8 tiles each.
+// Shapes the streaming kernel takes over from the register-staged one: KV groups of up to 128 rows (and the many-row
+// shapes of the row-pair layout) whose workgroups stream at least 8 tiles each.
 bool stream_bf16_covers(const PassParams& p, int D, PassMode mode) {
   const int nrows = p.G * p.Bq;
   const int tiles = (p.nkeys + kKeyTile - 1) / kKeyTile;
   switch (mode) {
     case kPassDense:
       if (dense_row_pairs(nrows, D)) return tiles >= 8 * p.nsplit;
-      return nrows > 64 && nrows <= 128 && tiles >= 8 * p.nsplit;
+      return nrows <= 128 && tiles >= 8 * p.nsplit;
     case kPassDenseHeads:
     case kPassDensePaged:
     case kPassSparseReuse:
     case kPassSparseRefresh:
-      return nrows > 64 && nrows <= 128 && tiles >= 8 * p.nsplit;
+      return nrows <= 128 && tiles >= 8 * p.nsplit;
     case kPassInternal: {
       // compute-bound internal pass: many rows per KV head and a 256-row workgroup for (almost) every CU
       const long long wgs = (long long)p.B * p.Hkv * ((nrows + 255) / 256);
@@ -827,7 +844,9 @@ bool stream_bf16_covers(const PassParams& p, int D, PassMode mode) {
 // Name of the instantiation launch_stream_bf16 picks, as a kernel trace prints it (without the namespaces).
 int stream_bf16_name(const PassParams& p, int D, PassMode mode, char* buf, size_t n) {
   const bool rp = (mode == kPassDense && dense_row_pairs(p.G * p.Bq, D)) || mode == kPassInternal;
-  return snprintf(buf, n, "attn_stream_kernel<%d, %d, %d>", D, (int)mode, rp ? (int)kRowPair : (int)kKeySplit);
+  const int nrows = p.G * p.Bq;
+  return snprintf(buf, n, "attn_stream_kernel<%d, %d, %d, %d>", D, (int)mode, rp ? (int)kRowPair : (int)kKeySplit,
+                  (rp || nrows > 64) ? 4 : nrows > 32 ? 2 : 1);
 }
 
 hipError_t launch_stream_bf16(const PassParams& p, int D, PassMode mode, hipStream_t s) {

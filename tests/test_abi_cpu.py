@@ -315,13 +315,15 @@ def test_builtin_workspace_entry_rejects_on_the_host():
 
 
 def test_external_kernel_name_follows_the_launch_rules():
-    """Host-only query the benchmark labels its roofline with: streaming kernel for 65..128 rows per KV group and at least
-    8 tiles per split, register-staged kernel with its column-split variants for small blocks, fp32 kernel for fp32."""
+    """Host-only query the benchmark labels its roofline with: streaming kernel (with 1, 2 or 4 row groups per workgroup) for up
+    to 128 rows per KV group and at least 8 tiles per split, register-staged kernel for short prefixes, fp32 kernel for fp32."""
     name = lambda *a: fb.fb_external_kernel_name(fb.make_shape(*a))
-    assert name(1, 32, 8, 128, 32, 32768, "bf16") == "attn_stream_kernel<128, 0, 0>"
-    assert name(1, 12, 12, 128, 4680, 37440, "bf16") == "attn_stream_kernel<128, 0, 2>"
-    assert name(1, 32, 8, 128, 8, 4096, "bf16").startswith("attn_bf16_kernel<128, 0, 64, 4, ")
-    assert name(1, 32, 8, 64, 32, 32768, "bf16") == "attn_stream_kernel<64, 0, 0>"
+    assert name(1, 32, 8, 128, 32, 32768, "bf16") == "attn_stream_kernel<128, 0, 0, 4>"       # 128 rows per KV group
+    assert name(1, 32, 8, 128, 16, 32768, "bf16") == "attn_stream_kernel<128, 0, 0, 2>"       # 64 rows
+    assert name(1, 32, 8, 128, 8, 131072, "bf16") == "attn_stream_kernel<128, 0, 0, 1>"       # 32 rows
+    assert name(1, 12, 12, 128, 4680, 37440, "bf16") == "attn_stream_kernel<128, 0, 2, 4>"    # row-pair layout
+    assert name(1, 32, 8, 128, 8, 4096, "bf16").startswith("attn_bf16_kernel<128, 0, 64, 4, ")  # short prefix: register-staged
+    assert name(1, 32, 8, 64, 32, 32768, "bf16") == "attn_stream_kernel<64, 0, 0, 4>"
     assert name(1, 4, 4, 64, 16, 256, "f32") == "attn_f32_kernel<64, 0>"
     bad = fb.make_shape(1, 4, 3, 64, 16, 256, "f32")
     assert fb.fb_external_kernel_name(bad) == ""
