@@ -321,3 +321,61 @@ def test_bf16_long_streams_two_tiles_ahead(d, P, n_splits):
     """Splits of >= 48 tiles run the variant that fetches tiles two ahead with alternating register sets,
     including odd tile counts (the wavefront groups then differ by one tile) and a ragged last tile."""
     _compare_block(_wl("bf16", 1, 8, 2, d, P, 32, S=2, R=2, scale_in=1.0 / np.sqrt(d)), seed=31, n_splits=n_splits)
+
+
+@pytest.mark.parametrize("Hq,Hkv,d,P,Bq,n_splits", [
+    (8, 2, 128, 2048 + 5, 4, 0),      # 16 rows per KV group, library split count
+    (8, 2, 128, 4096, 8, 3),          # 32 rows, three splits (uneven tile ranges)
+    (12, 3, 64, 3000, 16, 2),         # 64 rows, head_dim 64, ragged last tile
+    (4, 4, 128, 1024 + 1, 33, 1),     # G = 1, 33 rows: two row groups with one valid row in the second
+])
+def test_bf16_small_blocks_on_the_streaming_kernel(Hq, Hkv, d, P, Bq, n_splits):
+    """KV groups of at most 64 rows with enough tiles per split for the streaming kernel's 1- and 2-row-group forms."""
+    _compare_block(_wl("bf16", 1, Hq, Hkv, d, P, Bq), seed=21, n_splits=n_splits)
+
+
+def test_bf16_small_block_refresh_step_heads_and_sparse():
+    """The other streaming modes at 32 rows per KV group: one-call refresh step, per-head refresh, sparse refresh / reuse."""
+    w = _wl("bf16", 2, 8, 2, 128, 4096 + 64, 8, S=3, R=3).with_(key_block=64, topk=20)
+    print(f"[case] small block modes {w.name}", flush=True)
+    Kp, Vp = wl.make_prefix(w, 22)
+    steps = wl.make_block_steps(w, 22)
+    Q, Kb, Vb = steps[0]
+    shape = T.shape_of(w)
+    q, kb, vb = T.to_dev(Q, "bf16"), T.to_dev(Kb, "bf16"), T.to_dev(Vb, "bf16")
+    kp, vp = T.to_dev(Kp, "bf16"), T.to_dev(Vp, "bf16")
+    ext = T.Partial(w)
+    out = torch.empty_like(q)
+    lse = torch.empty(q.shape[:3], device=T.DEV, dtype=torch.float32)
+    fb.fb_refresh_step(shape, q, kp, vp, kb, vb, ext.o, ext.m, ext.lse, out, lse, T.workspace(shape))
+    torch.cuda.synchronize()
+    ora_ext = orc.partial(Q, Kp, Vp)
+    T.check_partial(ext.numpy(), ora_ext, "bf16", "small refresh_step ext")
+    ora_out, ora_lse = orc.merge(ora_ext, orc.partial(Q, Kb, Vb))
+    T.assert_close(out.double().cpu().numpy(), ora_out, "bf16", "small refresh_step out")
+    T.assert_close(lse.double().cpu().numpy(), ora_lse, "bf16", "small refresh_step lse", lse=True)
+    # per-head refresh with a later query
+    Q2 = steps[1][0]
+    hm = torch.zeros((w.batch, w.n_q_heads), device=T.DEV, dtype=torch.uint8)
+    hm[:, [0, 5]] = 1
+    ns = max(fb.fb_external_heads_splits(shape, 2), 1)
+    fb.fb_external_partial_heads(shape, T.to_dev(Q2, "bf16"), kp, vp, hm, ext.o, ext.m, ext.lse,
+                                 T.workspace(shape, n_splits=ns), 2)
+    torch.cuda.synchronize()
+    new = orc.partial(Q2, Kp, Vp)
+    got = ext.numpy()
+    for hd in range(w.n_q_heads):
+        ref = new if hd in (0, 5) else ora_ext
+        T.check_partial({k: v[:, hd:hd + 1] for k, v in got.items()}, {k: v[:, hd:hd + 1] for k, v in ref.items()},
+                        "bf16", f"small heads refresh head {hd}")
+    # sparse refresh and reuse with the oracle's selection
+    idx = orc.select_topk(steps[0][0], Kp, w.key_block, w.topk)
+    gpu = T.run_sparse_block_gpu(w, Kp, Vp, steps, idx_per_refresh={0: idx})
+    kmask = orc.selection_key_mask(idx, w.prefix_len, w.key_block)
+    res = orc.partial(steps[0][0], Kp, Vp, key_mask=~kmask)
+    T.check_partial(gpu[0]["residual"], res, "bf16", "small sparse residual")
+    for t, (Qt, Kbt, Vbt) in enumerate(steps):
+        e = orc.merge_partials(orc.partial(Qt, Kp, Vp, key_mask=kmask), res)
+        T.check_partial(gpu[t]["ext"], e, "bf16", f"small sparse step {t} sel(+)res")
+        o_, _ = orc.merge(e, orc.partial(Qt, Kbt, Vbt))
+        T.assert_close(gpu[t]["out"], o_, "bf16", f"small sparse step {t} out")

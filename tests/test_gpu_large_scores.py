@@ -147,3 +147,11 @@ def test_paged_large_scores():
     for b, (Kb_, Vb_) in enumerate(seqs):
         ora = orc.partial(Q[b:b + 1], Kb_[None], Vb_[None], scale)
         T.check_partial({k: v[b:b + 1] for k, v in got.items()}, ora, "bf16", f"paged seq {b}")
+
+
+@pytest.mark.parametrize("Bq", [4, 8, 16])
+@pytest.mark.parametrize("d,n_splits", [(128, 1), (128, 4), (64, 2)])
+def test_streaming_kernel_small_blocks(Bq, d, n_splits):
+    """16, 32 and 64 rows per KV group with 65+ tiles: the streaming kernel with one or two 32-row groups per
+    workgroup (the 4- and 8-token blocks of the language-model experiments), large scores and planted keys."""
+    _dense(_w(8, 2, d, 4096 + 37, Bq), 16, 1.0, n_splits)
