@@ -70,7 +70,7 @@ struct SCfg {
   static constexpr int NKB = (LAYOUT == kKeySplit) ? 1 : 2;    // 32-key blocks of a tile one wavefront computes
   static constexpr int QPARTS = (ROWS + 63) / 64;             // the query rows are loaded 64 at a time, like a K operand
   static constexpr int QSTAGES = (QPARTS * OPB + STAGE - 1) / STAGE;   // ring stages they pass through at start
-  static constexpr int MERGE = (LAYOUT == kKeySplit) ? NSETS * NRG * (NDB * 16 + 2) * 64 * 4 : 0;   // key-half hand-over
+  static constexpr int MERGE = (LAYOUT == kKeySplit) ? NSETS * NRG * 2 * (NDB / 2 * 16 + 2) * 64 * 4 : 0;   // key-half exchange
   static constexpr int RING = NS * STAGE;
   static constexpr int FIFO = RING > MERGE ? RING : MERGE;
   static constexpr int LDS = FIFO;
@@ -638,37 +638,52 @@ __global__ __launch_bounds__(((LAYOUT == kRowPair) ? 8 : 2 * NRG) * 64, 1) void 
     }
   }
 
+  // Output column blocks this wavefront finishes and stores.  Row-pair layout: all of them.  Key-split layout: the two
+  // wavefronts of a row group exchange halves, so that both take part in the merge and in the stores (the wavefront of
+  // key half 0 keeps the lower column blocks, the other one the upper ones).
+  constexpr int NDBK = (LAYOUT == kKeySplit) ? C::NDB / 2 : C::NDB;
+  const int db_keep = (LAYOUT == kKeySplit) ? kb0 * NDBK : 0;
   if constexpr (LAYOUT == kKeySplit) {
-    // ---- merge the two key halves through LDS: wavefronts 4..7 hand their statistics to wavefronts 0..3
-    constexpr int REC = C::NDB * 16 + 2;
+    // ---- merge the two key halves through LDS.  Record per (set, row group, key half): the NDBK column blocks the
+    // wavefront gives away, then its m and l; [register][lane] so that neighbouring lanes hit neighbouring banks.
+    constexpr int REC = NDBK * 16 + 2;
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < NSETS; ++i) {
-      float* mbuf = (float*)ring + ((size_t)i * NRG + rg) * REC * 64 + lane;
-      if (kb0 == 1) {
+      float* mine = (float*)ring + (((size_t)i * NRG + rg) * 2 + kb0) * REC * 64 + lane;
 #pragma unroll
-        for (int db = 0; db < C::NDB; ++db)
+      for (int db = 0; db < NDBK; ++db)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) mbuf[(db * 16 + r) * 64] = accs[i].o[db][r];
-        mbuf[(C::NDB * 16) * 64] = accs[i].m;
-        mbuf[(C::NDB * 16 + 1) * 64] = accs[i].l;
-      }
+        for (int r = 0; r < 16; ++r) {
+          // static register indices: select between the two halves instead of indexing by kb0
+          mine[(db * 16 + r) * 64] = kb0 ? accs[i].o[db][r] : accs[i].o[NDBK + db][r];
+        }
+      mine[(NDBK * 16) * 64] = accs[i].m;
+      mine[(NDBK * 16 + 1) * 64] = accs[i].l;
     }
     __syncthreads();
-    if (kb0 == 1) return;
 #pragma unroll
     for (int i = 0; i < NSETS; ++i) {
-      const float* mbuf = (const float*)ring + ((size_t)i * NRG + rg) * REC * 64 + lane;
+      const float* other = (const float*)ring + (((size_t)i * NRG + rg) * 2 + (kb0 ^ 1)) * REC * 64 + lane;
       WaveAcc<C::NDB>& a = accs[i];
-      const float m1 = mbuf[(C::NDB * 16) * 64], l1 = mbuf[(C::NDB * 16 + 1) * 64];
-      const float M = fmaxf(a.m, m1);
+      const float mo = other[(NDBK * 16) * 64], lo = other[(NDBK * 16 + 1) * 64];
+      // both wavefronts of the pair evaluate the same expressions on (key half 0, key half 1) in that order
+      const float m0 = kb0 ? mo : a.m, m1 = kb0 ? a.m : mo;
+      const float l0 = kb0 ? lo : a.l, l1 = kb0 ? a.l : lo;
+      const float M = fmaxf(m0, m1);
       const float Mu = (M == -INFINITY) ? 0.f : M;
-      const float w0 = __builtin_amdgcn_exp2f(a.m - Mu), w1 = __builtin_amdgcn_exp2f(m1 - Mu);
+      const float w0 = __builtin_amdgcn_exp2f(m0 - Mu), w1 = __builtin_amdgcn_exp2f(m1 - Mu);
+      const float ws = kb0 ? w1 : w0, wo = kb0 ? w0 : w1;
 #pragma unroll
-      for (int db = 0; db < C::NDB; ++db)
+      for (int db = 0; db < NDBK; ++db)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) a.o[db][r] = a.o[db][r] * w0 + mbuf[(db * 16 + r) * 64] * w1;
-      a.l = a.l * w0 + l1 * w1;
+        for (int r = 0; r < 16; ++r) {
+          const float x = other[(db * 16 + r) * 64];
+          // kept block = lower ones for key half 0, upper ones for key half 1; result parked in o[db]
+          const float own = kb0 ? a.o[NDBK + db][r] : a.o[db][r];
+          a.o[db][r] = kb0 ? (x * wo + own * ws) : (own * ws + x * wo);
+        }
+      a.l = l0 * w0 + l1 * w1;
       a.m = M;
     }
   }
@@ -694,10 +709,10 @@ __global__ __launch_bounds__(((LAYOUT == kRowPair) ? 8 : 2 * NRG) * 64, 1) void 
     const float inv = den > 0.f ? 1.f / den : 0.f;
     __bf16* out = (__bf16*)p.out + grow * D;
 #pragma unroll
-    for (int db = 0; db < C::NDB; ++db)
+    for (int db = 0; db < NDBK; ++db)
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
-        const int d0 = 32 * db + 8 * q4 + 4 * h;
+        const int d0 = 32 * (db_keep + db) + 8 * q4 + 4 * h;
         f32x4 e = {0.f, 0.f, 0.f, 0.f};
         if (has_ext) e = *(const f32x4*)(p.ext_o + grow * D + d0);
         float r[4];
@@ -722,15 +737,15 @@ __global__ __launch_bounds__(((LAYOUT == kRowPair) ? 8 : 2 * NRG) * 64, 1) void 
         L = (acc.m + log2f(l_row)) * kLn2;
       }
 #pragma unroll
-      for (int db = 0; db < C::NDB; ++db)
+      for (int db = 0; db < NDBK; ++db)
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
-          const int d0 = 32 * db + 8 * q4 + 4 * h;
+          const int d0 = 32 * (db_keep + db) + 8 * q4 + 4 * h;
           f32x4 o4 = {acc.o[db][4 * q4] * adj, acc.o[db][4 * q4 + 1] * adj, acc.o[db][4 * q4 + 2] * adj,
                       acc.o[db][4 * q4 + 3] * adj};
           *(f32x4*)(p.ws_o + grow * D + d0) = o4;
         }
-      if (h == 0) {
+      if (h == 0 && kb0 == 0) {
         p.ws_m[grow] = m_nat;
         p.ws_l[grow] = L;
       }
@@ -747,16 +762,16 @@ __global__ __launch_bounds__(((LAYOUT == kRowPair) ? 8 : 2 * NRG) * 64, 1) void 
       const WaveAcc<C::NDB>& a = accs[i];
       const float l_i = (i == 0) ? l_row : a.l + __shfl_xor(a.l, 32, 64);
 #pragma unroll
-      for (int db = 0; db < C::NDB; ++db)
+      for (int db = 0; db < NDBK; ++db)
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
-          const int d0 = 32 * db + 8 * q4 + 4 * h;
+          const int d0 = 32 * (db_keep + db) + 8 * q4 + 4 * h;
           f32x4 o4 = {a.o[db][4 * q4], a.o[db][4 * q4 + 1], a.o[db][4 * q4 + 2], a.o[db][4 * q4 + 3]};
           // streaming store: read next by another kernel, never again by this one (measured: faster than staging
           // the rows through LDS for whole-row stores, and faster than write-back stores)
           __builtin_nontemporal_store(o4, (f32x4*)(w_o + wrow * D + d0));
         }
-      if (h == 0) {
+      if (h == 0 && kb0 == 0) {
         w_m[wrow] = a.m;
         w_l[wrow] = l_i;
       }
