@@ -228,6 +228,9 @@ def profile_external(dev, n_blocks, R, batch=8):
     left = n_blocks
     while left > 0:
         nb = min(batch, left)
+        for t in range(S):                       # one untimed block first: the queue was drained by the synchronisation
+            dev.step(t, blk % dev.nsets, R)
+        blk += 1
         for i in range(nb):
             for t in range(S):
                 dev.step(t, blk % dev.nsets, R, prof=pool[i] if t == 0 else None)
