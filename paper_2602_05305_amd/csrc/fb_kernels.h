@@ -133,6 +133,7 @@ struct PassParams {
   int xcd_bias;
   FastDiv div_rowtiles, div_nsplit, div_hkv;   // bf16 pass: decomposition of the linear workgroup index
   FastDiv div_page;                            // bf16 paged pass: key index -> page slot
+  FastDiv div_tpb;                             // streaming sparse passes: tile index -> key block (tiles per key block)
 };
 
 // Fold split partials (and optionally a cached residual) into final (o, m, lse) partials.

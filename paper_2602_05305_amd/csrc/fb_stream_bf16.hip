@@ -407,10 +407,11 @@ __global__ __launch_bounds__(((LAYOUT == kRowPair) ? 8 : 2 * NRG) * 64, 1) void 
     r.word = 0;
     r.mask = 0xffffffffu;
     if constexpr (MODE == kPassSparseReuse) {
-      r.word = sload(ulist, r.e / tpb);
-      r.mask = (uint32_t)sload(umask, r.e / tpb);
+      const int blk_i = (int)fastdiv((uint32_t)r.e, p.div_tpb);     // entry of the union list
+      r.word = sload(ulist, blk_i);
+      r.mask = (uint32_t)sload(umask, blk_i);
     } else if constexpr (MODE == kPassSparseRefresh) {
-      r.mask = (uint32_t)sload(bmask, (int)((uint32_t)(r.e * C::KT) / (uint32_t)p.key_block));
+      r.mask = (uint32_t)sload(bmask, (int)fastdiv((uint32_t)r.e, p.div_tpb));
     } else if constexpr (MODE == kPassDensePaged) {
       r.word = sload(p.block_table + (size_t)b * p.max_pages, (int)fastdiv((uint32_t)(r.e * C::KT), p.div_page));
     }
@@ -419,7 +420,9 @@ __global__ __launch_bounds__(((LAYOUT == kRowPair) ? 8 : 2 * NRG) * 64, 1) void 
   auto tile_desc = [&](const TileRaw& r) -> TileDesc {
     TileDesc d;
     d.mask = r.mask;
-    d.k0 = (MODE == kPassSparseReuse) ? r.word * p.key_block + C::KT * (r.e % tpb) : r.e * C::KT;
+    d.k0 = (MODE == kPassSparseReuse)
+               ? r.word * p.key_block + C::KT * (r.e - (int)(fastdiv((uint32_t)r.e, p.div_tpb) * p.div_tpb.d))
+               : r.e * C::KT;
     if constexpr (MODE == kPassDensePaged) {
       const uint32_t slot = fastdiv((uint32_t)d.k0, p.div_page);
       const int page = min(max(r.word, 0), p.num_pages - 1);       // clamped into the pool
@@ -793,6 +796,7 @@ hipError_t launch_stream(const PassParams& p, hipStream_t s) {
   if (nwg >= (1ll << 31)) return hipErrorInvalidValue;
   PassParams q = p;
   if (MODE == kPassDensePaged) q.div_page = make_fastdiv((uint32_t)p.page_size);
+  q.div_tpb = make_fastdiv((uint32_t)(p.key_block > 0 ? p.key_block / kKeyTile : 1));
   {
     // long streams only: below 64 tiles per split a 1/64 bias rounds away
     const int tiles = (p.nkeys + kKeyTile - 1) / kKeyTile;
