@@ -7,10 +7,12 @@
 // against a stream of keys and either stores split partials / the final partial (external passes) or finishes
 // with the log-space composition of Eq. 8-9 against a cached partial (internal pass).
 //
-// Work decomposition: workgroup = 8 wavefronts, one tile stream of 64-key tiles, NS ring stages.
-//   kKeySplit  128 group-flattened rows; wavefront w owns rows [32 (w%4), +32) and the key half w/4 of every
-//              tile; the two halves' statistics are merged through LDS after the last tile.  (LLM-shaped
-//              blocks: the whole KV group is one workgroup, every K/V byte is fetched once.)
+// Work decomposition: one workgroup streams one list of 64-key tiles through NS ring stages.
+//   kKeySplit  NRG = 4, 2 or 1 groups of 32 group-flattened rows (8, 4 or 2 wavefronts); wavefront w owns row group
+//              w % NRG and the key half w / NRG of every tile; the two halves exchange accumulator halves through LDS
+//              after the last tile and each finishes and stores half of the output columns.  (LLM-shaped blocks:
+//              the whole KV group is one workgroup, every K/V byte is fetched once; NRG = 2 / 1 for KV groups of
+//              at most 64 / 32 rows, the 4- and 8-token blocks, where more row groups would compute padding.)
 //              Sparse refresh pass: the same layout with two accumulator sets per wavefront (selected /
 //              residual key blocks); a tile's scores are computed once and go to the set the row's head routes
 //              the tile's key block to, so the eight wavefronts stay evenly loaded whatever the selection.
