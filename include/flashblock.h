@@ -57,7 +57,7 @@
 extern "C" {
 #endif
 
-#define FB_VERSION 100
+#define FB_VERSION 110
 
 typedef enum fb_status {
   FB_OK = 0,

@@ -27,7 +27,7 @@ def test_library_exports_every_declared_symbol():
     for n in names:
         assert hasattr(lib, n), n
     assert set(names) == set(fb.exported_symbols())
-    assert fb.fb_version() == 100
+    assert fb.fb_version() == 110
     for n in names:   # the binding offers the same names
         assert hasattr(fb, n) or n in ("fb_status_string", "fb_last_hip_error"), n
 
