@@ -298,7 +298,7 @@ def test_header_is_plain_c_and_links(tmp_path):
     out = subprocess.run([str(exe)], capture_output=True, text=True, timeout=60)
     assert out.returncode == 0, out.stderr
     ver, ok, splits, ws = out.stdout.split()
-    assert int(ver) == 100 and int(ok) == fb.FB_OK and int(splits) >= 1 and int(ws) >= 256
+    assert int(ver) == 110 and int(ok) == fb.FB_OK and int(splits) >= 1 and int(ws) >= 256
 
 
 def test_builtin_workspace_entry_rejects_on_the_host():
