@@ -148,7 +148,8 @@ fb_status fb_external_partial_ex(const fb_shape* shape, const void* q, const voi
  * LLM-shaped configuration up to 128K context fits; batch 4 at 128K and the video shape do not).
  * All calls on one GPU share the one array: calls that may overlap in time (different streams, or
  * different threads) race on it and must be ordered by the caller; nothing in it has to be cleared
- * between calls.  More than 16 GPUs per process: FB_ERR_UNSUPPORTED.
+ * between calls.  More than 16 GPUs per process: FB_ERR_UNSUPPORTED.  The first call on a device looks up
+ * the array's device address (hipGetSymbolAddress): make it outside graph capture.
  */
 size_t fb_builtin_workspace_bytes(void);
 fb_status fb_external_partial_builtin_ws(const fb_shape* shape, const void* q, const void* k_prefix,
