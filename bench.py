@@ -321,7 +321,7 @@ class Calib:
         lib.fbc_read_vgpr.argtypes = [vp, ctypes.c_size_t, ctypes.c_int, vp, vp]
         lib.fbc_read_lds.argtypes = [vp, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, vp, vp]
         lib.fbc_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
-        lib.fbc_mfma.argtypes = [ctypes.c_int, ctypes.c_int, vp, vp]
+        lib.fbc_mfma.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp]
         self.lib = lib
 
 
@@ -353,12 +353,16 @@ def measure_ceilings(torch, reps=30):
     flops = wgs * 4 * iters * 4 * 32768.0
 
     def mfma():
-        check(lib.fbc_mfma(iters, wgs, sink.data_ptr(), st))
+        check(lib.fbc_mfma(iters, wgs, 1, sink.data_ptr(), st))
+
+    def mfma_const():
+        check(lib.fbc_mfma(iters, wgs, 0, sink.data_ptr(), st))
 
     t_v, t_vmin = _ev_median_us(torch, read_vgpr, reps, 3, warm_s=0.1)
     t_l, t_lmin = _ev_median_us(torch, read_lds, reps, 3, warm_s=0.1)
     t_c, _ = _ev_median_us(torch, copy, reps, 3, warm_s=0.05)
     t_m, t_mmin = _ev_median_us(torch, mfma, 10, 2, warm_s=0.05)
+    t_mc, _ = _ev_median_us(torch, mfma_const, 10, 2, warm_s=0.05)
     del bufs
     torch.cuda.empty_cache()
     best, kern = (t_v, "fbc_read_vgpr (16-byte loads into registers, 512 workgroups)") if t_v <= t_l else \
@@ -368,6 +372,9 @@ def measure_ceilings(torch, reps=30):
             "read_lds_ring_us": round(t_l, 1), "read_lds_ring_min_us": round(t_lmin, 1),
             "copy_GBps_read_plus_write": round(2 * nbytes / t_c / 1e3, 1),
             "mfma_bf16_TFLOPs": round(flops / t_m / 1e6, 1), "mfma_us": round(t_m, 1),
+            "mfma_bf16_TFLOPs_constant_operands": round(flops / t_mc / 1e6, 1),
+            "mfma_note": "back-to-back v_mfma_f32_32x32x16_bf16, no memory traffic; operands changing from MFMA to MFMA (pseudo-random "
+                         "bf16, what a real contraction presents: the part lowers its clock under that load) / one constant pair",
             "note": "medians of event-timed launches in this process; source paper_2602_05305_amd/csrc/fb_calib.hip"}
 
 
@@ -464,7 +471,7 @@ def _ev_median_us(torch, fn, reps=30, warm=3, warm_s=0.05):
     return ts[len(ts) // 2] * 1e3, ts[0] * 1e3
 
 
-def video_extra(torch, fb, wl):
+def video_extra(torch, fb, wl, ceilings=None):
     """Video-shaped workload: both passes are dense contractions, priced against bf16 MFMA peak."""
     w = wl.CONFIGS["video"]
     d = DeviceBlock(w, 1)
@@ -494,6 +501,10 @@ def video_extra(torch, fb, wl):
             "internal_tflops": round(f_int / t_int / 1e6, 1),
             "internal_frac": round(f_int / t_int / 1e6 / peak, 4),
             "block_speedup_cached_vs_full": round(S * (t_ext + t_int) / (-(-S // R) * t_ext + S * t_int), 3),
+            **({"measured_peak": ceilings["mfma_bf16_TFLOPs"],
+                "external_frac_of_measured": round(f_ext / t_ext / 1e6 / ceilings["mfma_bf16_TFLOPs"], 4),
+                "internal_frac_of_measured": round(f_int / t_int / 1e6 / ceilings["mfma_bf16_TFLOPs"], 4),
+                "measured_peak_kernel": "fbc_mfma with changing operands (MFMA-only loop, this process)"} if ceilings else {}),
             "timing": "median (and min) of 30 event-timed calls after 50 ms of the same call"}
 
 
@@ -1059,7 +1070,7 @@ def main():
         torch.cuda.empty_cache()
 
     if not args.no_extras:
-        line["video_mfma"] = video_extra(torch, fb, wl)
+        line["video_mfma"] = video_extra(torch, fb, wl, ceilings)
         torch.cuda.empty_cache()
         line["sparse_64k"] = sparse_extra(torch, fb, wl)
         torch.cuda.empty_cache()

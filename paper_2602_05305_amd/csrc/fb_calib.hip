@@ -6,7 +6,8 @@
 //   fbc_read_lds    the same stream through direct-to-LDS loads into a ring of stages (the data path of the
 //                   streaming attention pass, with the arithmetic taken out)
 //   fbc_copy        plain device copy of a known size (scale factor of the profiler's HBM byte counters)
-//   fbc_mfma        back-to-back v_mfma_f32_32x32x16_bf16 on independent accumulators, no memory traffic
+//   fbc_mfma        back-to-back v_mfma_f32_32x32x16_bf16 on independent accumulators, no memory traffic; with operands
+//                   that change from MFMA to MFMA (what a real contraction presents) or with one constant pair
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -80,22 +81,37 @@ __global__ __launch_bounds__(256) void copy_kernel(const u32x4* __restrict__ src
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) dst[i] = ((gptr128)src)[i];
 }
 
-// Each wavefront: iters x 4 MFMAs on four independent accumulators (no dependency between neighbours).
+// Each wavefront: iters x 4 MFMAs on four independent accumulators (no dependency between neighbours).  The operands
+// rotate through four register sets of pseudo-random bf16 values per lane, so that the multipliers see changing bits as
+// they do on real data (with one constant operand pair the part draws less power and holds a higher clock than any real
+// contraction does).
+template <bool VARY>
 __global__ __launch_bounds__(256) void mfma_kernel(int iters, float* __restrict__ sink) {
-  bf16x8 a, b;
+  bf16x8 a[4], b[4];
+  uint32_t h = (uint32_t)(blockIdx.x * 256 + threadIdx.x) * 2654435761u + 12345u;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    a[i] = (__bf16)(float)((threadIdx.x + i) & 3);
-    b[i] = (__bf16)(float)((threadIdx.x * 3 + i) & 1);
-  }
+  for (int k = 0; k < 4; ++k)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      h = h * 1664525u + 1013904223u;
+      a[k][i] = (__bf16)(((float)(h >> 8) * (1.0f / 16777216.0f) - 0.5f) * 0.25f);
+      h = h * 1664525u + 1013904223u;
+      b[k][i] = (__bf16)(((float)(h >> 8) * (1.0f / 16777216.0f) - 0.5f) * 0.25f);
+      if (!VARY) {                       // one constant operand pair for every MFMA: the best case for the clock
+        a[k][i] = (__bf16)(float)((threadIdx.x + i) & 3);
+        b[k][i] = (__bf16)(float)((threadIdx.x * 3 + i) & 1);
+      }
+    }
   f32x16 c[4];
 #pragma unroll
   for (int k = 0; k < 4; ++k)
 #pragma unroll
     for (int r = 0; r < 16; ++r) c[k][r] = 0.f;
-  for (int it = 0; it < iters; ++it) {
+  for (int it = 0; it < iters; it += 4) {
 #pragma unroll
-    for (int k = 0; k < 4; ++k) c[k] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c[k], 0, 0, 0);
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int k = 0; k < 4; ++k) c[k] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[(k + u) & 3], b[u], c[k], 0, 0, 0);
   }
   float s = 0.f;
 #pragma unroll
@@ -145,10 +161,11 @@ int fbc_copy(void* dst, const void* src, size_t bytes, void* stream) {
   return (int)hipGetLastError();
 }
 
-// flops per launch = wgs * 4 wavefronts * iters * 4 MFMAs * 32768
-int fbc_mfma(int iters, int wgs, void* sink, void* stream) {
-  if (wgs <= 0 || iters <= 0) return (int)hipErrorInvalidValue;
-  hipLaunchKernelGGL(mfma_kernel, dim3(wgs), dim3(256), 0, (hipStream_t)stream, iters, (float*)sink);
+// flops per launch = wgs * 4 wavefronts * iters * 4 MFMAs * 32768 (iters a multiple of 4)
+int fbc_mfma(int iters, int wgs, int vary, void* sink, void* stream) {
+  if (wgs <= 0 || iters <= 0 || iters % 4 != 0) return (int)hipErrorInvalidValue;
+  if (vary) hipLaunchKernelGGL(mfma_kernel<true>, dim3(wgs), dim3(256), 0, (hipStream_t)stream, iters, (float*)sink);
+  else hipLaunchKernelGGL(mfma_kernel<false>, dim3(wgs), dim3(256), 0, (hipStream_t)stream, iters, (float*)sink);
   return (int)hipGetLastError();
 }
 
