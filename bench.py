@@ -332,7 +332,8 @@ def measure_ceilings(torch, reps=30):
     lib = Calib().lib
     st = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
     nbytes = 512 * 1024 * 1024
-    bufs = [torch.full((nbytes,), 3, dtype=torch.uint8, device="cuda") for _ in range(3)]
+    # random bytes: what the bus carries when real K/V stream through it (constant data would toggle fewer lines)
+    bufs = [torch.randint(0, 256, (nbytes,), dtype=torch.uint8, device="cuda") for _ in range(3)]
     sink = torch.zeros(64, dtype=torch.int32, device="cuda")
     i = [0]
 
