@@ -29,6 +29,18 @@ def test_bench_prints_one_json_line_with_the_contract_fields():
     assert rf["bound"] == "hbm" and rf["unit"] == "GB/s" and rf["peak"] == 8000.0
     assert abs(rf["frac"] - rf["achieved"] / rf["peak"]) < 1e-3
     assert 0.05 < rf["frac"] < 1.0 and 1.0 < d["value"] < 1000.0
+    # the ceiling measured in the same process, the label's single source of truth, and the traffic's provenance
+    assert 4000.0 < rf["measured_peak"] < 8000.0 and abs(rf["frac_of_measured"] - rf["achieved"] / rf["measured_peak"]) < 1e-3
+    assert rf["kernel"].startswith("fb::attn_stream_kernel<128, 0, 0, 4>")
+    assert rf["traffic"] is None or "not measured in this run" in rf["traffic_source"]
+    assert rf["launches_timed"] >= 30 and rf["min_launch_us"] <= rf["median_launch_us"]
+    cal = d["calibration"]
+    assert cal["mfma_bf16_TFLOPs"] < cal["mfma_bf16_TFLOPs_constant_operands"] <= 2600.0
+    assert d["timing"]["repeats"] >= 5
+    # parity of this very run against the oracle, inside the stated tolerances by a wide margin
+    par = d["parity"]
+    assert par["tiny_f32"]["max_abs_err_out"] < 1e-5 and par["tiny_f32"]["max_abs_err_L_ext"] < 1e-5
+    assert par["llm_32k"]["max_abs_err_out"] < 1e-3 and par["llm_32k"]["max_abs_err_L_ext"] < 1e-3
 
 
 def test_gamma_calibration_report():
